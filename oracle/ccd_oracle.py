@@ -1,0 +1,188 @@
+"""CPU oracle for the Continual Context Distillation (CCD) compression step.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition that the
+HIP path is checked against.  Nothing in the product path may import it; only
+the tests, the smoke check and the benchmark's CPU-baseline leg do.  It shares
+no code with the HIP kernels or their Python binding and imports neither.
+
+Every floating-point step runs in fp64 on the exact values of the (fp32 or
+bf16) inputs.  The only narrowing is the final score, which is cast to fp32
+because the selection is defined on fp32 scores (the precision the library's
+`scores` array has).
+
+Notation follows the paper: a pot holds n cached context tokens per (layer,
+KV head); |P| catalyst-prompt (CaP) query tokens attend to them; |C| = k
+entries survive, T of which are reserved for the tokens with the highest
+Novelty-under-Compression (NuC) score.
+
+Steps, per unit (sequence b, layer l, KV head h), in the paper's order:
+
+  nuc_slots     Sec. 3.3.3, first step: the T tokens with the largest novelty.
+  cap_scores    Eq. 2: representative score = sum over the CaP query tokens of
+                their attention probability on each context token (the Listing
+                in App. B sums the CaP rows of the attention map and keeps the
+                context columns only).  With grouped-query attention the G
+                query heads that share the KV head are summed as well.
+  pool          1-D pooling of the score along the token axis (not in the
+                paper; the paper's implementation follows a code base that
+                clusters scores this way, and the benchmark configs ask for a
+                window of 7).
+  combine       App. B "Combine NuC and CaP": NuC-selected tokens are lifted
+                above every CaP score so that they always survive (+inf here).
+  select        Sec. 3.3.3, second step / App. B "Final Token Selection":
+                top-k per head; ties go to the lower index; the kept indices
+                are emitted in ascending (temporal) order.
+  compact       App. B: K' = K[keep], V' = V[keep] (bit copies).
+
+Parity status of the choices the paper does not fix (pool mode, the GQA
+reduction, softmax over context tokens only, +inf sentinel, per-head carried
+novelty): pinned by the benchmark's wording only - "parity unpinned" against
+the paper for those choices.  All arithmetic (softmax-sum, pooling, top-k,
+gather) is pinned by the tests in tests/test_oracle_pins.py.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
+FLT_MIN = float(np.finfo(np.float32).tiny)
+
+
+def to_f64(x: np.ndarray) -> np.ndarray:
+    """Exact fp64 value of an input array: float32, or bf16 bit patterns (uint16)."""
+    x = np.asarray(x)
+    if x.dtype == np.uint16:
+        return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    if x.dtype in (np.float32, np.float64):
+        return x.astype(np.float64)
+    raise TypeError(f"unsupported input dtype {x.dtype}")
+
+
+def nuc_slots(novelty: np.ndarray, T: int) -> np.ndarray:
+    """Sec. 3.3.3, step 1: indices of the T largest novelty scores (ascending).
+
+    Equal novelty goes to the lower index.  Tokens whose novelty is NaN or
+    -inf never take a slot, so fewer than T may be returned.
+    """
+    nov = np.asarray(novelty, dtype=np.float32)
+    n = nov.shape[0]
+    eligible = np.flatnonzero(~np.isnan(nov) & (nov > -np.inf))
+    if T <= 0 or eligible.size == 0:
+        return np.zeros(0, dtype=np.int64)
+    vals = nov[eligible].astype(np.float64)
+    order = np.lexsort((eligible, -vals))  # primary: novelty descending; then index ascending
+    take = eligible[order[: min(T, eligible.size)]]
+    assert take.size <= n
+    return np.sort(take)
+
+
+def cap_scores(Q: np.ndarray, K: np.ndarray, scale: float) -> np.ndarray:
+    """Eq. 2: u_t = sum over CaP queries of softmax_t(scale * <q, k_t>).
+
+    Q is [G*P, d] (all query rows that attend through this KV head), K is
+    [n, d]; both already fp64.  The softmax runs over the n context tokens.
+    """
+    S = scale * (Q @ K.T)                      # [G*P, n] attention logits
+    m = S.max(axis=1, keepdims=True)
+    E = np.exp(S - m)
+    Z = E.sum(axis=1, keepdims=True)
+    A = E / Z                                  # attention probabilities, rows sum to 1
+    return A.sum(axis=0)                       # sum over the CaP rows
+
+
+def pool(u: np.ndarray, w: int, mode: int) -> np.ndarray:
+    """Stride-1 pooling along the token axis with an odd window w, centred.
+
+    max: the window is clipped at both ends.  avg: zero padding, divide by w.
+    """
+    if mode == POOL_NONE or w <= 1:
+        return u.copy()
+    n = u.shape[0]
+    r = w // 2
+    out = np.empty_like(u)
+    for t in range(n):
+        lo, hi = max(0, t - r), min(n, t + r + 1)
+        if mode == POOL_MAX:
+            out[t] = u[lo:hi].max()
+        elif mode == POOL_AVG:
+            out[t] = u[lo:hi].sum() / w
+        else:
+            raise ValueError("pool mode")
+    return out
+
+
+def combine(ubar: np.ndarray, nuc: np.ndarray) -> np.ndarray:
+    """fp32 score: pooled CaP score, subnormals flushed to zero, +inf at NuC tokens."""
+    with np.errstate(under="ignore", over="ignore"):
+        s = ubar.astype(np.float32)
+    s[np.abs(s) < np.float32(FLT_MIN)] = np.float32(0.0)
+    s[nuc] = np.float32(np.inf)
+    return s
+
+
+def select(scores: np.ndarray, k: int) -> np.ndarray:
+    """Top-k of fp32 scores; equal scores -> lower index; result ascending.
+
+    NaN ranks with -inf.
+    """
+    s = np.asarray(scores, dtype=np.float32).astype(np.float64)
+    s = np.where(np.isnan(s), -np.inf, s)
+    idx = np.arange(s.shape[0])
+    order = np.lexsort((idx, -s))
+    return np.sort(order[:k]).astype(np.int32)
+
+
+def compact(X: np.ndarray, keep: np.ndarray) -> np.ndarray:
+    """Rows of X at the kept indices, in that order (a copy of the stored bits)."""
+    return X[np.asarray(keep, dtype=np.int64)].copy()
+
+
+def score_unit(Q, K, novelty, *, T, scale, pool_w, pool_mode):
+    """Final fp32 scores of one unit. Q [G*P, d], K [n, d] raw inputs; novelty [n] fp32."""
+    u = cap_scores(to_f64(Q), to_f64(K), scale)
+    ubar = pool(u, pool_w, pool_mode)
+    return combine(ubar, nuc_slots(novelty, T))
+
+
+def default_scale(d: int) -> float:
+    return 1.0 / math.sqrt(d)
+
+
+def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=None,
+             n_valid=None, units=None):
+    """One CCD compression over a whole cache.
+
+    Q_cat [B, L, Hq, P, d]; K, V [B, L, Hkv, n_cap, d]; novelty [B, n] (shared by
+    all layers and heads) or [B, L, Hkv, n_cap] (carried per head).  Returns a dict
+    with scores [B, L, Hkv, n] fp32, keep_idx [B, L, Hkv, k] int32, K', V'
+    [B, L, Hkv, k, d] and, for per-head novelty, novelty' [B, L, Hkv, k].
+    `units` optionally restricts the work to a list of (b, l, h) triples; the
+    other entries of the outputs stay zero.
+    """
+    B, L, Hq, P, d = Q_cat.shape
+    Hkv, n_cap = K.shape[2], K.shape[3]
+    G = Hq // Hkv
+    assert Hq == G * Hkv
+    n = n_cap if n_valid is None else n_valid
+    scale = default_scale(d) if not scale else float(scale)
+    per_head = novelty.ndim == 4
+    scores = np.zeros((B, L, Hkv, n), dtype=np.float32)
+    keep_idx = np.zeros((B, L, Hkv, k), dtype=np.int32)
+    Kc = np.zeros((B, L, Hkv, k, d), dtype=K.dtype)
+    Vc = np.zeros((B, L, Hkv, k, d), dtype=V.dtype)
+    novc = np.zeros((B, L, Hkv, k), dtype=np.float32) if per_head else None
+    todo = units if units is not None else [(b, l, h) for b in range(B) for l in range(L) for h in range(Hkv)]
+    for (b, l, h) in todo:
+        Qu = Q_cat[b, l, h * G:(h + 1) * G].reshape(G * P, d)
+        nov = novelty[b, l, h, :n] if per_head else novelty[b, :n]
+        s = score_unit(Qu, K[b, l, h, :n], nov, T=T, scale=scale, pool_w=pool_w, pool_mode=pool_mode)
+        keep = select(s, k)
+        scores[b, l, h] = s
+        keep_idx[b, l, h] = keep
+        Kc[b, l, h] = compact(K[b, l, h], keep)
+        Vc[b, l, h] = compact(V[b, l, h], keep)
+        if per_head:
+            novc[b, l, h] = compact(novelty[b, l, h], keep)
+    return {"scores": scores, "keep_idx": keep_idx, "K": Kc, "V": Vc, "novelty": novc}
