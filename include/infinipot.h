@@ -1,0 +1,117 @@
+/*
+ * libinfinipot - the compression step of InfiniPot's Continual Context Distillation (CCD),
+ * hand-written HIP for AMD MI355X (gfx950).
+ *
+ * When the fixed-size KV "memory pot" is full (paper Sec. 3.2), every unit - one (sequence b,
+ * layer l, KV head h) triple - is compressed independently from n cached tokens to k = |C|:
+ *
+ *   score    representative score of Eq. 2: sum over the |P| catalyst-prompt (CaP) query tokens of
+ *            their attention probability on each cached token (App. B, "Calculate Attention Score"),
+ *            summed over the G = Hq/Hkv query heads that share the KV head; then 1-D pooling along
+ *            the token axis; then the T tokens with the largest Novelty-under-Compression score
+ *            (Eq. 3-4, passed in as `novelty`) are lifted to +inf (Sec. 3.3.3, App. B "Combine NuC
+ *            and CaP").
+ *   select   the k tokens with the largest score per unit (App. B "Final Token Selection"); equal
+ *            scores go to the lower token index; indices are emitted in ascending order so the
+ *            temporal order of the cache is preserved.
+ *   compact  K' = K[keep_idx], V' = V[keep_idx] (App. B, the two gathers) - bit copies.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers (HIP global memory) owned by the caller; the library
+ *     never allocates, frees or keeps them.  `shape` is a HOST pointer, read during the call only.
+ *   - `hip_stream` is a hipStream_t (NULL = the default stream).  Calls only enqueue kernels on that
+ *     stream and return; nothing is synchronised and nothing is copied to the host.
+ *   - Q_cat, K, V share `dtype` (fp32, or bf16 stored as 16-bit patterns).  The last dimension (d) is
+ *     contiguous and the token / query-token dimension has stride d; the outer three dimensions use
+ *     the strides in the shape (in elements).  Base pointers must be 16-byte aligned and the strides
+ *     multiples of 16 bytes.
+ *   - Return value: CCD_OK, CCD_NOOP (ccd_compress only) or a negative CCD_E* code.  All argument
+ *     checks happen on the host before anything is launched; on an error nothing is launched and no
+ *     buffer is touched.  Errors inside asynchronous kernels are not reported.
+ */
+#ifndef INFINIPOT_H
+#define INFINIPOT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CCD_API __attribute__((visibility("default")))
+
+enum {
+  CCD_OK = 0,
+  CCD_NOOP = 1,          /* pot not full (n_valid < n_cap) or nothing to drop (n_valid <= k): untouched */
+  CCD_EINVAL = -1,       /* NULL pointer, or a shape field out of range                                 */
+  CCD_EUNSUPPORTED = -2, /* d not in {64, 128}, unknown dtype or pool_mode                              */
+  CCD_EALIGN = -3,       /* pointer or stride not 16-byte aligned                                       */
+  CCD_EWORKSPACE = -4,   /* workspace NULL, misaligned or smaller than ccd_workspace_bytes()            */
+  CCD_ELAUNCH = -5       /* the HIP runtime refused a kernel launch                                    */
+};
+
+enum { CCD_FP32 = 0, CCD_BF16 = 1 };
+enum { CCD_POOL_NONE = 0, CCD_POOL_MAX = 1, CCD_POOL_AVG = 2 };
+
+typedef struct {
+  int32_t B, L, Hq, Hkv, d;   /* sequences, layers, query heads, KV heads (Hq % Hkv == 0), head dim      */
+  int32_t n_valid;            /* n: tokens now in the pot, scored and selected from                      */
+  int32_t n_cap;              /* capacity of the pot in tokens (paper: |M| - |P|); n_valid <= n_cap      */
+  int32_t k;                  /* |C|: tokens kept, 1 <= k <= n_valid                                     */
+  int32_t P;                  /* |P|: CaP query tokens per query head, >= 1                              */
+  int32_t T;                  /* NuC slots, 0 <= T <= k (paper: alpha * |C|)                             */
+  int32_t pool_w, pool_mode;  /* odd window >= 1; CCD_POOL_*.  max: window clipped at the ends;          */
+                              /* avg: zero padding, divide by pool_w.  Pooling precedes the NuC lift.    */
+  int32_t dtype;              /* CCD_FP32 or CCD_BF16, for Q_cat, K and V                                */
+  float scale;                /* logit scale; 0 means 1/sqrt(d)                                          */
+  int64_t kv_stride_b, kv_stride_l, kv_stride_h;    /* K, V: [B, L, Hkv, n_cap, d], strides in elements */
+  int64_t q_stride_b, q_stride_l, q_stride_h;       /* Q_cat: [B, L, Hq, P, d]                          */
+  int64_t nov_stride_b, nov_stride_l, nov_stride_h; /* novelty fp32: [B, n] shared by layers and heads  */
+                              /* when the l and h strides are both 0, else carried per head              */
+                              /* [B, L, Hkv, n_cap].                                                     */
+} ccd_shape_t;
+
+/* Bytes of scratch that ccd_score and ccd_compress need for this shape (0 if the shape is invalid).
+ * The workspace must be 256-byte aligned; its contents need not survive between calls. */
+CCD_API size_t ccd_workspace_bytes(const ccd_shape_t* shape);
+
+/* Steps a1-a5 (Eq. 2, pooling, Sec. 3.3.3 step 1): writes the final fp32 score of every token,
+ * scores[B, L, Hkv, n_valid] (dense).  NuC-selected tokens hold +inf; finite scores whose magnitude
+ * is below FLT_MIN are written as 0.  Tokens whose novelty is NaN or -inf never take a NuC slot. */
+CCD_API int ccd_score(const ccd_shape_t* shape, const void* Q_cat, const void* K, const float* novelty,
+              float* scores, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Step a6 (Sec. 3.3.3 step 2): keep_idx[B, L, Hkv, k] int32 = the k indices of largest score per unit,
+ * ascending.  Equal scores: lower index first; NaN ranks with -inf; -0 equals +0.  Only B, L, Hkv,
+ * n_valid and k of the shape are read. */
+CCD_API int ccd_select(const ccd_shape_t* shape, const float* scores, int32_t* keep_idx, void* hip_stream);
+
+/* Step a7 (App. B gathers): row j of K_dst/V_dst (same layout and strides as the sources) becomes row
+ * keep_idx[j] of K_src/V_src for j < k; rows >= k of the destination are left as they are.  K_dst may
+ * equal K_src and V_dst may equal V_src (in place; keep_idx must be strictly ascending per unit, as
+ * ccd_select produces); partially overlapping buffers are not allowed.  If `novelty_inout` is not NULL
+ * and the shape carries per-head novelty, its first k entries per unit are compacted the same way. */
+CCD_API int ccd_compact(const ccd_shape_t* shape, const void* K_src, const void* V_src, const int32_t* keep_idx,
+                void* K_dst, void* V_dst, float* novelty_inout, void* hip_stream);
+
+/* The fused step: score, select and compact K, V (and per-head novelty) in place.  Returns CCD_NOOP and
+ * launches nothing when the pot is not full (Sec. 3.2: distillation happens once the cache is full).
+ * keep_idx[B, L, Hkv, k] is always written; scores_opt[B, L, Hkv, n_valid] only if not NULL.  After
+ * CCD_OK the caller's pot holds k tokens per unit; rows >= k are stale. */
+CCD_API int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty,
+                 float* scores_opt, int32_t* keep_idx, void* workspace, size_t workspace_bytes,
+                 void* hip_stream);
+
+/* Process-wide choice of the kernels that compute the attention logits of Eq. 2: 0 = automatic (matrix
+ * cores for bf16, vector ALUs for fp32), 1 = vector ALUs, 2 = matrix cores where the dtype allows.  Meant
+ * for profiling one path against the other; returns CCD_EINVAL for any other value. */
+CCD_API int ccd_set_score_path(int path);
+
+/* Static, human-readable text for a return code. */
+CCD_API const char* ccd_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INFINIPOT_H */

@@ -1,0 +1,93 @@
+// Order-preserving gather-compaction of the cache rows (App. B: K' = K[keep_idx], V' = V[keep_idx]).
+//
+// In place, destination row j and source row keep_idx[j] live in the same buffer.  keep_idx is strictly
+// ascending, so keep_idx[j] >= j: a row only ever moves towards the front.  One workgroup walks the destination
+// rows of one (unit, tensor) in ascending chunks; inside a chunk every source row is first loaded into registers,
+// then the workgroup synchronises, then the rows are stored.  A store of chunk c lands in rows
+// [c*R, (c+1)*R), and every later chunk reads only rows >= (c+1)*R, so the only reads a store could overtake
+// are those of its own chunk, which the barrier orders.  Out of place the same code runs without the barrier.
+#include "ccd_common.h"
+
+namespace ccd {
+
+namespace {
+
+constexpr int kCpThreads = 1024;
+constexpr int kCpUnroll = 4;
+
+template <int ROWB>
+__global__ __launch_bounds__(kCpThreads) void compact_rows_kernel(Dims D, const char* Ksrc, const char* Vsrc,
+                                                                  const int32_t* __restrict__ keep_idx, char* Kdst,
+                                                                  char* Vdst) {
+  constexpr int kLanesPerRow = ROWB / 16;
+  constexpr int kRowsPerPass = kCpThreads / kLanesPerRow;
+  const int unit = blockIdx.x >> 1;
+  const bool isV = blockIdx.x & 1;
+  const int64_t ubytes = kv_offset(D, decode_unit(D, unit)) * (int64_t)(ROWB / D.d);
+  const char* src = (isV ? Vsrc : Ksrc) + ubytes;
+  char* dst = (isV ? Vdst : Kdst) + ubytes;
+  const bool inplace = (src == dst);
+  const int32_t* keep = keep_idx + (int64_t)unit * D.k;
+  const int lane_off = (threadIdx.x % kLanesPerRow) * 16;
+  const int row_in_pass = threadIdx.x / kLanesPerRow;
+
+  for (int base = 0; base < D.k; base += kRowsPerPass * kCpUnroll) {
+    uint4 v[kCpUnroll];
+    bool move[kCpUnroll];
+#pragma unroll
+    for (int i = 0; i < kCpUnroll; ++i) {
+      const int j = base + i * kRowsPerPass + row_in_pass;
+      move[i] = false;
+      if (j < D.k) {
+        int sidx = keep[j];
+        sidx = min(max(sidx, 0), D.n_cap - 1);   // a corrupt index must not leave the pot
+        move[i] = !(inplace && sidx == j);
+        if (move[i]) v[i] = *reinterpret_cast<const uint4*>(src + (int64_t)sidx * ROWB + lane_off);
+      }
+    }
+    if (inplace) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < kCpUnroll; ++i) {
+      const int j = base + i * kRowsPerPass + row_in_pass;
+      if (move[i]) *reinterpret_cast<uint4*>(dst + (int64_t)j * ROWB + lane_off) = v[i];
+    }
+  }
+}
+
+// per-head novelty carried with the cache: nov[j] <- nov[keep_idx[j]], same chunk discipline
+__global__ __launch_bounds__(kCpThreads) void compact_novelty_kernel(Dims D, const int32_t* __restrict__ keep_idx,
+                                                                     float* novelty) {
+  const int unit = blockIdx.x;
+  float* nov = novelty + nov_offset(D, decode_unit(D, unit));
+  const int32_t* keep = keep_idx + (int64_t)unit * D.k;
+  for (int base = 0; base < D.k; base += kCpThreads) {
+    const int j = base + threadIdx.x;
+    float v = 0.f;
+    if (j < D.k) v = nov[min(max(keep[j], 0), D.n_cap - 1)];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (j < D.k) nov[j] = v;
+  }
+}
+
+}  // namespace
+
+void launch_compact(const Dims& D, const void* Ksrc, const void* Vsrc, const int32_t* keep_idx, void* Kdst, void* Vdst,
+                    float* novelty, hipStream_t s) {
+  const int rowb = D.d * (D.dtype == 0 ? 4 : 2);
+  dim3 grid(2u * D.units), block(kCpThreads);
+#define CCD_LAUNCH(RB)                                                                                             \
+  hipLaunchKernelGGL((compact_rows_kernel<RB>), grid, block, 0, s, D, (const char*)Ksrc, (const char*)Vsrc, keep_idx, \
+                     (char*)Kdst, (char*)Vdst)
+  if (rowb == 128) CCD_LAUNCH(128);
+  else if (rowb == 256) CCD_LAUNCH(256);
+  else CCD_LAUNCH(512);
+#undef CCD_LAUNCH
+  if (novelty != nullptr)
+    hipLaunchKernelGGL(compact_novelty_kernel, dim3(D.units), block, 0, s, D, keep_idx, novelty);
+}
+
+}  // namespace ccd

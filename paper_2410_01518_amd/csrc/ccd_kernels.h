@@ -1,0 +1,49 @@
+// Internal launch interface between the C-ABI host code and the HIP kernels of libinfinipot.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ccd {
+
+// Device-side description of one call (a flattened copy of ccd_shape_t plus derived values).
+struct Dims {
+  int B, L, Hq, Hkv, G, d;
+  int n;        // tokens scored (n_valid)
+  int n_cap;
+  int k, P, T;
+  int GP;       // G * P query rows per unit
+  int pool_w, pool_mode;
+  int dtype;    // 0 fp32, 1 bf16
+  int units;    // B * L * Hkv
+  float scale_log2;  // logit scale times log2(e): probabilities are computed with exp2
+  int64_t kv_sb, kv_sl, kv_sh;
+  int64_t q_sb, q_sl, q_sh;
+  int64_t nov_sb, nov_sl, nov_sh;
+};
+
+struct ScorePlan {
+  int use_mfma;   // 1: bf16 matrix-core kernels, 0: vector-ALU kernels
+  int slice1;     // tokens per workgroup in the statistics pass
+  int n_slices1;
+  int slice2;     // tokens per workgroup in the probability pass
+  int n_slices2;
+};
+
+ScorePlan plan_score(const Dims& D);
+
+// pass 1: per (unit, slice, query) running maximum and sum of exp2 of the log2-domain logits
+void launch_stats_valu(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s);
+// merge the per-slice statistics into one log2-sum-exp per (unit, query)
+void launch_merge(const Dims& D, const ScorePlan& pl, const float2* part, float* lse2, hipStream_t s);
+// pass 2: u[unit, t] = sum over queries of exp2(logit2 - lse2)
+void launch_prob_valu(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float* lse2, float* u,
+                      hipStream_t s);
+
+// pooling + NuC lift -> scores (when `u` != null), top-k -> keep_idx (when `keep_idx` != null)
+void launch_finalize_select(const Dims& D, const float* u, const float* novelty, float* scores,
+                            int32_t* keep_idx, hipStream_t s);
+
+void launch_compact(const Dims& D, const void* Ksrc, const void* Vsrc, const int32_t* keep_idx,
+                    void* Kdst, void* Vdst, float* novelty, hipStream_t s);
+
+}  // namespace ccd

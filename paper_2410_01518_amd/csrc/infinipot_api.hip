@@ -1,0 +1,213 @@
+// Host side of libinfinipot: argument checks, workspace layout and kernel sequencing for the C ABI
+// declared in include/infinipot.h.  Everything here runs before any launch; the kernels live in the
+// ccd_*.hip files.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/infinipot.h"
+#include "ccd_kernels.h"
+
+namespace ccd {
+
+static int g_score_path = 0;   // 0 auto, 1 vector ALU, 2 MFMA (profiling comparisons)
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+enum Need { kNeedQ = 1, kNeedKV = 2, kNeedNov = 4, kNeedFull = 7 };
+
+// Checks the fields a call reads; returns CCD_OK or an error code.
+static int check_shape(const ccd_shape_t* s, int need) {
+  if (s == nullptr) return CCD_EINVAL;
+  if (s->B < 1 || s->L < 1 || s->Hkv < 1) return CCD_EINVAL;
+  if (s->n_valid < 1 || s->k < 1 || s->k > s->n_valid) return CCD_EINVAL;
+  if ((int64_t)s->B * s->L * s->Hkv > (int64_t)1 << 24) return CCD_EINVAL;
+  if (s->n_valid > (1 << 24)) return CCD_EINVAL;
+  if (need == 0) return CCD_OK;
+  if (s->n_cap < s->n_valid) return CCD_EINVAL;
+  if (s->dtype != CCD_FP32 && s->dtype != CCD_BF16) return CCD_EUNSUPPORTED;
+  if (s->d != 64 && s->d != 128) return CCD_EUNSUPPORTED;
+  const int64_t esz = s->dtype == CCD_FP32 ? 4 : 2;
+  if (need & kNeedKV) {
+    const int64_t row = (int64_t)s->n_cap * s->d;
+    if (s->kv_stride_h < row || s->kv_stride_l < 0 || s->kv_stride_b < 0) return CCD_EINVAL;
+    if ((s->kv_stride_b * esz) % 16 || (s->kv_stride_l * esz) % 16 || (s->kv_stride_h * esz) % 16) return CCD_EALIGN;
+  }
+  if (need & kNeedQ) {
+    if (s->Hq < 1 || s->Hq % s->Hkv != 0 || s->P < 1) return CCD_EINVAL;
+    if ((int64_t)(s->Hq / s->Hkv) * s->P > (1 << 20)) return CCD_EINVAL;
+    if (s->q_stride_h < (int64_t)s->P * s->d || s->q_stride_l < 0 || s->q_stride_b < 0) return CCD_EINVAL;
+    if ((s->q_stride_b * esz) % 16 || (s->q_stride_l * esz) % 16 || (s->q_stride_h * esz) % 16) return CCD_EALIGN;
+    if (!(s->scale >= 0.f) || isinf(s->scale)) return CCD_EINVAL;
+    if (s->pool_mode < CCD_POOL_NONE || s->pool_mode > CCD_POOL_AVG) return CCD_EUNSUPPORTED;
+    if (s->pool_w < 1 || s->pool_w % 2 == 0) return CCD_EINVAL;
+  }
+  if (need & kNeedNov) {
+    if (s->T < 0 || s->T > s->k) return CCD_EINVAL;
+    if (s->nov_stride_b < 0 || s->nov_stride_l < 0 || s->nov_stride_h < 0) return CCD_EINVAL;
+    const bool per_head = s->nov_stride_l != 0 || s->nov_stride_h != 0;
+    if (per_head && s->nov_stride_h < s->n_cap) return CCD_EINVAL;
+    if (!per_head && s->B > 1 && s->nov_stride_b < s->n_valid) return CCD_EINVAL;
+  }
+  return CCD_OK;
+}
+
+static Dims make_dims(const ccd_shape_t* s) {
+  Dims D{};
+  D.B = s->B; D.L = s->L; D.Hq = s->Hq; D.Hkv = s->Hkv; D.d = s->d;
+  D.G = (s->Hq > 0 && s->Hkv > 0) ? s->Hq / s->Hkv : 0;
+  D.n = s->n_valid; D.n_cap = s->n_cap; D.k = s->k; D.P = s->P; D.T = s->T;
+  D.GP = D.G * s->P;
+  D.pool_w = s->pool_w; D.pool_mode = s->pool_mode; D.dtype = s->dtype;
+  D.units = s->B * s->L * s->Hkv;
+  const double scale = s->scale > 0.f ? (double)s->scale : 1.0 / sqrt((double)(s->d > 0 ? s->d : 1));
+  D.scale_log2 = (float)(scale * 1.4426950408889634074);
+  D.kv_sb = s->kv_stride_b; D.kv_sl = s->kv_stride_l; D.kv_sh = s->kv_stride_h;
+  D.q_sb = s->q_stride_b; D.q_sl = s->q_stride_l; D.q_sh = s->q_stride_h;
+  D.nov_sb = s->nov_stride_b; D.nov_sl = s->nov_stride_l; D.nov_sh = s->nov_stride_h;
+  return D;
+}
+
+ScorePlan plan_score(const Dims& D) {
+  ScorePlan pl{};
+  pl.use_mfma = 0;
+  (void)g_score_path;
+  pl.slice1 = 256;
+  pl.n_slices1 = (D.n + pl.slice1 - 1) / pl.slice1;
+  pl.slice2 = 256;
+  pl.n_slices2 = (D.n + pl.slice2 - 1) / pl.slice2;
+  return pl;
+}
+
+struct Workspace {
+  size_t off_part, off_lse, off_u, off_scores, total;
+};
+
+static Workspace layout_workspace(const Dims& D, const ScorePlan& pl) {
+  Workspace w{};
+  size_t off = 0;
+  w.off_part = off;   off = align_up(off + (size_t)D.units * pl.n_slices1 * D.GP * sizeof(float2), 256);
+  w.off_lse = off;    off = align_up(off + (size_t)D.units * D.GP * sizeof(float), 256);
+  w.off_u = off;      off = align_up(off + (size_t)D.units * D.n * sizeof(float), 256);
+  w.off_scores = off; off = align_up(off + (size_t)D.units * D.n * sizeof(float), 256);
+  w.total = off;
+  return w;
+}
+
+static int check_workspace(const Workspace& w, const void* ws, size_t ws_bytes) {
+  if (ws == nullptr || ws_bytes < w.total) return CCD_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) & 255u) return CCD_EWORKSPACE;
+  return CCD_OK;
+}
+
+static int launch_status() { return hipGetLastError() == hipSuccess ? CCD_OK : CCD_ELAUNCH; }
+
+// steps a2-a3: raw CaP score u[unit, t]
+static void run_cap_scores(const Dims& D, const ScorePlan& pl, const Workspace& w, const void* Q, const void* K,
+                           char* ws, hipStream_t st) {
+  float2* part = reinterpret_cast<float2*>(ws + w.off_part);
+  float* lse2 = reinterpret_cast<float*>(ws + w.off_lse);
+  float* u = reinterpret_cast<float*>(ws + w.off_u);
+  launch_stats_valu(D, pl, Q, K, part, st);
+  launch_merge(D, pl, part, lse2, st);
+  launch_prob_valu(D, pl, Q, K, lse2, u, st);
+}
+
+}  // namespace ccd
+
+using namespace ccd;
+
+extern "C" {
+
+size_t ccd_workspace_bytes(const ccd_shape_t* shape) {
+  if (check_shape(shape, kNeedFull) != CCD_OK) return 0;
+  const Dims D = make_dims(shape);
+  return layout_workspace(D, plan_score(D)).total;
+}
+
+int ccd_score(const ccd_shape_t* shape, const void* Q_cat, const void* K, const float* novelty, float* scores,
+              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_shape(shape, kNeedFull);
+  if (rc != CCD_OK) return rc;
+  if (Q_cat == nullptr || K == nullptr || scores == nullptr) return CCD_EINVAL;
+  if (novelty == nullptr && shape->T > 0) return CCD_EINVAL;
+  if (!aligned16(Q_cat) || !aligned16(K)) return CCD_EALIGN;
+  const Dims D = make_dims(shape);
+  const ScorePlan pl = plan_score(D);
+  const Workspace w = layout_workspace(D, pl);
+  rc = check_workspace(w, workspace, workspace_bytes);
+  if (rc != CCD_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  run_cap_scores(D, pl, w, Q_cat, K, ws, st);
+  launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), novelty, scores, nullptr, st);
+  return launch_status();
+}
+
+int ccd_select(const ccd_shape_t* shape, const float* scores, int32_t* keep_idx, void* hip_stream) {
+  int rc = check_shape(shape, 0);
+  if (rc != CCD_OK) return rc;
+  if (scores == nullptr || keep_idx == nullptr) return CCD_EINVAL;
+  const Dims D = make_dims(shape);
+  launch_finalize_select(D, nullptr, nullptr, const_cast<float*>(scores), keep_idx, static_cast<hipStream_t>(hip_stream));
+  return launch_status();
+}
+
+int ccd_compact(const ccd_shape_t* shape, const void* K_src, const void* V_src, const int32_t* keep_idx, void* K_dst,
+                void* V_dst, float* novelty_inout, void* hip_stream) {
+  int rc = check_shape(shape, kNeedKV | (novelty_inout ? kNeedNov : 0));
+  if (rc != CCD_OK) return rc;
+  if (K_src == nullptr || V_src == nullptr || K_dst == nullptr || V_dst == nullptr || keep_idx == nullptr)
+    return CCD_EINVAL;
+  if (!aligned16(K_src) || !aligned16(V_src) || !aligned16(K_dst) || !aligned16(V_dst)) return CCD_EALIGN;
+  const Dims D = make_dims(shape);
+  const bool per_head = shape->nov_stride_l != 0 || shape->nov_stride_h != 0;
+  launch_compact(D, K_src, V_src, keep_idx, K_dst, V_dst, per_head ? novelty_inout : nullptr,
+                 static_cast<hipStream_t>(hip_stream));
+  return launch_status();
+}
+
+int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
+                 int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_shape(shape, kNeedFull);
+  if (rc != CCD_OK) return rc;
+  if (Q_cat == nullptr || K == nullptr || V == nullptr || keep_idx == nullptr) return CCD_EINVAL;
+  if (novelty == nullptr && shape->T > 0) return CCD_EINVAL;
+  if (!aligned16(Q_cat) || !aligned16(K) || !aligned16(V)) return CCD_EALIGN;
+  const Dims D = make_dims(shape);
+  const ScorePlan pl = plan_score(D);
+  const Workspace w = layout_workspace(D, pl);
+  rc = check_workspace(w, workspace, workspace_bytes);
+  if (rc != CCD_OK) return rc;
+  if (shape->n_valid < shape->n_cap || shape->n_valid <= shape->k) return CCD_NOOP;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  float* scores = scores_opt ? scores_opt : reinterpret_cast<float*>(ws + w.off_scores);
+  run_cap_scores(D, pl, w, Q_cat, K, ws, st);
+  launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), novelty, scores, keep_idx, st);
+  const bool per_head = shape->nov_stride_l != 0 || shape->nov_stride_h != 0;
+  launch_compact(D, K, V, keep_idx, K, V, per_head ? novelty : nullptr, st);
+  return launch_status();
+}
+
+int ccd_set_score_path(int path) {
+  if (path < 0 || path > 2) return CCD_EINVAL;
+  g_score_path = path;
+  return CCD_OK;
+}
+
+const char* ccd_strerror(int code) {
+  switch (code) {
+    case CCD_OK: return "ok";
+    case CCD_NOOP: return "pot not full or nothing to drop: nothing done";
+    case CCD_EINVAL: return "invalid argument (null pointer or shape field out of range)";
+    case CCD_EUNSUPPORTED: return "unsupported head dimension, dtype or pool mode";
+    case CCD_EALIGN: return "pointer or stride not 16-byte aligned";
+    case CCD_EWORKSPACE: return "workspace null, misaligned or too small";
+    case CCD_ELAUNCH: return "HIP kernel launch failed";
+    default: return "unknown code";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,131 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the header
+declares, agrees with the header on the struct layout, and decides every error / no-op case before any launch."""
+import ctypes
+import os
+import re
+import subprocess
+import tempfile
+
+import pytest
+
+from paper_2410_01518_amd import infinipot as ip
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "infinipot.h")
+
+
+def _declared():
+    src = open(HEADER).read()
+    return re.findall(r"CCD_API\s+[\w\s\*]+?\b(ccd_\w+)\s*\(", src)
+
+
+def test_header_symbols_are_exported():
+    names = _declared()
+    assert set(names) == set(ip.EXPORTS) and len(names) == len(ip.EXPORTS)
+    L = ip.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_struct_layout_matches_header():
+    prog = r'''
+#include <stdio.h>
+#include <stddef.h>
+#include "infinipot.h"
+int main(void){ printf("%zu %zu %zu %zu %zu\n", sizeof(ccd_shape_t), offsetof(ccd_shape_t, scale),
+  offsetof(ccd_shape_t, kv_stride_b), offsetof(ccd_shape_t, q_stride_h), offsetof(ccd_shape_t, nov_stride_h));
+  printf("%d %d %d %d %d %d %d\n", CCD_OK, CCD_NOOP, CCD_EINVAL, CCD_EUNSUPPORTED, CCD_EALIGN, CCD_EWORKSPACE, CCD_ELAUNCH);
+  return 0; }'''
+    with tempfile.TemporaryDirectory() as td:
+        c = os.path.join(td, "t.c"); exe = os.path.join(td, "t")
+        open(c, "w").write(prog)
+        subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), c, "-o", exe], check=True)
+        out = subprocess.run([exe], capture_output=True, text=True, check=True).stdout.split()
+    vals = [int(v) for v in out]
+    S = ip.ccd_shape_t
+    assert vals[:5] == [ctypes.sizeof(S), S.scale.offset, S.kv_stride_b.offset, S.q_stride_h.offset, S.nov_stride_h.offset]
+    assert vals[5:] == [ip.CCD_OK, ip.CCD_NOOP, ip.CCD_EINVAL, ip.CCD_EUNSUPPORTED, ip.CCD_EALIGN, ip.CCD_EWORKSPACE,
+                        ip.CCD_ELAUNCH]
+
+
+def _shape(**kw):
+    s = ip.ccd_shape_t()
+    base = dict(B=1, L=2, Hq=8, Hkv=2, d=128, n_valid=512, n_cap=512, k=256, P=16, T=128, pool_w=7,
+                pool_mode=ip.CCD_POOL_MAX, dtype=ip.CCD_BF16, scale=0.0)
+    base.update(kw)
+    for k_, v in base.items():
+        setattr(s, k_, v)
+    d, n_cap = s.d, s.n_cap
+    s.kv_stride_h = kw.get("kv_stride_h", n_cap * d); s.kv_stride_l = kw.get("kv_stride_l", s.Hkv * n_cap * d)
+    s.kv_stride_b = kw.get("kv_stride_b", s.L * s.Hkv * n_cap * d)
+    s.q_stride_h = kw.get("q_stride_h", s.P * d); s.q_stride_l = kw.get("q_stride_l", max(s.Hq, 1) * s.P * d)
+    s.q_stride_b = kw.get("q_stride_b", s.L * max(s.Hq, 1) * s.P * d)
+    s.nov_stride_b = kw.get("nov_stride_b", s.n_valid)
+    s.nov_stride_l = kw.get("nov_stride_l", 0); s.nov_stride_h = kw.get("nov_stride_h", 0)
+    return s
+
+
+P = 0x1000  # a fake, aligned, non-null device address: never dereferenced because every case below fails on the host
+
+
+def _compress(s, Q=P, K=P, V=P, nov=P, scores=None, keep=P, ws=0x10000, ws_bytes=None):
+    nbytes = ip.ccd_workspace_bytes(s) if ws_bytes is None else ws_bytes
+    return ip.lib().ccd_compress(ctypes.byref(s), Q, K, V, nov, scores, keep, ws, nbytes, None)
+
+
+def test_workspace_bytes():
+    s = _shape()
+    n = ip.ccd_workspace_bytes(s)
+    assert n > 0 and n % 256 == 0
+    assert ip.ccd_workspace_bytes(_shape(k=0)) == 0
+    assert ip.lib().ccd_workspace_bytes(None) == 0
+    assert ip.ccd_workspace_bytes(_shape(n_valid=1024, n_cap=1024)) > n
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(k=0), ip.CCD_EINVAL), (dict(k=513), ip.CCD_EINVAL), (dict(T=257), ip.CCD_EINVAL), (dict(T=-1), ip.CCD_EINVAL),
+    (dict(Hq=7), ip.CCD_EINVAL), (dict(B=0), ip.CCD_EINVAL), (dict(P=0), ip.CCD_EINVAL),
+    (dict(pool_w=4), ip.CCD_EINVAL), (dict(pool_w=0), ip.CCD_EINVAL), (dict(n_valid=600), ip.CCD_EINVAL),
+    (dict(scale=-1.0), ip.CCD_EINVAL), (dict(scale=float("nan")), ip.CCD_EINVAL),
+    (dict(kv_stride_h=100), ip.CCD_EINVAL), (dict(q_stride_h=8), ip.CCD_EINVAL),
+    (dict(d=96), ip.CCD_EUNSUPPORTED), (dict(dtype=3), ip.CCD_EUNSUPPORTED), (dict(pool_mode=5), ip.CCD_EUNSUPPORTED),
+    (dict(kv_stride_l=2 * 512 * 128 + 4), ip.CCD_EALIGN), (dict(q_stride_b=2 * 8 * 16 * 128 + 2), ip.CCD_EALIGN),
+])
+def test_bad_shapes_are_rejected_on_the_host(kw, code):
+    s = _shape(**kw)
+    assert ip.lib().ccd_compress(ctypes.byref(s), P, P, P, P, None, P, 0x10000, 1 << 40, None) == code
+    assert ip.lib().ccd_score(ctypes.byref(s), P, P, P, P, 0x10000, 1 << 40, None) == code
+
+
+def test_null_misaligned_and_workspace_errors():
+    s = _shape()
+    assert _compress(s, Q=None) == ip.CCD_EINVAL
+    assert _compress(s, K=None) == ip.CCD_EINVAL
+    assert _compress(s, V=None) == ip.CCD_EINVAL
+    assert _compress(s, keep=None) == ip.CCD_EINVAL
+    assert _compress(s, nov=None) == ip.CCD_EINVAL           # T > 0 needs novelty
+    assert _compress(s, K=P + 8) == ip.CCD_EALIGN
+    assert _compress(s, ws=None) == ip.CCD_EWORKSPACE
+    assert _compress(s, ws=0x10010) == ip.CCD_EWORKSPACE      # not 256-byte aligned
+    assert _compress(s, ws_bytes=ip.ccd_workspace_bytes(s) - 1) == ip.CCD_EWORKSPACE
+    L = ip.lib()
+    assert L.ccd_compress(None, P, P, P, P, None, P, 0x10000, 1 << 40, None) == ip.CCD_EINVAL
+    assert L.ccd_select(ctypes.byref(s), None, P, None) == ip.CCD_EINVAL
+    assert L.ccd_select(ctypes.byref(_shape(k=0)), P, P, None) == ip.CCD_EINVAL
+    assert L.ccd_compact(ctypes.byref(s), P, P, None, P, P, None, None) == ip.CCD_EINVAL
+    assert L.ccd_compact(ctypes.byref(s), P, P + 4, P, P, P, None, None) == ip.CCD_EALIGN
+    assert L.ccd_compact(ctypes.byref(_shape(d=80)), P, P, P, P, P, None, None) == ip.CCD_EUNSUPPORTED
+    assert L.ccd_set_score_path(7) == ip.CCD_EINVAL and L.ccd_set_score_path(0) == ip.CCD_OK
+
+
+def test_pot_not_full_is_a_noop_decided_on_the_host():
+    # Sec. 3.2: distillation only happens once the cache is full.  The fake pointers prove nothing is launched.
+    assert _compress(_shape(n_valid=300, n_cap=512, k=256)) == ip.CCD_NOOP
+    assert _compress(_shape(n_valid=512, n_cap=512, k=512, T=0)) == ip.CCD_NOOP
+
+
+def test_strerror():
+    for code in (0, 1, -1, -2, -3, -4, -5, 99):
+        assert len(ip.ccd_strerror(code)) > 0
+    with pytest.raises(ip.CCDError):
+        ip._check(ip.CCD_EALIGN)

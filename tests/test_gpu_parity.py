@@ -1,0 +1,228 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ccd_oracle as O
+from paper_2410_01518_amd import infinipot as ip
+from paper_2410_01518_amd import synth
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _cfg(**kw):
+    base = dict(name="t", B=1, L=2, Hq=8, Hkv=2, d=128, N=700, k=300, P=9, T=100, w=7, dtype="bf16", keys="normal", seed=11)
+    base.update(kw)
+    return synth.CCDConfig(**base)
+
+
+def _upload(inp):
+    return {k: gu.to_dev(v) for k, v in inp.items()}
+
+
+def _oracle(cfg, inp, pool_mode=O.POOL_MAX, **kw):
+    args = dict(k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=pool_mode)
+    args.update(kw)
+    return O.compress(inp["Q_cat"], inp["K"], inp["V"], inp["novelty"], **args)
+
+
+# ------------------------------------------------------------------ a7: compaction, bit exact
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp32", 64), ("fp32", 128)])
+@pytest.mark.parametrize("inplace", [True, False])
+def test_compact_bit_exact(dtype, d, inplace):
+    print(f"compact dtype={dtype} d={d} inplace={inplace}", flush=True)
+    cfg = _cfg(d=d, dtype=dtype, N=1500, k=777, B=2, L=2)
+    inp = synth.make_inputs(cfg, per_head_novelty=True)
+    rng = np.random.default_rng(3)
+    keep = np.stack([np.sort(rng.choice(cfg.N, cfg.k, replace=False)) for _ in range(cfg.units)]).astype(np.int32)
+    keep[0, :50] = np.arange(50)                      # a unit whose first rows stay where they are
+    keep = keep.reshape(cfg.B, cfg.L, cfg.Hkv, cfg.k)
+    dev = _upload(inp)
+    dk = gu.to_dev(keep)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=0)
+    if inplace:
+        Kd, Vd = dev["K"], dev["V"]
+    else:
+        Kd, Vd = torch.zeros_like(dev["K"]), torch.zeros_like(dev["V"])
+    assert ip.ccd_compact(shape, dev["K"], dev["V"], dk, Kd, Vd, dev["novelty"]) == ip.CCD_OK
+    torch.cuda.synchronize()
+    Kh, Vh, nh = gu.to_host(Kd), gu.to_host(Vd), gu.to_host(dev["novelty"])
+    for b in range(cfg.B):
+        for l in range(cfg.L):
+            for h in range(cfg.Hkv):
+                kp = keep[b, l, h]
+                np.testing.assert_array_equal(Kh[b, l, h, :cfg.k], O.compact(inp["K"][b, l, h], kp))
+                np.testing.assert_array_equal(Vh[b, l, h, :cfg.k], O.compact(inp["V"][b, l, h], kp))
+                np.testing.assert_array_equal(nh[b, l, h, :cfg.k], O.compact(inp["novelty"][b, l, h], kp))
+    if inplace:   # rows beyond k are left as they were
+        np.testing.assert_array_equal(Kh[..., cfg.k:, :], inp["K"][..., cfg.k:, :])
+
+
+# ------------------------------------------------------------------ a6: selection, bit exact
+
+def _special_scores(rng, units, n):
+    s = rng.standard_normal((units, n)).astype(np.float32)
+    s[0] = np.round(s[0], 1)                                           # heavy ties
+    if units > 1:
+        s[1] = 0.25                                                    # everything ties
+    if units > 2:
+        s[2, rng.choice(n, n // 3, replace=False)] = np.inf            # many sentinels
+        s[2, rng.choice(n, min(n, 5), replace=False)] = np.nan
+        s[2, rng.choice(n, min(n, 5), replace=False)] = -np.inf
+        s[2, rng.choice(n, min(n, 7), replace=False)] = 0.0
+        s[2, rng.choice(n, min(n, 7), replace=False)] = -0.0
+    if units > 3:
+        s[3] = np.abs(s[3]) * 1e-38                                    # subnormals
+    return s
+
+
+@pytest.mark.parametrize("n,k", [(1, 1), (5, 2), (64, 64), (1000, 1), (1024, 512), (1025, 513), (4096, 2048), (5000, 4999),
+                                 (33000, 4096)])
+def test_select_bit_exact(n, k):
+    print(f"select n={n} k={k}", flush=True)
+    rng = np.random.default_rng(n * 7 + k)
+    B, L, Hkv = 1, 2, 3
+    s = _special_scores(rng, B * L * Hkv, n).reshape(B, L, Hkv, n)
+    shape = ip.ccd_shape_t()
+    shape.B, shape.L, shape.Hkv, shape.n_valid, shape.k = B, L, Hkv, n, k
+    ds = gu.to_dev(s)
+    keep = torch.full((B, L, Hkv, k), -1, dtype=torch.int32, device="cuda")
+    assert ip.ccd_select(shape, ds, keep) == ip.CCD_OK
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(gu.to_host(keep), gu.replay_select(s, k))
+
+
+# ------------------------------------------------------------------ a1-a5: scores
+
+SCORE_CASES = [
+    dict(),                                                                       # bf16, d 128, ragged n and G*P
+    dict(d=64, N=513, k=100, P=1, T=0, w=1),                                      # one query token, no pooling, CaP only
+    dict(dtype="fp32", d=64, Hq=4, Hkv=4, N=512, k=256, P=16, T=128, w=1),        # config-1 shape
+    dict(dtype="fp32", d=128, N=300, k=299, P=33, T=299, w=3),                    # NuC only
+    dict(keys="outlier1pct", Hq=8, Hkv=2, N=2048, k=1024, P=32, T=512),           # config-2 shape, fewer heads
+    dict(B=2, L=1, Hq=16, Hkv=2, N=1111, k=10, P=40, T=3, w=5),                   # G*P = 320 > one workgroup of queries
+    dict(keys="zipf", B=2, L=1, N=900, k=128, P=16, T=64),
+]
+
+
+@pytest.mark.parametrize("case", range(len(SCORE_CASES)))
+@pytest.mark.parametrize("pool_mode", [O.POOL_MAX, O.POOL_AVG])
+def test_scores_and_staged_calls(case, pool_mode):
+    cfg = _cfg(**SCORE_CASES[case])
+    print(f"score case={case} cfg={cfg} pool_mode={pool_mode}", flush=True)
+    inp = synth.make_inputs(cfg, per_head_novelty=(case % 2 == 1))
+    ref = _oracle(cfg, inp, pool_mode)
+    dev = _upload(inp)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=pool_mode)
+    ws = ip.alloc_workspace(shape)
+    scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
+    keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device="cuda")
+    assert ip.ccd_score(shape, dev["Q_cat"], dev["K"], dev["novelty"], scores, ws) == ip.CCD_OK
+    assert ip.ccd_select(shape, scores, keep) == ip.CCD_OK
+    torch.cuda.synchronize()
+    sh, kh = gu.to_host(scores), gu.to_host(keep)
+    gu.assert_scores_close(sh, ref["scores"], cfg.G * cfg.P)                      # (A) scores
+    gu.check_keep_valid(kh, cfg.N, cfg.k)
+    gu.assert_keep_matches(kh, ref["keep_idx"], ref["scores"], cfg.k)             # (B) selection up to threshold ties
+    np.testing.assert_array_equal(kh, gu.replay_select(sh, cfg.k))                # (C) replay on the GPU's scores
+
+
+# ------------------------------------------------------------------ fused ccd_compress
+
+def _run_fused(cfg, inp, pool_mode=O.POOL_MAX, per_head=False, want_scores=True):
+    dev = _upload(inp)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=pool_mode)
+    ws = ip.alloc_workspace(shape)
+    scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda") if want_scores else None
+    keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device="cuda")
+    rc = ip.ccd_compress(shape, dev["Q_cat"], dev["K"], dev["V"], dev["novelty"], keep, ws, scores=scores)
+    torch.cuda.synchronize()
+    return rc, dev, scores, keep
+
+
+def _check_fused(cfg, inp, ref, dev, scores, keep, per_head):
+    kh = gu.to_host(keep)
+    gu.check_keep_valid(kh, cfg.N, cfg.k)
+    if scores is not None:
+        sh = gu.to_host(scores)
+        gu.assert_scores_close(sh, ref["scores"], cfg.G * cfg.P)
+        np.testing.assert_array_equal(kh, gu.replay_select(sh, cfg.k))
+    frac = gu.assert_keep_matches(kh, ref["keep_idx"], ref["scores"], cfg.k)
+    Kh, Vh = gu.to_host(dev["K"]), gu.to_host(dev["V"])
+    idx = kh.astype(np.int64)[..., None]
+    np.testing.assert_array_equal(Kh[..., :cfg.k, :], np.take_along_axis(inp["K"], idx, axis=3))   # bit copies
+    np.testing.assert_array_equal(Vh[..., :cfg.k, :], np.take_along_axis(inp["V"], idx, axis=3))
+    if per_head:
+        np.testing.assert_array_equal(gu.to_host(dev["novelty"])[..., :cfg.k],
+                                      np.take_along_axis(inp["novelty"], kh.astype(np.int64), axis=3))
+    return frac
+
+
+@pytest.mark.parametrize("name", ["c1", "c2"])
+def test_fused_compress_configs(name):
+    cfg = synth.CONFIGS[name]
+    print(f"fused {cfg}", flush=True)
+    inp = synth.make_inputs(cfg)
+    ref = _oracle(cfg, inp)
+    rc, dev, scores, keep = _run_fused(cfg, inp)
+    assert rc == ip.CCD_OK
+    frac = _check_fused(cfg, inp, ref, dev, scores, keep, False)
+    print(f"  exact keep_idx units: {frac:.3f}", flush=True)
+    # the NuC slots survive in every head (Sec. 3.3.3)
+    kh = gu.to_host(keep)
+    nuc = O.nuc_slots(inp["novelty"][0], cfg.T)
+    for h in range(cfg.Hkv):
+        assert set(nuc.tolist()) <= set(kh[0, 0, h].tolist())
+
+
+@pytest.mark.parametrize("per_head,want_scores", [(True, False), (False, False), (True, True)])
+def test_fused_compress_small(per_head, want_scores):
+    cfg = _cfg(B=2, L=2, N=640, k=320, T=160)
+    print(f"fused small per_head={per_head} want_scores={want_scores}", flush=True)
+    inp = synth.make_inputs(cfg, per_head_novelty=per_head)
+    ref = _oracle(cfg, inp)
+    rc, dev, scores, keep = _run_fused(cfg, inp, per_head=per_head, want_scores=want_scores)
+    assert rc == ip.CCD_OK
+    _check_fused(cfg, inp, ref, dev, scores, keep, per_head)
+
+
+def test_not_full_pot_is_left_untouched():
+    cfg = _cfg()
+    inp = synth.make_inputs(cfg)
+    dev = _upload(inp)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, n_valid=cfg.N - 1)
+    ws = ip.alloc_workspace(shape)
+    keep = torch.full((cfg.B, cfg.L, cfg.Hkv, cfg.k), -7, dtype=torch.int32, device="cuda")
+    assert ip.ccd_compress(shape, dev["Q_cat"], dev["K"], dev["V"], dev["novelty"], keep, ws) == ip.CCD_NOOP
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(gu.to_host(dev["K"]), inp["K"])
+    np.testing.assert_array_equal(gu.to_host(dev["V"]), inp["V"])
+    assert (gu.to_host(keep) == -7).all()
+
+
+def test_partial_pot_staged_scoring_ignores_rows_beyond_n_valid():
+    cfg = _cfg(N=600, k=200, T=50)
+    inp = synth.make_inputs(cfg)
+    n = 555
+    inp["K"][..., n:, :] = 0x7FC0                                   # NaN rows beyond n_valid must never be read into a score
+    ref = O.compress(inp["Q_cat"], inp["K"], inp["V"], inp["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, n_valid=n)
+    dev = _upload(inp)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, n_valid=n)
+    ws = ip.alloc_workspace(shape)
+    scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, n), dtype=torch.float32, device="cuda")
+    assert ip.ccd_score(shape, dev["Q_cat"], dev["K"], dev["novelty"], scores, ws) == ip.CCD_OK
+    torch.cuda.synchronize()
+    gu.assert_scores_close(gu.to_host(scores), ref["scores"], cfg.G * cfg.P)
+
+
+def test_non_finite_keys_keep_indices_valid():
+    cfg = _cfg(N=400, k=150, T=40)
+    inp = synth.make_inputs(cfg)
+    inp["K"][0, 0, 0, 17, :] = 0x7FC0                               # NaN key row
+    inp["K"][0, 1, 1, 5, 3] = 0x7F80                                # +inf element
+    inp["novelty"][0, 3] = np.nan
+    rc, dev, scores, keep = _run_fused(cfg, inp)
+    assert rc == ip.CCD_OK
+    gu.check_keep_valid(gu.to_host(keep), cfg.N, cfg.k)
