@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused CCD compression step (ccd_compress) on one MI355X.
+
+A step is one ccd_compress call over one full pot of the headline configuration (32 layers x 8 KV heads
+x 128, 32 query heads, pot 4096 -> 2048, 64 CaP query tokens, T = 1024 NuC slots, max-pool window 7, bf16,
+synthetic seeded data).  Steps cycle over a ring of independent pots so that no call finds its cache warm
+from the previous one.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+VALU_FP32_PEAK_TFLOPS = 157.3
+
+
+def algorithmic_bytes(cfg) -> dict:
+    """Bytes the method has to move per call, by stage and for the whole call ('Algorithmic bytes')."""
+    e = 4 if cfg.dtype == "fp32" else 2
+    u, N, k, d, GP = cfg.units, cfg.N, cfg.k, cfg.d, cfg.G * cfg.P
+    kbytes, qbytes = u * N * d * e, u * GP * d * e
+    rows = u * k * d * e
+    return {
+        "score_stats": kbytes + qbytes,
+        "score_merge": 0,
+        "score_prob": kbytes + qbytes + u * N * 4,
+        "select": u * N * 4 + cfg.B * N * 4 + u * k * 4,
+        "compact": 4 * rows + u * k * 4,
+        # whole call: K read once, Q_cat once, kept V rows read once, K' and V' written once, keep_idx, novelty
+        "call": kbytes + qbytes + rows + 2 * rows + u * k * 4 + cfg.B * N * 4,
+    }
+
+
+def algorithmic_flops(cfg) -> float:
+    return 2.0 * cfg.units * cfg.G * cfg.P * cfg.N * cfg.d
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--ring", type=int, default=3, help="independent pots cycled through")
+    ap.add_argument("--config", default="c3")
+    ap.add_argument("--score-path", type=int, default=0, help="0 auto, 1 vector ALU, 2 MFMA")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-units", type=int, default=16, help="units of the workload the CPU oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (units shard without communication; see DESIGN.md); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2410_01518_amd import infinipot as ip
+    from paper_2410_01518_amd import synth
+
+    cfg = synth.CONFIGS[args.config]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    ip.lib()
+    ip.ccd_set_score_path(args.score_path)
+
+    def upload(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(dev)
+        return torch.from_numpy(a).to(dev)
+
+    host0 = synth.make_inputs(cfg)                       # pot 0: host-generated, also feeds the CPU baseline
+    pots = [{k: upload(v) for k, v in host0.items()}]
+    tdt = torch.float32 if cfg.dtype == "fp32" else torch.bfloat16
+    for r in range(1, args.ring):                        # further pots: same recipe drawn on the device
+        g = torch.Generator(device=dev).manual_seed(1000 * cfg.seed + r)
+        pot = {
+            "Q_cat": torch.randn((cfg.B, cfg.L, cfg.Hq, cfg.P, cfg.d), generator=g, device=dev, dtype=torch.float32).to(tdt),
+            "K": torch.randn((cfg.B, cfg.L, cfg.Hkv, cfg.N, cfg.d), generator=g, device=dev, dtype=torch.float32).to(tdt),
+            "V": torch.randn((cfg.B, cfg.L, cfg.Hkv, cfg.N, cfg.d), generator=g, device=dev, dtype=torch.float32).to(tdt),
+            "novelty": torch.rand((cfg.B, cfg.N), generator=g, device=dev, dtype=torch.float32),
+        }
+        pots.append(pot)
+    shape = ip.make_shape(pots[0]["Q_cat"], pots[0]["K"], pots[0]["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w,
+                          pool_mode=ip.CCD_POOL_MAX)
+    ws = ip.alloc_workspace(shape)
+    keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        p = pots[i % len(pots)]
+        rc = ip.ccd_compress(shape, p["Q_cat"], p["K"], p["V"], p["novelty"], keep, ws, stream=stream)
+        assert rc == ip.CCD_OK, rc
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # the same K steps again with an event after every kernel: per-kernel average durations
+    ip.ccd_profile_enable(True)
+    for i in range(args.steps):
+        step(i)
+    stage_ms, calls = ip.ccd_profile_collect()
+    ip.ccd_profile_enable(False)
+    stage_avg_us = {k: 1e3 * v / max(calls, 1) for k, v in stage_ms.items()}
+
+    ab = algorithmic_bytes(cfg)
+    dom = max(stage_avg_us, key=stage_avg_us.get)
+    dom_s = stage_avg_us[dom] * 1e-6
+    if dom in ("score_stats", "score_prob"):
+        flops = algorithmic_flops(cfg)
+        if args.score_path == 1 or cfg.dtype == "fp32":
+            roof = {"kernel": dom, "bound": "alu", "achieved": flops / dom_s / 1e12, "peak": VALU_FP32_PEAK_TFLOPS,
+                    "unit": "TFLOP/s"}
+        else:
+            roof = {"kernel": dom, "bound": "mfma", "achieved": flops / dom_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s"}
+    else:
+        roof = {"kernel": dom, "bound": "hbm", "achieved": ab[dom] / dom_s / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["avg_us"] = stage_avg_us[dom]
+
+    call_gbps = ab["call"] / (ms_per_step * 1e-3) / 1e9
+    out = {
+        "metric": "ccd_compress calls/s (fused score+select+compact, 32L x 8KV x 128d pot 4096->2048)",
+        "value": 1e3 / ms_per_step, "unit": "calls/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B{cfg.B} L{cfg.L} Hq{cfg.Hq} Hkv{cfg.Hkv} d{cfg.d} N{cfg.N}->k{cfg.k} "
+                               f"P{cfg.P} T{cfg.T} pool{cfg.w}", "ring_pots": len(pots), "score_path": args.score_path},
+        "call_hbm": {"algorithmic_bytes": ab["call"], "achieved_GBps": call_gbps, "frac_of_peak": call_gbps / HBM_PEAK_GBPS},
+        "stage_avg_us": stage_avg_us,
+        "roofline": roof,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import ccd_oracle as O   # CPU baseline leg only
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            threads = os.cpu_count() or 1
+        n_units = min(args.cpu_units, cfg.units)
+        sample = [(u // (cfg.L * cfg.Hkv), (u // cfg.Hkv) % cfg.L, u % cfg.Hkv)
+                  for u in np.linspace(0, cfg.units - 1, n_units).astype(int)]
+        c0 = time.perf_counter()
+        O.compress(host0["Q_cat"], host0["K"], host0["V"], host0["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w,
+                   pool_mode=O.POOL_MAX, units=sample)
+        c1 = time.perf_counter()
+        per_call = (c1 - c0) * cfg.units / n_units
+        out["cpu_baseline"] = {"value": 1.0 / per_call, "unit": "calls/s", "cores": threads, "kind": "oracle",
+                               "sample": f"{n_units} of {cfg.units} units of pot 0 in {c1 - c0:.2f} s, scaled to a whole call"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

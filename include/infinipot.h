@@ -108,6 +108,17 @@ CCD_API int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, v
  * for profiling one path against the other; returns CCD_EINVAL for any other value. */
 CCD_API int ccd_set_score_path(int path);
 
+/* Per-kernel timing of ccd_compress for benchmarks (host-side aid, off by default).  While enabled, each
+ * ccd_compress call records a HIP event on the caller's stream before its first kernel and after every kernel
+ * (events are created on demand and reused; nothing else changes).  ccd_profile_collect waits for the recorded
+ * events, adds up the elapsed milliseconds per stage into stage_ms[ccd_profile_stages()] (host array) and stores
+ * the number of calls covered in *calls (host), then forgets them.  Stage i is named ccd_profile_stage_name(i).
+ * Not thread safe; meant for one stream. */
+CCD_API int ccd_profile_enable(int on);
+CCD_API int ccd_profile_stages(void);
+CCD_API const char* ccd_profile_stage_name(int stage);
+CCD_API int ccd_profile_collect(double* stage_ms, int64_t* calls);
+
 /* Static, human-readable text for a return code. */
 CCD_API const char* ccd_strerror(int code);
 

@@ -39,6 +39,11 @@ void launch_merge(const Dims& D, const ScorePlan& pl, const float2* part, float*
 void launch_prob_valu(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float* lse2, float* u,
                       hipStream_t s);
 
+// the same two passes on the matrix cores (bf16 only)
+void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s);
+void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float* lse2, float* u,
+                      hipStream_t s);
+
 // pooling + NuC lift -> scores (when `u` != null), top-k -> keep_idx (when `keep_idx` != null)
 void launch_finalize_select(const Dims& D, const float* u, const float* novelty, float* scores,
                             int32_t* keep_idx, hipStream_t s);

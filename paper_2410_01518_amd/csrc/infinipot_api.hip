@@ -5,6 +5,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/infinipot.h"
 #include "ccd_kernels.h"
 
@@ -69,13 +71,19 @@ static Dims make_dims(const ccd_shape_t* s) {
   return D;
 }
 
+constexpr int kMinSlice = 256;   // smallest token slice any plan uses: sizes the per-slice statistics
+
 ScorePlan plan_score(const Dims& D) {
   ScorePlan pl{};
-  pl.use_mfma = 0;
-  (void)g_score_path;
-  pl.slice1 = 256;
+  pl.use_mfma = (D.dtype == CCD_BF16 && g_score_path != 1) ? 1 : 0;
+  if (pl.use_mfma) {
+    pl.slice1 = 512;
+    pl.slice2 = 512;   // multiple of 64, at most mfma_max_slice2()
+  } else {
+    pl.slice1 = kMinSlice;
+    pl.slice2 = 256;   // one token per thread
+  }
   pl.n_slices1 = (D.n + pl.slice1 - 1) / pl.slice1;
-  pl.slice2 = 256;
   pl.n_slices2 = (D.n + pl.slice2 - 1) / pl.slice2;
   return pl;
 }
@@ -84,10 +92,12 @@ struct Workspace {
   size_t off_part, off_lse, off_u, off_scores, total;
 };
 
-static Workspace layout_workspace(const Dims& D, const ScorePlan& pl) {
+// The layout does not depend on the kernel path, so a workspace sized once serves either.
+static Workspace layout_workspace(const Dims& D) {
   Workspace w{};
   size_t off = 0;
-  w.off_part = off;   off = align_up(off + (size_t)D.units * pl.n_slices1 * D.GP * sizeof(float2), 256);
+  const size_t max_slices = (D.n + kMinSlice - 1) / kMinSlice;
+  w.off_part = off;   off = align_up(off + (size_t)D.units * max_slices * D.GP * sizeof(float2), 256);
   w.off_lse = off;    off = align_up(off + (size_t)D.units * D.GP * sizeof(float), 256);
   w.off_u = off;      off = align_up(off + (size_t)D.units * D.n * sizeof(float), 256);
   w.off_scores = off; off = align_up(off + (size_t)D.units * D.n * sizeof(float), 256);
@@ -101,17 +111,44 @@ static int check_workspace(const Workspace& w, const void* ws, size_t ws_bytes) 
   return CCD_OK;
 }
 
+// ---- optional per-kernel timing of ccd_compress -------------------------------------------------------
+enum Stage { kStStats = 0, kStMerge, kStProb, kStSelect, kStCompact, kNumStages };
+static const char* const kStageNames[kNumStages] = {"score_stats", "score_merge", "score_prob", "select", "compact"};
+
+struct Profiler {
+  bool on = false;
+  std::vector<hipEvent_t> pool;       // every event ever created
+  size_t used = 0;                    // events handed out since the last collect
+  std::vector<int> marks;             // stage that ENDS at event i (-1: start of a call)
+  void mark(int stage, hipStream_t st) {
+    if (!on) return;
+    if (used == pool.size()) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return;
+      pool.push_back(e);
+    }
+    (void)hipEventRecord(pool[used], st);
+    marks.resize(used + 1);
+    marks[used] = stage;
+    ++used;
+  }
+};
+static Profiler g_prof;
+
 static int launch_status() { return hipGetLastError() == hipSuccess ? CCD_OK : CCD_ELAUNCH; }
 
 // steps a2-a3: raw CaP score u[unit, t]
 static void run_cap_scores(const Dims& D, const ScorePlan& pl, const Workspace& w, const void* Q, const void* K,
-                           char* ws, hipStream_t st) {
+                           char* ws, hipStream_t st, bool profile) {
   float2* part = reinterpret_cast<float2*>(ws + w.off_part);
   float* lse2 = reinterpret_cast<float*>(ws + w.off_lse);
   float* u = reinterpret_cast<float*>(ws + w.off_u);
-  launch_stats_valu(D, pl, Q, K, part, st);
+  if (pl.use_mfma) launch_stats_mfma(D, pl, Q, K, part, st); else launch_stats_valu(D, pl, Q, K, part, st);
+  if (profile) g_prof.mark(kStStats, st);
   launch_merge(D, pl, part, lse2, st);
-  launch_prob_valu(D, pl, Q, K, lse2, u, st);
+  if (profile) g_prof.mark(kStMerge, st);
+  if (pl.use_mfma) launch_prob_mfma(D, pl, Q, K, lse2, u, st); else launch_prob_valu(D, pl, Q, K, lse2, u, st);
+  if (profile) g_prof.mark(kStProb, st);
 }
 
 }  // namespace ccd
@@ -123,7 +160,7 @@ extern "C" {
 size_t ccd_workspace_bytes(const ccd_shape_t* shape) {
   if (check_shape(shape, kNeedFull) != CCD_OK) return 0;
   const Dims D = make_dims(shape);
-  return layout_workspace(D, plan_score(D)).total;
+  return layout_workspace(D).total;
 }
 
 int ccd_score(const ccd_shape_t* shape, const void* Q_cat, const void* K, const float* novelty, float* scores,
@@ -135,12 +172,12 @@ int ccd_score(const ccd_shape_t* shape, const void* Q_cat, const void* K, const 
   if (!aligned16(Q_cat) || !aligned16(K)) return CCD_EALIGN;
   const Dims D = make_dims(shape);
   const ScorePlan pl = plan_score(D);
-  const Workspace w = layout_workspace(D, pl);
+  const Workspace w = layout_workspace(D);
   rc = check_workspace(w, workspace, workspace_bytes);
   if (rc != CCD_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  run_cap_scores(D, pl, w, Q_cat, K, ws, st);
+  run_cap_scores(D, pl, w, Q_cat, K, ws, st, false);
   launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), novelty, scores, nullptr, st);
   return launch_status();
 }
@@ -177,23 +214,53 @@ int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, 
   if (!aligned16(Q_cat) || !aligned16(K) || !aligned16(V)) return CCD_EALIGN;
   const Dims D = make_dims(shape);
   const ScorePlan pl = plan_score(D);
-  const Workspace w = layout_workspace(D, pl);
+  const Workspace w = layout_workspace(D);
   rc = check_workspace(w, workspace, workspace_bytes);
   if (rc != CCD_OK) return rc;
   if (shape->n_valid < shape->n_cap || shape->n_valid <= shape->k) return CCD_NOOP;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
   float* scores = scores_opt ? scores_opt : reinterpret_cast<float*>(ws + w.off_scores);
-  run_cap_scores(D, pl, w, Q_cat, K, ws, st);
+  g_prof.mark(-1, st);
+  run_cap_scores(D, pl, w, Q_cat, K, ws, st, true);
   launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), novelty, scores, keep_idx, st);
+  g_prof.mark(kStSelect, st);
   const bool per_head = shape->nov_stride_l != 0 || shape->nov_stride_h != 0;
   launch_compact(D, K, V, keep_idx, K, V, per_head ? novelty : nullptr, st);
+  g_prof.mark(kStCompact, st);
   return launch_status();
 }
 
 int ccd_set_score_path(int path) {
   if (path < 0 || path > 2) return CCD_EINVAL;
   g_score_path = path;
+  return CCD_OK;
+}
+
+int ccd_profile_enable(int on) {
+  g_prof.on = on != 0;
+  return CCD_OK;
+}
+
+int ccd_profile_stages(void) { return kNumStages; }
+
+const char* ccd_profile_stage_name(int stage) {
+  return (stage >= 0 && stage < kNumStages) ? kStageNames[stage] : "";
+}
+
+int ccd_profile_collect(double* stage_ms, int64_t* calls) {
+  if (stage_ms == nullptr || calls == nullptr) return CCD_EINVAL;
+  for (int i = 0; i < kNumStages; ++i) stage_ms[i] = 0.0;
+  *calls = 0;
+  if (g_prof.used > 0 && hipEventSynchronize(g_prof.pool[g_prof.used - 1]) != hipSuccess) return CCD_ELAUNCH;
+  for (size_t i = 0; i < g_prof.used; ++i) {
+    const int stage = g_prof.marks[i];
+    if (stage < 0) { ++*calls; continue; }
+    float ms = 0.f;
+    if (i > 0 && hipEventElapsedTime(&ms, g_prof.pool[i - 1], g_prof.pool[i]) == hipSuccess) stage_ms[stage] += ms;
+  }
+  g_prof.used = 0;
+  g_prof.marks.clear();
   return CCD_OK;
 }
 

@@ -21,7 +21,8 @@ CCD_FP32, CCD_BF16 = 0, 1
 CCD_POOL_NONE, CCD_POOL_MAX, CCD_POOL_AVG = 0, 1, 2
 
 EXPORTS = ("ccd_workspace_bytes", "ccd_score", "ccd_select", "ccd_compact", "ccd_compress",
-           "ccd_set_score_path", "ccd_strerror")
+           "ccd_set_score_path", "ccd_profile_enable", "ccd_profile_stages", "ccd_profile_stage_name",
+           "ccd_profile_collect", "ccd_strerror")
 
 
 class ccd_shape_t(ctypes.Structure):
@@ -64,6 +65,14 @@ def lib() -> ctypes.CDLL:
         L.ccd_compress.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.ccd_set_score_path.restype = ctypes.c_int
         L.ccd_set_score_path.argtypes = [ctypes.c_int]
+        L.ccd_profile_enable.restype = ctypes.c_int
+        L.ccd_profile_enable.argtypes = [ctypes.c_int]
+        L.ccd_profile_stages.restype = ctypes.c_int
+        L.ccd_profile_stages.argtypes = []
+        L.ccd_profile_stage_name.restype = ctypes.c_char_p
+        L.ccd_profile_stage_name.argtypes = [ctypes.c_int]
+        L.ccd_profile_collect.restype = ctypes.c_int
+        L.ccd_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
         L.ccd_strerror.restype = ctypes.c_char_p
         L.ccd_strerror.argtypes = [ctypes.c_int]
         _lib = L
@@ -157,3 +166,16 @@ def ccd_compress(shape, Q_cat, K, V, novelty, keep_idx, workspace, scores=None, 
 
 def ccd_set_score_path(path: int) -> int:
     return _check(lib().ccd_set_score_path(path))
+
+
+def ccd_profile_enable(on: bool) -> int:
+    return _check(lib().ccd_profile_enable(1 if on else 0))
+
+
+def ccd_profile_collect():
+    """(dict stage name -> total ms, number of ccd_compress calls covered) since profiling was enabled."""
+    n = lib().ccd_profile_stages()
+    ms = (ctypes.c_double * n)()
+    calls = ctypes.c_int64(0)
+    _check(lib().ccd_profile_collect(ms, ctypes.byref(calls)))
+    return {lib().ccd_profile_stage_name(i).decode(): ms[i] for i in range(n)}, calls.value

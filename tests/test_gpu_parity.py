@@ -107,11 +107,20 @@ SCORE_CASES = [
 ]
 
 
+@pytest.fixture
+def score_path(request):
+    """Selects the logit kernels (0 automatic: matrix cores for bf16; 1: vector ALUs) and restores the default."""
+    ip.ccd_set_score_path(request.param)
+    yield request.param
+    ip.ccd_set_score_path(0)
+
+
 @pytest.mark.parametrize("case", range(len(SCORE_CASES)))
 @pytest.mark.parametrize("pool_mode", [O.POOL_MAX, O.POOL_AVG])
-def test_scores_and_staged_calls(case, pool_mode):
+@pytest.mark.parametrize("score_path", [0, 1], indirect=True)
+def test_scores_and_staged_calls(case, pool_mode, score_path):
     cfg = _cfg(**SCORE_CASES[case])
-    print(f"score case={case} cfg={cfg} pool_mode={pool_mode}", flush=True)
+    print(f"score case={case} cfg={cfg} pool_mode={pool_mode} path={score_path}", flush=True)
     inp = synth.make_inputs(cfg, per_head_novelty=(case % 2 == 1))
     ref = _oracle(cfg, inp, pool_mode)
     dev = _upload(inp)
