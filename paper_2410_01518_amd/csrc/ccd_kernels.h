@@ -41,7 +41,8 @@ void launch_prob_valu(const Dims& D, const ScorePlan& pl, const void* Q, const v
 
 // the same two passes on the matrix cores (bf16 only)
 void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s);
-void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float* lse2, float* u,
+// (pass 2 merges the per-slice statistics itself: no merge launch on this path)
+void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float2* part, float* u,
                       hipStream_t s);
 
 // pooling + NuC lift -> scores (when `u` != null), top-k -> keep_idx (when `keep_idx` != null)

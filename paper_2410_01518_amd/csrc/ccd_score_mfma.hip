@@ -3,7 +3,7 @@
 // Same two-pass scheme as the vector-ALU kernels (the normaliser of every CaP query over ALL cached tokens is
 // needed before probabilities can be summed over queries); the logits are recomputed in pass 2 rather than kept.
 // A workgroup of 4 waves owns one token slice of one unit.  Each wave keeps the fragments of 64 query rows in
-// registers for the whole slice; K streams HBM -> registers -> LDS (64-token tiles, double buffered, rows padded
+// registers for the whole slice; K streams HBM -> registers -> LDS in 32-token tiles (ring of three, rows padded
 // by 16 bytes so that fragment reads are bank-conflict free) and every wave reads each tile.
 //
 // The 32x32 accumulator tile puts its column index on the lane (lane % 32) and its row index on the register, so
@@ -11,9 +11,13 @@
 //   pass 1  D[token][query] = Kfrag x Qfrag : each lane owns one query, folds its 16 token rows into a running
 //           (max, sum of 2^(x - max)) pair;
 //   pass 2  D[query][token] = Qfrag x Kfrag : each lane owns one token, adds 2^(x - lse2[query]) of its 16 query
-//           rows into one partial sum.
+//           rows into partial sums.
 // The fragment a lane holds is the same in both roles: the vector with index lane % 32, elements
 // 8*(lane/32) .. +7 of each 16-element step of the head dimension.
+//
+// The path is bound by the vector ALU (fma + exp2 + add per logit), not by the matrix cores, so the loop is
+// software pipelined inside each wave: the MFMAs of tile s+1 are issued between the ALU instructions that
+// consume tile s, and the scheduler is told to keep that interleave.
 #include "ccd_common.h"
 
 namespace ccd {
@@ -24,10 +28,11 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kMT = 256;            // threads per workgroup (4 waves)
-constexpr int kTile = 64;           // tokens per LDS buffer
+constexpr int kStep = 32;           // tokens per tile
+constexpr int kDepth = 6;           // LDS ring slots = tiles in flight from HBM (must be even)
 constexpr int kQB = 2;              // 32-query blocks per wave
 constexpr int kQPerPass = 4 * kQB * 32;   // query rows a workgroup covers per sweep over its slice
-constexpr int kMaxSlice2 = 1024;    // pass-2 slice limit (per-wave partial sums live in LDS)
+constexpr int kMaxSlice = 1024;     // slice limit (per-wave partial sums of pass 2 live in LDS)
 constexpr float kNegHuge = -1.0e30f;
 
 // row of the 32x32 accumulator tile held in register r by a lane of half `half` (lane / 32)
@@ -42,32 +47,60 @@ __device__ __forceinline__ bool decode_block(const Dims& D, int n_slices, int& u
   return unit < D.units;
 }
 
+// K tiles go from HBM straight into LDS (global_load_lds_dwordx4): one wave instruction moves 64 x 16 bytes to
+// consecutive LDS addresses starting at M0, each lane choosing its own global address.  No padding is possible
+// in that scheme, so bank conflicts of the fragment reads are avoided by an XOR swizzle instead: the 16-byte
+// chunk c of row r is stored at chunk position c ^ swz(r) of that row.
 template <int HD>
 struct Tiles {
-  static constexpr int kRowBytes = HD * 2 + 16;
-  static constexpr int kChunksPerRow = HD / 8;                       // 16-byte chunks
-  static constexpr int kChunksPerThread = kTile * kChunksPerRow / kMT;
+  static constexpr int kRowBytes = HD * 2;
+  static constexpr int kChunksPerRow = HD / 8;                       // 16-byte chunks: 16 or 8
+  static constexpr int kRowsPerInstr = 64 / kChunksPerRow;           // rows one wave instruction moves
+  static constexpr int kInstrPerTile = kStep / kRowsPerInstr;        // 8 or 4
+  static constexpr int kInstrPerWave = kInstrPerTile / 4;            // 2 or 1
+  static constexpr int kSlotBytes = kStep * kRowBytes;
+  __device__ static __forceinline__ int swz(int row) { return HD == 128 ? (row & 15) : ((row >> 1) & 7); }
 };
 
+__device__ __forceinline__ void dma16(const void* gbase, uint32_t voff, uint32_t lds_addr) {
+  // gbase and lds_addr are wave-uniform; lane L's 16 bytes land at lds_addr + 16 * L
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase)
+               : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else static_assert(N == 0, "add the immediate");
+}
+
+// this wave's share of tile `tile` of the slice -> ring slot at LDS byte address slot_addr.  Rows past the end
+// of the pot re-read the last valid row: they are masked (pass 1) or never stored (pass 2).
 template <int HD>
-__device__ __forceinline__ void load_tile(uint4 (&g)[Tiles<HD>::kChunksPerThread], const uint16_t* Ku, int tile_t0, int t1) {
+__device__ __forceinline__ void issue_tile(const uint16_t* Ku, int t0, int t1, int tile, uint32_t slot_addr, int wave,
+                                           int lane) {
+  const int tile_t0 = t0 + tile * kStep;
+  const uint16_t* base = Ku + (int64_t)tile_t0 * HD;
+  const int last = t1 - 1 - tile_t0;
 #pragma unroll
-  for (int i = 0; i < Tiles<HD>::kChunksPerThread; ++i) {
-    const int e = threadIdx.x + i * kMT;
-    const int row = e / Tiles<HD>::kChunksPerRow, c = e % Tiles<HD>::kChunksPerRow;
-    const int tok = tile_t0 + row;
-    g[i] = tok < t1 ? *reinterpret_cast<const uint4*>(Ku + (int64_t)tok * HD + c * 8) : make_uint4(0, 0, 0, 0);
+  for (int i = 0; i < Tiles<HD>::kInstrPerWave; ++i) {
+    const int j = wave + 4 * i;
+    const int row = j * Tiles<HD>::kRowsPerInstr + lane / Tiles<HD>::kChunksPerRow;
+    const int c = (lane % Tiles<HD>::kChunksPerRow) ^ Tiles<HD>::swz(row);
+    const uint32_t voff = (uint32_t)(min(row, last) * Tiles<HD>::kRowBytes + c * 16);
+    dma16(base, voff, slot_addr + j * 1024);
   }
 }
 
-template <int HD>
-__device__ __forceinline__ void store_tile(const uint4 (&g)[Tiles<HD>::kChunksPerThread], uint8_t* buf) {
+// fragment reads of tile slot SLOT: koff[ks] is the lane's swizzled byte offset inside a slot
+template <int HD, int SLOT>
+__device__ __forceinline__ void load_k_frags(bf16x8 (&a)[HD / 16], const uint8_t* lds, const int (&koff)[HD / 16]) {
 #pragma unroll
-  for (int i = 0; i < Tiles<HD>::kChunksPerThread; ++i) {
-    const int e = threadIdx.x + i * kMT;
-    const int row = e / Tiles<HD>::kChunksPerRow, c = e % Tiles<HD>::kChunksPerRow;
-    *reinterpret_cast<uint4*>(buf + row * Tiles<HD>::kRowBytes + c * 16) = g[i];
-  }
+  for (int ks = 0; ks < HD / 16; ++ks)
+    a[ks] = *reinterpret_cast<const bf16x8*>(lds + SLOT * Tiles<HD>::kSlotBytes + koff[ks]);
 }
 
 template <int HD>
@@ -87,165 +120,251 @@ __device__ __forceinline__ void load_q_frags(bf16x8 (&bq)[kQB][HD / 16], const D
   }
 }
 
-template <int HD>
-__global__ __launch_bounds__(kMT, 2) void stats_mfma_kernel(Dims D, ScorePlan pl, const uint16_t* __restrict__ Q,
-                                                            const uint16_t* __restrict__ K, float2* __restrict__ part) {
-  constexpr int KS = HD / 16;
-  constexpr int ROWB = Tiles<HD>::kRowBytes;
-  __shared__ __attribute__((aligned(16))) uint8_t lds[2][kTile * ROWB];
-  int unit, slice;
-  if (!decode_block(D, pl.n_slices1, unit, slice)) return;
-  const UnitIdx ui = decode_unit(D, unit);
-  const uint16_t* Ku = K + kv_offset(D, ui);
-  const int t0 = slice * pl.slice1, t1 = min(D.n, t0 + pl.slice1);
-  const int ntiles = (t1 - t0 + kTile - 1) / kTile;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, col = lane & 31, half = lane >> 5;
-  const float c = D.scale_log2;
-
-  for (int qc = 0; qc < D.GP; qc += kQPerPass) {
-    bf16x8 bq[kQB][KS];
-    load_q_frags<HD>(bq, D, ui, Q, qc + wave * (kQB * 32), col, half);
-    float m_raw[kQB], Z[kQB];
+// logits of one 32-token tile against the wave's 2 x 32 query rows; the two chains alternate so that
+// dependent MFMAs are never adjacent.  PASS 1: D[token][query], PASS 2: D[query][token].
+template <int HD, int PASS>
+__device__ __forceinline__ void logits(floatx16 (&acc)[kQB], const bf16x8 (&a)[HD / 16], const bf16x8 (&bq)[kQB][HD / 16]) {
 #pragma unroll
-    for (int qb = 0; qb < kQB; ++qb) { m_raw[qb] = kNegHuge; Z[qb] = 0.f; }
-
-    uint4 g[Tiles<HD>::kChunksPerThread];
-    load_tile<HD>(g, Ku, t0, t1);
-    for (int it = 0; it < ntiles; ++it) {
-      uint8_t* buf = lds[it & 1];
-      store_tile<HD>(g, buf);
-      __syncthreads();
-      if (it + 1 < ntiles) load_tile<HD>(g, Ku, t0 + (it + 1) * kTile, t1);
-      const int tile_t0 = t0 + it * kTile;
+  for (int qb = 0; qb < kQB; ++qb)
 #pragma unroll
-      for (int sub = 0; sub < kTile / 32; ++sub) {
-        const int nvalid = t1 - (tile_t0 + sub * 32);
-        if (nvalid <= 0) break;
-        bf16x8 a[KS];
-        const uint8_t* rowp = buf + (sub * 32 + col) * ROWB + half * 16;
+    for (int r = 0; r < 16; ++r) acc[qb][r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(rowp + ks * 32);
-#pragma unroll
-        for (int qb = 0; qb < kQB; ++qb) {
-          floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bq[qb][ks], acc, 0, 0, 0);
-          if (nvalid < 32) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-              if (acc_row(r, half) >= nvalid) acc[r] = -INFINITY;
-          }
-          float tmax = acc[0];
-#pragma unroll
-          for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, acc[r]);
-          const float m_new = fmaxf(m_raw[qb], tmax);
-          float z = Z[qb] * fast_exp2((m_raw[qb] - m_new) * c);
-          m_raw[qb] = m_new;
-          const float negm = -m_new * c;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) z += fast_exp2(fmaf(acc[r], c, negm));
-          Z[qb] = z;
-        }
-      }
-    }
-    __syncthreads();   // the LDS buffers are refilled by the next sweep
-
-    // the two lane halves hold different token rows of the same query: merge, lower half writes
+  for (int ks = 0; ks < HD / 16; ++ks)
 #pragma unroll
     for (int qb = 0; qb < kQB; ++qb) {
-      const float m_o = __shfl_xor(m_raw[qb], 32), z_o = __shfl_xor(Z[qb], 32);
-      const float M = fmaxf(m_raw[qb], m_o);
-      const float z = Z[qb] * fast_exp2((m_raw[qb] - M) * c) + z_o * fast_exp2((m_o - M) * c);
-      const int q = qc + wave * (kQB * 32) + qb * 32 + col;
-      if (half == 0 && q < D.GP) part[((int64_t)unit * pl.n_slices1 + slice) * D.GP + q] = make_float2(M * c, z);
+      if (PASS == 1) acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bq[qb][ks], acc[qb], 0, 0, 0);
+      else           acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[qb][ks], a[ks], acc[qb], 0, 0, 0);
     }
+}
+
+// pass 1: fold the 16 token rows a lane holds into its query's running (max, sum); nvalid < 32 masks the tail
+template <bool MASKED>
+__device__ __forceinline__ void fold_stats(floatx16 (&acc)[kQB], float (&m_raw)[kQB], float (&Z)[kQB], float c, int half,
+                                           int nvalid) {
+#pragma unroll
+  for (int qb = 0; qb < kQB; ++qb) {
+    if (MASKED) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (acc_row(r, half) >= nvalid) acc[qb][r] = -INFINITY;
+    }
+    float t0 = fmaxf(fmaxf(acc[qb][0], acc[qb][1]), acc[qb][2]);
+    float t1 = fmaxf(fmaxf(acc[qb][3], acc[qb][4]), acc[qb][5]);
+    float t2 = fmaxf(fmaxf(acc[qb][6], acc[qb][7]), acc[qb][8]);
+    float t3 = fmaxf(fmaxf(acc[qb][9], acc[qb][10]), acc[qb][11]);
+    float t4 = fmaxf(fmaxf(acc[qb][12], acc[qb][13]), acc[qb][14]);
+    t0 = fmaxf(fmaxf(t0, t1), t2);
+    t3 = fmaxf(fmaxf(t3, t4), acc[qb][15]);
+    const float m_new = fmaxf(fmaxf(t0, t3), m_raw[qb]);
+    const float negm = -m_new * c;
+    float z0 = Z[qb] * fast_exp2((m_raw[qb] - m_new) * c), z1 = 0.f;   // exact difference first: m may be huge
+    m_raw[qb] = m_new;
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+      z0 += fast_exp2(fmaf(acc[qb][r], c, negm));
+      z1 += fast_exp2(fmaf(acc[qb][r + 1], c, negm));
+    }
+    Z[qb] = z0 + z1;
   }
 }
 
-template <int HD>
-__global__ __launch_bounds__(kMT, 2) void prob_mfma_kernel(Dims D, ScorePlan pl, const uint16_t* __restrict__ Q,
-                                                           const uint16_t* __restrict__ K,
-                                                           const float* __restrict__ lse2, float* __restrict__ u) {
+// pass 2: probability of the lane's token under its 2 x 16 query rows, summed
+__device__ __forceinline__ float fold_prob(const floatx16 (&acc)[kQB], const float (&neg_lse)[kQB][16], float c) {
+  float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+  for (int qb = 0; qb < kQB; ++qb)
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+      s0 += fast_exp2(fmaf(acc[qb][r], c, neg_lse[qb][r]));
+      s1 += fast_exp2(fmaf(acc[qb][r + 1], c, neg_lse[qb][r + 1]));
+    }
+  return s0 + s1;
+}
+
+// scheduling shape of one pipelined step: the LDS fragment reads first, a run of ALU work on the current tile
+// to cover their latency, then one MFMA of the next tile per group of ALU instructions
+template <int KS, int VALU_LEAD, int VALU_PER_MFMA>
+__device__ __forceinline__ void interleave_hint() {
+  __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);          // DS reads
+  __builtin_amdgcn_sched_group_barrier(0x002, VALU_LEAD, 0);   // VALU
+#pragma unroll
+  for (int i = 0; i < 2 * KS; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         // MFMA
+    __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_MFMA, 0);
+  }
+}
+
+// PASS 1 writes part[unit][slice][q] = (max2, sum); PASS 2 reads part (all slices), writes u[unit][t].
+template <int HD, int PASS>
+__global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl, const uint16_t* __restrict__ Q,
+                                                            const uint16_t* __restrict__ K, float2* __restrict__ part,
+                                                            float* __restrict__ u) {
   constexpr int KS = HD / 16;
-  constexpr int ROWB = Tiles<HD>::kRowBytes;
-  __shared__ __attribute__((aligned(16))) uint8_t lds[2][kTile * ROWB];
-  __shared__ float up[4][kMaxSlice2];     // per-wave partial sums over the wave's query rows
+  constexpr int SLOTB = Tiles<HD>::kSlotBytes;
+  constexpr int IPW = Tiles<HD>::kInstrPerWave;
+  __shared__ __attribute__((aligned(1024))) uint8_t lds[kDepth * SLOTB];
+  __shared__ float up[PASS == 2 ? 4 : 1][PASS == 2 ? kMaxSlice : 1];   // per-wave partial sums (pass 2)
+  __shared__ float lse_s[PASS == 2 ? kQPerPass : 1];
+
+  const int slice_len = PASS == 1 ? pl.slice1 : pl.slice2;
+  const int n_slices = PASS == 1 ? pl.n_slices1 : pl.n_slices2;
   int unit, slice;
-  if (!decode_block(D, pl.n_slices2, unit, slice)) return;
+  if (!decode_block(D, n_slices, unit, slice)) return;
   const UnitIdx ui = decode_unit(D, unit);
   const uint16_t* Ku = K + kv_offset(D, ui);
-  const int t0 = slice * pl.slice2, t1 = min(D.n, t0 + pl.slice2);
-  const int ntiles = (t1 - t0 + kTile - 1) / kTile;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, col = lane & 31, half = lane >> 5;
+  const int t0 = slice * slice_len, t1 = min(D.n, t0 + slice_len);
+  const int S = (t1 - t0 + kStep - 1) / kStep;       // tiles in the slice (the last one may be partial)
+  const int S_full = (t1 - t0) / kStep;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63, col = lane & 31, half = lane >> 5;
   const float c = D.scale_log2;
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
+  int koff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) koff[ks] = col * Tiles<HD>::kRowBytes + (((2 * ks + half) ^ Tiles<HD>::swz(col)) << 4);
 
   for (int qc = 0; qc < D.GP; qc += kQPerPass) {
+    // start the K stream first: up to kDepth tiles in flight while the query fragments are fetched
+#pragma unroll
+    for (int i = 0; i < kDepth; ++i)
+      if (i < S) issue_tile<HD>(Ku, t0, t1, i, lds_addr + i * SLOTB, wave, lane);
+
     bf16x8 bq[kQB][KS];
     load_q_frags<HD>(bq, D, ui, Q, qc + wave * (kQB * 32), col, half);
-    float neg_lse[kQB][16];
-#pragma unroll
-    for (int qb = 0; qb < kQB; ++qb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int q = qc + wave * (kQB * 32) + qb * 32 + acc_row(r, half);
-        neg_lse[qb][r] = q < D.GP ? -lse2[(int64_t)unit * D.GP + q] : -INFINITY;
-      }
 
-    uint4 g[Tiles<HD>::kChunksPerThread];
-    load_tile<HD>(g, Ku, t0, t1);
-    for (int it = 0; it < ntiles; ++it) {
-      uint8_t* buf = lds[it & 1];
-      store_tile<HD>(g, buf);
-      __syncthreads();
-      if (it + 1 < ntiles) load_tile<HD>(g, Ku, t0 + (it + 1) * kTile, t1);
+    float m_raw[kQB], Z[kQB];
+    float neg_lse[kQB][16];
+    if (PASS == 1) {
 #pragma unroll
-      for (int sub = 0; sub < kTile / 32; ++sub) {
-        if (t0 + it * kTile + sub * 32 >= t1) break;
-        bf16x8 a[KS];
-        const uint8_t* rowp = buf + (sub * 32 + col) * ROWB + half * 16;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(rowp + ks * 32);
-        float usum = 0.f;
-#pragma unroll
-        for (int qb = 0; qb < kQB; ++qb) {
-          floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[qb][ks], a[ks], acc, 0, 0, 0);
-#pragma unroll
-          for (int r = 0; r < 16; ++r) usum += fast_exp2(fmaf(acc[r], c, neg_lse[qb][r]));
+      for (int qb = 0; qb < kQB; ++qb) { m_raw[qb] = kNegHuge; Z[qb] = 0.f; }
+    } else {
+      // merge the per-slice statistics of pass 1 into log2-sum-exp per query (thread = query of this sweep)
+      const int q = qc + threadIdx.x;
+      float lse = INFINITY;
+      if (q < D.GP) {
+        const float2* p = part + (int64_t)unit * pl.n_slices1 * D.GP + q;
+        float M = kNegHuge;
+        for (int j = 0; j < pl.n_slices1; ++j) M = fmaxf(M, p[(int64_t)j * D.GP].x);
+        float z = 0.f;
+        for (int j = 0; j < pl.n_slices1; ++j) {
+          const float2 v = p[(int64_t)j * D.GP];
+          z += v.y * fast_exp2(v.x - M);
         }
-        usum += __shfl_xor(usum, 32);
+        lse = M + __log2f(z);
+      }
+      lse_s[threadIdx.x] = lse;
+    }
+    // tiles 0 and 1 must have landed (everything older, i.e. the loads above, has then landed too)
+    if (S >= kDepth) wait_vmcnt<IPW * (kDepth - 2)>(); else wait_vmcnt<0>();
+    __syncthreads();
+    if (PASS == 2) {
+#pragma unroll
+      for (int qb = 0; qb < kQB; ++qb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) neg_lse[qb][r] = -lse_s[wave * (kQB * 32) + qb * 32 + acc_row(r, half)];
+    }
+    bf16x8 a[KS];
+    floatx16 accA[kQB], accB[kQB];
+    load_k_frags<HD, 0>(a, lds, koff);
+    logits<HD, PASS>(accA, a, bq);
+
+    // Step s (ring slot I = s mod kDepth): the slot of tile s is free (its fragments were read one step ago),
+    // so tile s+kDepth is requested into it; the MFMAs of tile s+1 run between the ALU work on tile s; before
+    // the barrier tile s+2 must have landed, i.e. at most kDepth-2 younger tiles may still be in flight.
+#define CCD_STEP(I, CUR, NXT)                                                                     \
+    {                                                                                             \
+      if (s >= S_full) break;                                                                     \
+      const bool more = s + kDepth < S;                                                           \
+      if (more) issue_tile<HD>(Ku, t0, t1, s + kDepth, lds_addr + (I) * SLOTB, wave, lane);       \
+      load_k_frags<HD, ((I) + 1) % kDepth>(a, lds, koff);                                         \
+      logits<HD, PASS>(NXT, a, bq);                                                               \
+      if (PASS == 1) {                                                                            \
+        fold_stats<false>(CUR, m_raw, Z, c, half, 32);                                            \
+        interleave_hint<KS, 20, 6>();                                                             \
+      } else {                                                                                    \
+        float us = fold_prob(CUR, neg_lse, c);                                                    \
+        interleave_hint<KS, 14, 5>();                                                             \
+        us += __shfl_xor(us, 32);                                                                 \
+        if (half == 0) {                                                                          \
+          float* dst = &up[wave][s * kStep + col];                                                \
+          *dst = (qc == 0) ? us : *dst + us;                                                      \
+        }                                                                                         \
+      }                                                                                           \
+      if (more) wait_vmcnt<IPW * (kDepth - 2)>(); else wait_vmcnt<0>();                           \
+      __builtin_amdgcn_s_barrier();                                                               \
+      ++s;                                                                                        \
+    }
+    int s = 0;
+    while (true) {
+      CCD_STEP(0, accA, accB)
+      CCD_STEP(1, accB, accA)
+      CCD_STEP(2, accA, accB)
+      CCD_STEP(3, accB, accA)
+      CCD_STEP(4, accA, accB)
+      CCD_STEP(5, accB, accA)
+    }
+#undef CCD_STEP
+    static_assert(kDepth == 6, "the step sequence above is written out for a ring of six");
+    // the logits of tile S_full - the partial tail tile, if there is one - are in accA or accB by parity
+    if (S > S_full) {
+      if (S_full & 1) {
+#pragma unroll
+        for (int qb = 0; qb < kQB; ++qb) accA[qb] = accB[qb];
+      }
+      if (PASS == 1) {
+        fold_stats<true>(accA, m_raw, Z, c, half, (t1 - t0) - S_full * kStep);
+      } else {
+        float us = fold_prob(accA, neg_lse, c);
+        us += __shfl_xor(us, 32);
         if (half == 0) {
-          float* dst = &up[wave][it * kTile + sub * 32 + col];
-          *dst = (qc == 0) ? usum : *dst + usum;
+          float* dst = &up[wave][S_full * kStep + col];
+          *dst = (qc == 0) ? us : *dst + us;
         }
       }
     }
-    __syncthreads();
+    __syncthreads();   // ring, lse_s and up are reused by the next sweep / read below
+
+    if (PASS == 1) {
+      // the two lane halves hold different token rows of the same query: merge, lower half writes
+#pragma unroll
+      for (int qb = 0; qb < kQB; ++qb) {
+        const float m_o = __shfl_xor(m_raw[qb], 32), z_o = __shfl_xor(Z[qb], 32);
+        const float M = fmaxf(m_raw[qb], m_o);
+        const float z = Z[qb] * fast_exp2((m_raw[qb] - M) * c) + z_o * fast_exp2((m_o - M) * c);
+        const int q = qc + wave * (kQB * 32) + qb * 32 + col;
+        if (half == 0 && q < D.GP) part[((int64_t)unit * pl.n_slices1 + slice) * D.GP + q] = make_float2(M * c, z);
+      }
+    }
   }
-  float* uu = u + (int64_t)unit * D.n + t0;
-  for (int t = threadIdx.x; t < t1 - t0; t += kMT) uu[t] = (up[0][t] + up[1][t]) + (up[2][t] + up[3][t]);
+  if (PASS == 2) {
+    float* uu = u + (int64_t)unit * D.n + t0;
+    for (int t = threadIdx.x; t < t1 - t0; t += kMT) uu[t] = (up[0][t] + up[1][t]) + (up[2][t] + up[3][t]);
+  }
 }
 
 }  // namespace
 
-int mfma_max_slice2() { return kMaxSlice2; }
+int mfma_max_slice() { return kMaxSlice; }
 
 void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s) {
   dim3 grid((unsigned)((D.units + 7) / 8 * 8) * pl.n_slices1), block(kMT);
   if (D.d == 64)
-    hipLaunchKernelGGL((stats_mfma_kernel<64>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part);
+    hipLaunchKernelGGL((score_pass_kernel<64, 1>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
+                       (float*)nullptr);
   else
-    hipLaunchKernelGGL((stats_mfma_kernel<128>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part);
+    hipLaunchKernelGGL((score_pass_kernel<128, 1>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
+                       (float*)nullptr);
 }
 
-void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float* lse2, float* u,
+void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float2* part, float* u,
                       hipStream_t s) {
   dim3 grid((unsigned)((D.units + 7) / 8 * 8) * pl.n_slices2), block(kMT);
   if (D.d == 64)
-    hipLaunchKernelGGL((prob_mfma_kernel<64>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, lse2, u);
+    hipLaunchKernelGGL((score_pass_kernel<64, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
+                       const_cast<float2*>(part), u);
   else
-    hipLaunchKernelGGL((prob_mfma_kernel<128>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, lse2, u);
+    hipLaunchKernelGGL((score_pass_kernel<128, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
+                       const_cast<float2*>(part), u);
 }
 
 }  // namespace ccd

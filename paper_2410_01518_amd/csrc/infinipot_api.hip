@@ -143,12 +143,19 @@ static void run_cap_scores(const Dims& D, const ScorePlan& pl, const Workspace& 
   float2* part = reinterpret_cast<float2*>(ws + w.off_part);
   float* lse2 = reinterpret_cast<float*>(ws + w.off_lse);
   float* u = reinterpret_cast<float*>(ws + w.off_u);
-  if (pl.use_mfma) launch_stats_mfma(D, pl, Q, K, part, st); else launch_stats_valu(D, pl, Q, K, part, st);
-  if (profile) g_prof.mark(kStStats, st);
-  launch_merge(D, pl, part, lse2, st);
-  if (profile) g_prof.mark(kStMerge, st);
-  if (pl.use_mfma) launch_prob_mfma(D, pl, Q, K, lse2, u, st); else launch_prob_valu(D, pl, Q, K, lse2, u, st);
-  if (profile) g_prof.mark(kStProb, st);
+  if (pl.use_mfma) {
+    launch_stats_mfma(D, pl, Q, K, part, st);
+    if (profile) g_prof.mark(kStStats, st);
+    launch_prob_mfma(D, pl, Q, K, part, u, st);
+    if (profile) g_prof.mark(kStProb, st);
+  } else {
+    launch_stats_valu(D, pl, Q, K, part, st);
+    if (profile) g_prof.mark(kStStats, st);
+    launch_merge(D, pl, part, lse2, st);
+    if (profile) g_prof.mark(kStMerge, st);
+    launch_prob_valu(D, pl, Q, K, lse2, u, st);
+    if (profile) g_prof.mark(kStProb, st);
+  }
 }
 
 }  // namespace ccd

@@ -34,8 +34,11 @@ def assert_scores_close(gpu: np.ndarray, ref: np.ndarray, GP: int):
     fin = ~inf_r
     err = np.abs(gpu[fin].astype(np.float64) - ref[fin].astype(np.float64))
     tol = score_tolerance(ref[fin], GP)
-    bad = err > tol
-    assert not bad.any(), f"{bad.sum()} scores off; worst rel {np.max(err / np.maximum(np.abs(ref[fin]), 1e-300)):.3e}"
+    bad = ~(err <= tol)                      # NaN on the GPU side counts as a failure
+    if bad.any():
+        where = np.argwhere(fin)[bad][:6].tolist()
+        raise AssertionError(f"{bad.sum()} scores off (NaN: {np.isnan(gpu).sum()}); first at {where}: "
+                             f"gpu {gpu[fin][bad][:6]} ref {ref[fin][bad][:6]}")
 
 
 def assert_keep_matches(gpu_keep, ref_keep, ref_scores, k):
