@@ -3,8 +3,8 @@
 // Same two-pass scheme as the vector-ALU kernels (the normaliser of every CaP query over ALL cached tokens is
 // needed before probabilities can be summed over queries); the logits are recomputed in pass 2 rather than kept.
 // A workgroup of 4 waves owns one token slice of one unit.  Each wave keeps the fragments of 64 query rows in
-// registers for the whole slice; K streams HBM -> registers -> LDS in 32-token tiles (ring of three, rows padded
-// by 16 bytes so that fragment reads are bank-conflict free) and every wave reads each tile.
+// registers for the whole slice; K streams HBM -> LDS by DMA in 32-token tiles (two batches of three tiles,
+// XOR-swizzled so that fragment reads are bank-conflict free) and every wave reads each tile.
 //
 // The 32x32 accumulator tile puts its column index on the lane (lane % 32) and its row index on the register, so
 // the operand order is chosen per pass to make the reduction run along registers, never across lanes:
@@ -29,7 +29,8 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kMT = 256;            // threads per workgroup (4 waves)
 constexpr int kStep = 32;           // tokens per tile
-constexpr int kDepth = 6;           // LDS ring slots = tiles in flight from HBM (must be even)
+constexpr int kBatch = 3;           // tiles per DMA batch
+constexpr int kDepth = 2 * kBatch;  // LDS ring slots: one batch is consumed while the other one lands
 constexpr int kQB = 2;              // 32-query blocks per wave
 constexpr int kQPerPass = 4 * kQB * 32;   // query rows a workgroup covers per sweep over its slice
 constexpr int kMaxSlice = 1024;     // slice limit (per-wave partial sums of pass 2 live in LDS)
@@ -68,14 +69,9 @@ __device__ __forceinline__ void dma16(const void* gbase, uint32_t voff, uint32_t
                : "memory");
 }
 
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N >= 0 && N < 64, "vmcnt range");
-  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-  else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  else static_assert(N == 0, "add the immediate");
-}
+// DMA loads to LDS do not retire in issue order (measured: waiting for "all but the youngest n" let stale tiles
+// through), so the only safe wait is for everything this wave has in flight.
+__device__ __forceinline__ void wait_all_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // this wave's share of tile `tile` of the slice -> ring slot at LDS byte address slot_addr.  Rows past the end
 // of the pot re-read the last valid row: they are masked (pass 1) or never stored (pass 2).
@@ -201,7 +197,6 @@ __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl
                                                             float* __restrict__ u) {
   constexpr int KS = HD / 16;
   constexpr int SLOTB = Tiles<HD>::kSlotBytes;
-  constexpr int IPW = Tiles<HD>::kInstrPerWave;
   __shared__ __attribute__((aligned(1024))) uint8_t lds[kDepth * SLOTB];
   __shared__ float up[PASS == 2 ? 4 : 1][PASS == 2 ? kMaxSlice : 1];   // per-wave partial sums (pass 2)
   __shared__ float lse_s[PASS == 2 ? kQPerPass : 1];
@@ -210,6 +205,9 @@ __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl
   const int n_slices = PASS == 1 ? pl.n_slices1 : pl.n_slices2;
   int unit, slice;
   if (!decode_block(D, n_slices, unit, slice)) return;
+  // pass 2 walks the units backwards: the keys pass 1 read last are the ones most likely still held by the
+  // memory-side cache
+  if (PASS == 2) unit = D.units - 1 - unit;
   const UnitIdx ui = decode_unit(D, unit);
   const uint16_t* Ku = K + kv_offset(D, ui);
   const int t0 = slice * slice_len, t1 = min(D.n, t0 + slice_len);
@@ -224,9 +222,9 @@ __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl
   for (int ks = 0; ks < KS; ++ks) koff[ks] = col * Tiles<HD>::kRowBytes + (((2 * ks + half) ^ Tiles<HD>::swz(col)) << 4);
 
   for (int qc = 0; qc < D.GP; qc += kQPerPass) {
-    // start the K stream first: up to kDepth tiles in flight while the query fragments are fetched
+    // start the K stream first: batch 0 is in flight while the query fragments are fetched
 #pragma unroll
-    for (int i = 0; i < kDepth; ++i)
+    for (int i = 0; i < kBatch; ++i)
       if (i < S) issue_tile<HD>(Ku, t0, t1, i, lds_addr + i * SLOTB, wave, lane);
 
     bf16x8 bq[kQB][KS];
@@ -254,9 +252,11 @@ __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl
       }
       lse_s[threadIdx.x] = lse;
     }
-    // tiles 0 and 1 must have landed (everything older, i.e. the loads above, has then landed too)
-    if (S >= kDepth) wait_vmcnt<IPW * (kDepth - 2)>(); else wait_vmcnt<0>();
+    wait_all_dma();
     __syncthreads();
+#pragma unroll
+    for (int i = kBatch; i < kDepth; ++i)      // batch 1 lands while batch 0 is consumed
+      if (i < S) issue_tile<HD>(Ku, t0, t1, i, lds_addr + i * SLOTB, wave, lane);
     if (PASS == 2) {
 #pragma unroll
       for (int qb = 0; qb < kQB; ++qb)
@@ -268,14 +268,19 @@ __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl
     load_k_frags<HD, 0>(a, lds, koff);
     logits<HD, PASS>(accA, a, bq);
 
-    // Step s (ring slot I = s mod kDepth): the slot of tile s is free (its fragments were read one step ago),
-    // so tile s+kDepth is requested into it; the MFMAs of tile s+1 run between the ALU work on tile s; before
-    // the barrier tile s+2 must have landed, i.e. at most kDepth-2 younger tiles may still be in flight.
+    // Step s (ring slot I = s mod 6) folds tile s on the ALU while the MFMAs of tile s+1 run.  Tiles arrive in
+    // batches of three: the batch that holds tile s+2 must have landed by the end of every step with
+    // s mod 3 == 1 (wait + barrier there, nowhere else); right after that barrier the slots of the batch
+    // consumed before are free, and the next batch (tiles s+4 .. s+6 seen from step s with s mod 3 == 2) is
+    // requested into them.
 #define CCD_STEP(I, CUR, NXT)                                                                     \
     {                                                                                             \
       if (s >= S_full) break;                                                                     \
-      const bool more = s + kDepth < S;                                                           \
-      if (more) issue_tile<HD>(Ku, t0, t1, s + kDepth, lds_addr + (I) * SLOTB, wave, lane);       \
+      if ((I) % kBatch == 2) {                                                                    \
+        _Pragma("unroll") for (int i = 0; i < kBatch; ++i)                                        \
+          if (s + 4 + i < S)                                                                      \
+            issue_tile<HD>(Ku, t0, t1, s + 4 + i, lds_addr + (((I) + 4 + i) % kDepth) * SLOTB, wave, lane); \
+      }                                                                                           \
       load_k_frags<HD, ((I) + 1) % kDepth>(a, lds, koff);                                         \
       logits<HD, PASS>(NXT, a, bq);                                                               \
       if (PASS == 1) {                                                                            \
@@ -290,8 +295,10 @@ __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl
           *dst = (qc == 0) ? us : *dst + us;                                                      \
         }                                                                                         \
       }                                                                                           \
-      if (more) wait_vmcnt<IPW * (kDepth - 2)>(); else wait_vmcnt<0>();                           \
-      __builtin_amdgcn_s_barrier();                                                               \
+      if ((I) % kBatch == 1) {                                                                    \
+        wait_all_dma();                                                                           \
+        __builtin_amdgcn_s_barrier();                                                             \
+      }                                                                                           \
       ++s;                                                                                        \
     }
     int s = 0;
@@ -304,7 +311,7 @@ __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl
       CCD_STEP(5, accB, accA)
     }
 #undef CCD_STEP
-    static_assert(kDepth == 6, "the step sequence above is written out for a ring of six");
+    static_assert(kDepth == 6 && kBatch == 3, "the step sequence above is written out for two batches of three");
     // the logits of tile S_full - the partial tail tile, if there is one - are in accA or accB by parity
     if (S > S_full) {
       if (S_full & 1) {
