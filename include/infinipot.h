@@ -45,7 +45,7 @@ enum {
   CCD_OK = 0,
   CCD_NOOP = 1,          /* pot not full (n_valid < n_cap) or nothing to drop (n_valid <= k): untouched */
   CCD_EINVAL = -1,       /* NULL pointer, or a shape field out of range                                 */
-  CCD_EUNSUPPORTED = -2, /* d not in {64, 128}, unknown dtype or pool_mode                              */
+  CCD_EUNSUPPORTED = -2, /* d not in {64, 128}, unknown dtype or pool_mode, n_valid > 65536             */
   CCD_EALIGN = -3,       /* pointer or stride not 16-byte aligned                                       */
   CCD_EWORKSPACE = -4,   /* workspace NULL, misaligned or smaller than ccd_workspace_bytes()            */
   CCD_ELAUNCH = -5       /* the HIP runtime refused a kernel launch                                    */

@@ -45,9 +45,13 @@ void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const 
 void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float2* part, float* u,
                       hipStream_t s);
 
+// NuC slots: mask[row][t] = 1 for the T tokens of largest novelty (row = sequence when novelty is shared, else unit)
+void launch_nuc_mask(const Dims& D, const float* novelty, uint8_t* mask, hipStream_t s);
 // pooling + NuC lift -> scores (when `u` != null), top-k -> keep_idx (when `keep_idx` != null)
-void launch_finalize_select(const Dims& D, const float* u, const float* novelty, float* scores,
+void launch_finalize_select(const Dims& D, const float* u, const uint8_t* mask, float* scores,
                             int32_t* keep_idx, hipStream_t s);
+
+int select_max_tokens();   // largest n the selection kernel handles
 
 void launch_compact(const Dims& D, const void* Ksrc, const void* Vsrc, const int32_t* keep_idx,
                     void* Kdst, void* Vdst, float* novelty, hipStream_t s);

@@ -1,0 +1,165 @@
+// Exact top-k threshold selection inside one workgroup, shared by the NuC-slot job and the final selection.
+//
+// Keys are order-preserving 32-bit images of fp32 values.  An MSB-first radix select with digits of 11, 11 and 10
+// bits (LDS histogram, one atomic per key and pass) yields the threshold key tau and the number `need` of keys
+// equal to tau that still belong to the k largest: a token is selected iff key > tau, or key == tau and fewer than
+// `need` equal tokens precede it in token order (lowest index wins ties).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ccd {
+
+constexpr int kRadixBins = 2048;
+
+// fp32 -> uint32 with the same order; NaN ranks with -inf and -0 equals +0
+__device__ __forceinline__ uint32_t score_key(float x) {
+  if (x != x) x = -INFINITY;
+  x += 0.0f;
+  const uint32_t b = __float_as_uint(x);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+// novelty key: NaN and -inf map to 0, strictly below every token that may take a NuC slot
+__device__ __forceinline__ uint32_t novelty_key(float x) {
+  if (x != x || x == -INFINITY) return 0u;
+  return score_key(x);
+}
+
+template <int THREADS>
+struct TopkShared {
+  uint32_t hist[kRadixBins];
+  uint32_t wave_sum[2][THREADS / 64];   // ping-pong: one barrier per scan
+  uint32_t digit, remaining;
+};
+
+// Exclusive prefix sum of v over the workgroup in thread order; `total` receives the workgroup's sum.
+template <int THREADS>
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, TopkShared<THREADS>& sh, int& phase, uint32_t& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t inc = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t o = __shfl_up(inc, off);
+    if (lane >= off) inc += o;
+  }
+  if (lane == 63) sh.wave_sum[phase][wave] = inc;
+  __syncthreads();
+  uint32_t before = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < THREADS / 64; ++w) {
+    const uint32_t c = sh.wave_sum[phase][w];
+    before += (w < wave) ? c : 0u;
+    tot += c;
+  }
+  phase ^= 1;
+  total = tot;
+  return before + inc - v;
+}
+
+// Exclusive prefix count of a predicate (ballot/popcount inside the wave).
+template <int THREADS>
+__device__ __forceinline__ uint32_t block_rank(bool pred, TopkShared<THREADS>& sh, int& phase, uint32_t& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint64_t bal = __ballot(pred);
+  const uint32_t r = __popcll(bal & ((1ull << lane) - 1ull));
+  if (lane == 0) sh.wave_sum[phase][wave] = __popcll(bal);
+  __syncthreads();
+  uint32_t before = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < THREADS / 64; ++w) {
+    const uint32_t c = sh.wave_sum[phase][w];
+    before += (w < wave) ? c : 0u;
+    tot += c;
+  }
+  phase ^= 1;
+  total = tot;
+  return before + r;
+}
+
+// Threshold of the kk largest of the keys of tokens 0 .. n-1, 1 <= kk <= n.  Thread tid owns tokens
+// tid + j*THREADS; key_of(j, t) returns the key of token t = tid + j*THREADS.  KPT > 0 unrolls j over 0..KPT-1
+// (keys held in registers), KPT == 0 loops at run time (keys re-read from memory).
+// On return #{key > tau} < kk <= #{key >= tau} and need = kk - #{key > tau}.  Ends with a barrier.
+template <int THREADS, int KPT, class KeyFn>
+__device__ void radix_threshold(KeyFn key_of, int n, uint32_t kk, TopkShared<THREADS>& sh, int& phase, uint32_t& tau,
+                                uint32_t& need) {
+  const int tid = threadIdx.x;
+  constexpr int kBinsPerThread = kRadixBins / THREADS;
+  uint32_t prefix = 0, hi_mask = 0, remaining = kk;
+#pragma unroll 1
+  for (int pass = 0; pass < 3; ++pass) {
+    const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
+    const uint32_t dmask = pass == 2 ? 1023u : 2047u;
+    for (int i = tid; i < kRadixBins; i += THREADS) sh.hist[i] = 0;
+    __syncthreads();
+    if constexpr (KPT > 0) {
+#pragma unroll
+      for (int j = 0; j < KPT; ++j) {
+        const int t = tid + j * THREADS;
+        if (t < n) {
+          const uint32_t key = key_of(j, t);
+          if ((key & hi_mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & dmask], 1u);
+        }
+      }
+    } else {
+      for (int j = 0, t = tid; t < n; ++j, t += THREADS) {
+        const uint32_t key = key_of(j, t);
+        if ((key & hi_mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & dmask], 1u);
+      }
+    }
+    __syncthreads();
+    // thread 0 owns the highest bins: prefix sums in thread order are counts of larger digits
+    uint32_t h[kBinsPerThread], mine = 0;
+#pragma unroll
+    for (int i = 0; i < kBinsPerThread; ++i) {
+      h[i] = sh.hist[kRadixBins - 1 - (tid * kBinsPerThread + i)];
+      mine += h[i];
+    }
+    uint32_t tot;
+    uint32_t excl = block_exclusive_scan<THREADS>(mine, sh, phase, tot);
+#pragma unroll
+    for (int i = 0; i < kBinsPerThread; ++i) {
+      const uint32_t incl = excl + h[i];
+      if (excl < remaining && remaining <= incl) {
+        sh.digit = kRadixBins - 1 - (tid * kBinsPerThread + i);
+        sh.remaining = remaining - excl;
+      }
+      excl = incl;
+    }
+    __syncthreads();
+    prefix |= sh.digit << shift;
+    hi_mask |= dmask << shift;
+    remaining = sh.remaining;
+  }
+  __syncthreads();
+  tau = prefix;
+  need = remaining;
+}
+
+// The T tokens of largest novelty (Sec. 3.3.3 step 1): mask[t] = 1 for them, 0 otherwise, t < n.  NaN and -inf
+// never qualify; ties go to the lower index.  Every thread of the workgroup must call this.
+template <int THREADS>
+__device__ void nuc_mask_job(const float* __restrict__ nov, uint8_t* __restrict__ mask, int n, int T, TopkShared<THREADS>& sh) {
+  const int tid = threadIdx.x;
+  int phase = 0;
+  uint32_t mine = 0;
+  for (int t = tid; t < n; t += THREADS) mine += novelty_key(nov[t]) != 0u;
+  uint32_t eligible;
+  block_exclusive_scan<THREADS>(mine, sh, phase, eligible);
+  const uint32_t T_eff = min((uint32_t)max(T, 0), eligible);
+  uint32_t tau = 0xFFFFFFFFu, need = 0;
+  if (T_eff > 0)
+    radix_threshold<THREADS, 0>([&](int, int t) { return novelty_key(nov[t]); }, n, T_eff, sh, phase, tau, need);
+  uint32_t eq_base = 0;
+  for (int base = 0; base < n; base += THREADS) {
+    const int t = base + tid;
+    const uint32_t key = t < n ? novelty_key(nov[t]) : 0u;
+    const bool eq = T_eff > 0 && t < n && key == tau;
+    uint32_t tot;
+    const uint32_t rank = block_rank<THREADS>(eq, sh, phase, tot);
+    if (t < n) mask[t] = (T_eff > 0 && (key > tau || (eq && eq_base + rank < need))) ? 1 : 0;
+    eq_base += tot;
+  }
+}
+
+}  // namespace ccd

@@ -25,7 +25,7 @@ static int check_shape(const ccd_shape_t* s, int need) {
   if (s->B < 1 || s->L < 1 || s->Hkv < 1) return CCD_EINVAL;
   if (s->n_valid < 1 || s->k < 1 || s->k > s->n_valid) return CCD_EINVAL;
   if ((int64_t)s->B * s->L * s->Hkv > (int64_t)1 << 24) return CCD_EINVAL;
-  if (s->n_valid > (1 << 24)) return CCD_EINVAL;
+  if (s->n_valid > select_max_tokens()) return CCD_EUNSUPPORTED;
   if (need == 0) return CCD_OK;
   if (s->n_cap < s->n_valid) return CCD_EINVAL;
   if (s->dtype != CCD_FP32 && s->dtype != CCD_BF16) return CCD_EUNSUPPORTED;
@@ -77,8 +77,8 @@ ScorePlan plan_score(const Dims& D) {
   ScorePlan pl{};
   pl.use_mfma = (D.dtype == CCD_BF16 && g_score_path != 1) ? 1 : 0;
   if (pl.use_mfma) {
-    pl.slice1 = 512;
-    pl.slice2 = 512;   // multiple of 64, at most mfma_max_slice2()
+    pl.slice1 = 1024;
+    pl.slice2 = 1024;   // multiple of 32, at most mfma_max_slice()
   } else {
     pl.slice1 = kMinSlice;
     pl.slice2 = 256;   // one token per thread
@@ -89,7 +89,7 @@ ScorePlan plan_score(const Dims& D) {
 }
 
 struct Workspace {
-  size_t off_part, off_lse, off_u, off_scores, total;
+  size_t off_part, off_lse, off_u, off_mask, total;
 };
 
 // The layout does not depend on the kernel path, so a workspace sized once serves either.
@@ -100,7 +100,7 @@ static Workspace layout_workspace(const Dims& D) {
   w.off_part = off;   off = align_up(off + (size_t)D.units * max_slices * D.GP * sizeof(float2), 256);
   w.off_lse = off;    off = align_up(off + (size_t)D.units * D.GP * sizeof(float), 256);
   w.off_u = off;      off = align_up(off + (size_t)D.units * D.n * sizeof(float), 256);
-  w.off_scores = off; off = align_up(off + (size_t)D.units * D.n * sizeof(float), 256);
+  w.off_mask = off;   off = align_up(off + (size_t)D.units * D.n, 256);
   w.total = off;
   return w;
 }
@@ -184,8 +184,10 @@ int ccd_score(const ccd_shape_t* shape, const void* Q_cat, const void* K, const 
   if (rc != CCD_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
+  uint8_t* mask = reinterpret_cast<uint8_t*>(ws + w.off_mask);
+  if (D.T > 0) launch_nuc_mask(D, novelty, mask, st);
   run_cap_scores(D, pl, w, Q_cat, K, ws, st, false);
-  launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), novelty, scores, nullptr, st);
+  launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), mask, scores, nullptr, st);
   return launch_status();
 }
 
@@ -227,10 +229,11 @@ int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, 
   if (shape->n_valid < shape->n_cap || shape->n_valid <= shape->k) return CCD_NOOP;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  float* scores = scores_opt ? scores_opt : reinterpret_cast<float*>(ws + w.off_scores);
+  uint8_t* mask = reinterpret_cast<uint8_t*>(ws + w.off_mask);
   g_prof.mark(-1, st);
+  if (D.T > 0) launch_nuc_mask(D, novelty, mask, st);
   run_cap_scores(D, pl, w, Q_cat, K, ws, st, true);
-  launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), novelty, scores, keep_idx, st);
+  launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), mask, scores_opt, keep_idx, st);
   g_prof.mark(kStSelect, st);
   const bool per_head = shape->nov_stride_l != 0 || shape->nov_stride_h != 0;
   launch_compact(D, K, V, keep_idx, K, V, per_head ? novelty : nullptr, st);
