@@ -3,8 +3,11 @@
 
 A step is one ccd_compress call over one full pot of the headline configuration (32 layers x 8 KV heads
 x 128, 32 query heads, pot 4096 -> 2048, 64 CaP query tokens, T = 1024 NuC slots, max-pool window 7, bf16,
-synthetic seeded data).  Steps cycle over a ring of independent pots so that no call finds its cache warm
-from the previous one.  Prints one JSON line.
+synthetic seeded data).  Steps cycle over rings of 3 pots (K, V), 4 catalyst-query sets and 5 novelty vectors
+(coprime periods), so that no call finds its cache warm from the previous one and every call scores its pot
+with queries and novelty it has not been compressed under before: the kept set is then spread over the whole
+pot, as in steady-state streaming where half of the pot is new context, and nearly every row moves.
+Prints one JSON line.
 """
 from __future__ import annotations
 
@@ -28,6 +31,7 @@ def algorithmic_bytes(cfg) -> dict:
     kbytes, qbytes = u * N * d * e, u * GP * d * e
     rows = u * k * d * e
     return {
+        "nuc_mask": cfg.B * N * 5,
         "score_stats": kbytes + qbytes,
         "score_merge": 0,
         "score_prob": kbytes + qbytes + u * N * 4,
@@ -51,7 +55,7 @@ def main() -> int:
     ap.add_argument("--config", default="c3")
     ap.add_argument("--score-path", type=int, default=0, help="0 auto, 1 vector ALU, 2 MFMA")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-units", type=int, default=16, help="units of the workload the CPU oracle is timed on")
+    ap.add_argument("--cpu-units", type=int, default=0, help="units the CPU oracle is timed on (0 = the whole call)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (units shard without communication; see DESIGN.md); "
@@ -73,27 +77,27 @@ def main() -> int:
             return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(dev)
         return torch.from_numpy(a).to(dev)
 
-    host0 = synth.make_inputs(cfg)                       # pot 0: host-generated, also feeds the CPU baseline
-    pots = [{k: upload(v) for k, v in host0.items()}]
+    host0 = synth.make_inputs(cfg)                       # set 0: host-generated, also feeds the CPU baseline
+    dev0 = {k: upload(v) for k, v in host0.items()}
     tdt = torch.float32 if cfg.dtype == "fp32" else torch.bfloat16
-    for r in range(1, args.ring):                        # further pots: same recipe drawn on the device
-        g = torch.Generator(device=dev).manual_seed(1000 * cfg.seed + r)
-        pot = {
-            "Q_cat": torch.randn((cfg.B, cfg.L, cfg.Hq, cfg.P, cfg.d), generator=g, device=dev, dtype=torch.float32).to(tdt),
-            "K": torch.randn((cfg.B, cfg.L, cfg.Hkv, cfg.N, cfg.d), generator=g, device=dev, dtype=torch.float32).to(tdt),
-            "V": torch.randn((cfg.B, cfg.L, cfg.Hkv, cfg.N, cfg.d), generator=g, device=dev, dtype=torch.float32).to(tdt),
-            "novelty": torch.rand((cfg.B, cfg.N), generator=g, device=dev, dtype=torch.float32),
-        }
-        pots.append(pot)
-    shape = ip.make_shape(pots[0]["Q_cat"], pots[0]["K"], pots[0]["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w,
-                          pool_mode=ip.CCD_POOL_MAX)
+    g = torch.Generator(device=dev).manual_seed(1000 * cfg.seed)
+
+    def randn(*shape):                                   # further sets: same recipe drawn on the device
+        return torch.randn(shape, generator=g, device=dev, dtype=torch.float32).to(tdt)
+
+    pots = [(dev0["K"], dev0["V"])] + [(randn(cfg.B, cfg.L, cfg.Hkv, cfg.N, cfg.d), randn(cfg.B, cfg.L, cfg.Hkv, cfg.N, cfg.d))
+                                       for _ in range(1, args.ring)]
+    qsets = [dev0["Q_cat"]] + [randn(cfg.B, cfg.L, cfg.Hq, cfg.P, cfg.d) for _ in range(args.ring)]
+    novs = [dev0["novelty"]] + [torch.rand((cfg.B, cfg.N), generator=g, device=dev, dtype=torch.float32)
+                                for _ in range(args.ring + 1)]
+    shape = ip.make_shape(qsets[0], pots[0][0], novs[0], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=ip.CCD_POOL_MAX)
     ws = ip.alloc_workspace(shape)
     keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream()
 
     def step(i):
-        p = pots[i % len(pots)]
-        rc = ip.ccd_compress(shape, p["Q_cat"], p["K"], p["V"], p["novelty"], keep, ws, stream=stream)
+        K, V = pots[i % len(pots)]
+        rc = ip.ccd_compress(shape, qsets[i % len(qsets)], K, V, novs[i % len(novs)], keep, ws, stream=stream)
         assert rc == ip.CCD_OK, rc
 
     for i in range(args.warmup):
@@ -113,6 +117,9 @@ def main() -> int:
     stage_ms, calls = ip.ccd_profile_collect()
     ip.ccd_profile_enable(False)
     stage_avg_us = {k: 1e3 * v / max(calls, 1) for k, v in stage_ms.items()}
+
+    # how much of the cache the last call actually moved (rows with keep_idx[j] != j)
+    moved = float((keep.to(torch.int64) != torch.arange(cfg.k, device=dev)).float().mean().item())
 
     ab = algorithmic_bytes(cfg)
     dom = max(stage_avg_us, key=stage_avg_us.get)
@@ -138,9 +145,9 @@ def main() -> int:
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B{cfg.B} L{cfg.L} Hq{cfg.Hq} Hkv{cfg.Hkv} d{cfg.d} N{cfg.N}->k{cfg.k} "
-                               f"P{cfg.P} T{cfg.T} pool{cfg.w}", "ring_pots": len(pots), "score_path": args.score_path},
+                               f"P{cfg.P} T{cfg.T} pool{cfg.w}", "ring": [len(pots), len(qsets), len(novs)], "score_path": args.score_path},
         "call_hbm": {"algorithmic_bytes": ab["call"], "achieved_GBps": call_gbps, "frac_of_peak": call_gbps / HBM_PEAK_GBPS},
-        "stage_avg_us": stage_avg_us,
+        "stage_avg_us": stage_avg_us, "moved_row_fraction": moved,
         "roofline": roof,
     }
 
@@ -151,7 +158,7 @@ def main() -> int:
             threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             threads = os.cpu_count() or 1
-        n_units = min(args.cpu_units, cfg.units)
+        n_units = cfg.units if args.cpu_units <= 0 else min(args.cpu_units, cfg.units)
         sample = [(u // (cfg.L * cfg.Hkv), (u // cfg.Hkv) % cfg.L, u % cfg.Hkv)
                   for u in np.linspace(0, cfg.units - 1, n_units).astype(int)]
         c0 = time.perf_counter()

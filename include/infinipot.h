@@ -109,8 +109,8 @@ CCD_API int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, v
 CCD_API int ccd_set_score_path(int path);
 
 /* Per-kernel timing of ccd_compress for benchmarks (host-side aid, off by default).  While enabled, each
- * ccd_compress call records a HIP event on the caller's stream before its first kernel and after every kernel
- * (events are created on demand and reused; nothing else changes).  ccd_profile_collect waits for the recorded
+ * kernel of ccd_compress is bracketed by two HIP events on the stream it runs on (events are created on demand
+ * and reused; nothing else changes).  ccd_profile_collect waits for the recorded
  * events, adds up the elapsed milliseconds per stage into stage_ms[ccd_profile_stages()] (host array) and stores
  * the number of calls covered in *calls (host), then forgets them.  Stage i is named ccd_profile_stage_name(i).
  * Not thread safe; meant for one stream. */

@@ -21,7 +21,7 @@ __global__ __launch_bounds__(kCpThreads) void compact_rows_kernel(Dims D, const 
                                                                   char* Vdst) {
   constexpr int kLanesPerRow = ROWB / 16;
   constexpr int kRowsPerPass = kCpThreads / kLanesPerRow;
-  const int unit = blockIdx.x >> 1;
+  const int unit = D.unit0 + (blockIdx.x >> 1);
   const bool isV = blockIdx.x & 1;
   const int64_t ubytes = kv_offset(D, decode_unit(D, unit)) * (int64_t)(ROWB / D.d);
   const char* src = (isV ? Vsrc : Ksrc) + ubytes;
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(kCpThreads) void compact_rows_kernel(Dims D, const 
 // per-head novelty carried with the cache: nov[j] <- nov[keep_idx[j]], same chunk discipline
 __global__ __launch_bounds__(kCpThreads) void compact_novelty_kernel(Dims D, const int32_t* __restrict__ keep_idx,
                                                                      float* novelty) {
-  const int unit = blockIdx.x;
+  const int unit = D.unit0 + blockIdx.x;
   float* nov = novelty + nov_offset(D, decode_unit(D, unit));
   const int32_t* keep = keep_idx + (int64_t)unit * D.k;
   for (int base = 0; base < D.k; base += kCpThreads) {
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(kCpThreads) void compact_novelty_kernel(Dims D, con
 void launch_compact(const Dims& D, const void* Ksrc, const void* Vsrc, const int32_t* keep_idx, void* Kdst, void* Vdst,
                     float* novelty, hipStream_t s) {
   const int rowb = D.d * (D.dtype == 0 ? 4 : 2);
-  dim3 grid(2u * D.units), block(kCpThreads);
+  dim3 grid(2u * D.units_run), block(kCpThreads);
 #define CCD_LAUNCH(RB)                                                                                             \
   hipLaunchKernelGGL((compact_rows_kernel<RB>), grid, block, 0, s, D, (const char*)Ksrc, (const char*)Vsrc, keep_idx, \
                      (char*)Kdst, (char*)Vdst)
@@ -87,7 +87,7 @@ void launch_compact(const Dims& D, const void* Ksrc, const void* Vsrc, const int
   else CCD_LAUNCH(512);
 #undef CCD_LAUNCH
   if (novelty != nullptr)
-    hipLaunchKernelGGL(compact_novelty_kernel, dim3(D.units), block, 0, s, D, keep_idx, novelty);
+    hipLaunchKernelGGL(compact_novelty_kernel, dim3(D.units_run), block, 0, s, D, keep_idx, novelty);
 }
 
 }  // namespace ccd

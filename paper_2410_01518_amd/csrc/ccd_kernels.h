@@ -15,6 +15,7 @@ struct Dims {
   int pool_w, pool_mode;
   int dtype;    // 0 fp32, 1 bf16
   int units;    // B * L * Hkv
+  int unit0, units_run;   // the range of units one launch covers (a call may be split into chunks)
   float scale_log2;  // logit scale times log2(e): probabilities are computed with exp2
   int64_t kv_sb, kv_sl, kv_sh;
   int64_t q_sb, q_sl, q_sh;

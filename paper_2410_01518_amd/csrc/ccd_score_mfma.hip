@@ -43,9 +43,9 @@ __device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 
 // blocks with the same residue mod 8 and share that XCD's L2 for their query fragments.
 __device__ __forceinline__ bool decode_block(const Dims& D, int n_slices, int& unit, int& slice) {
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-  unit = (j / n_slices) * 8 + xcd;
+  unit = (j / n_slices) * 8 + xcd;     // index inside the launch's range of units
   slice = j % n_slices;
-  return unit < D.units;
+  return unit < D.units_run;
 }
 
 // K tiles go from HBM straight into LDS (global_load_lds_dwordx4): one wave instruction moves 64 x 16 bytes to
@@ -207,7 +207,8 @@ __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl
   if (!decode_block(D, n_slices, unit, slice)) return;
   // pass 2 walks the units backwards: the keys pass 1 read last are the ones most likely still held by the
   // memory-side cache
-  if (PASS == 2) unit = D.units - 1 - unit;
+  if (PASS == 2) unit = D.units_run - 1 - unit;
+  unit += D.unit0;
   const UnitIdx ui = decode_unit(D, unit);
   const uint16_t* Ku = K + kv_offset(D, ui);
   const int t0 = slice * slice_len, t1 = min(D.n, t0 + slice_len);
@@ -354,7 +355,7 @@ __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl
 int mfma_max_slice() { return kMaxSlice; }
 
 void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s) {
-  dim3 grid((unsigned)((D.units + 7) / 8 * 8) * pl.n_slices1), block(kMT);
+  dim3 grid((unsigned)((D.units_run + 7) / 8 * 8) * pl.n_slices1), block(kMT);
   if (D.d == 64)
     hipLaunchKernelGGL((score_pass_kernel<64, 1>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
                        (float*)nullptr);
@@ -365,7 +366,7 @@ void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const 
 
 void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float2* part, float* u,
                       hipStream_t s) {
-  dim3 grid((unsigned)((D.units + 7) / 8 * 8) * pl.n_slices2), block(kMT);
+  dim3 grid((unsigned)((D.units_run + 7) / 8 * 8) * pl.n_slices2), block(kMT);
   if (D.d == 64)
     hipLaunchKernelGGL((score_pass_kernel<64, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
                        const_cast<float2*>(part), u);

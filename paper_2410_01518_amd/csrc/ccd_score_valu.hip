@@ -20,7 +20,7 @@ template <typename T, int HD>
 __global__ __launch_bounds__(kThreads) void stats_valu_kernel(Dims D, ScorePlan pl, const T* __restrict__ Q,
                                                               const T* __restrict__ K, float2* __restrict__ part) {
   __shared__ float4 Ks[kTokTile][HD / 4];
-  const int slice = blockIdx.x % pl.n_slices1, unit = blockIdx.x / pl.n_slices1, tid = threadIdx.x;
+  const int slice = blockIdx.x % pl.n_slices1, unit = D.unit0 + blockIdx.x / pl.n_slices1, tid = threadIdx.x;
   const UnitIdx ui = decode_unit(D, unit);
   const T* Ku = K + kv_offset(D, ui);
   const int t0 = slice * pl.slice1;
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kThreads) void stats_valu_kernel(Dims D, ScorePlan 
 __global__ __launch_bounds__(kThreads) void merge_kernel(Dims D, ScorePlan pl, const float2* __restrict__ part,
                                                          float* __restrict__ lse2) {
   const int qblocks = (D.GP + kThreads - 1) / kThreads;
-  const int unit = blockIdx.x / qblocks;
+  const int unit = D.unit0 + blockIdx.x / qblocks;
   const int q = (blockIdx.x % qblocks) * kThreads + threadIdx.x;
   if (q >= D.GP) return;
   const float2* p = part + (int64_t)unit * pl.n_slices1 * D.GP + q;
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kThreads) void prob_valu_kernel(Dims D, ScorePlan p
                                                              float* __restrict__ u) {
   __shared__ float4 Qs[kQryTile][HD / 4];
   __shared__ float Ls[kQryTile];
-  const int unit = blockIdx.x / pl.n_slices2, tid = threadIdx.x;
+  const int unit = D.unit0 + blockIdx.x / pl.n_slices2, tid = threadIdx.x;
   const UnitIdx ui = decode_unit(D, unit);
   const int tok = (blockIdx.x % pl.n_slices2) * kThreads + tid;   // one token per thread
   const bool active = tok < D.n;
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(kThreads) void prob_valu_kernel(Dims D, ScorePlan p
 }  // namespace
 
 void launch_stats_valu(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s) {
-  dim3 grid((unsigned)pl.n_slices1 * D.units), block(kThreads);
+  dim3 grid((unsigned)pl.n_slices1 * D.units_run), block(kThreads);
 #define CCD_LAUNCH(T, HD) \
   hipLaunchKernelGGL((stats_valu_kernel<T, HD>), grid, block, 0, s, D, pl, (const T*)Q, (const T*)K, part)
   if (D.dtype == 0) { if (D.d == 64) CCD_LAUNCH(float, 64); else CCD_LAUNCH(float, 128); }
@@ -148,13 +148,13 @@ void launch_stats_valu(const Dims& D, const ScorePlan& pl, const void* Q, const 
 }
 
 void launch_merge(const Dims& D, const ScorePlan& pl, const float2* part, float* lse2, hipStream_t s) {
-  dim3 grid((unsigned)((D.GP + kThreads - 1) / kThreads) * D.units), block(kThreads);
+  dim3 grid((unsigned)((D.GP + kThreads - 1) / kThreads) * D.units_run), block(kThreads);
   hipLaunchKernelGGL(merge_kernel, grid, block, 0, s, D, pl, part, lse2);
 }
 
 void launch_prob_valu(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float* lse2, float* u,
                       hipStream_t s) {
-  dim3 grid((unsigned)pl.n_slices2 * D.units), block(kThreads);
+  dim3 grid((unsigned)pl.n_slices2 * D.units_run), block(kThreads);
 #define CCD_LAUNCH(T, HD) \
   hipLaunchKernelGGL((prob_valu_kernel<T, HD>), grid, block, 0, s, D, pl, (const T*)Q, (const T*)K, lse2, u)
   if (D.dtype == 0) { if (D.d == 64) CCD_LAUNCH(float, 64); else CCD_LAUNCH(float, 128); }

@@ -45,7 +45,7 @@ __global__ __launch_bounds__(kSelThreads) void finalize_select_kernel(Dims D, co
                                                                       const uint8_t* __restrict__ mask, float* scores,
                                                                       int32_t* __restrict__ keep_idx) {
   __shared__ TopkShared<kSelThreads> sh;
-  const int unit = blockIdx.x, tid = threadIdx.x, n = D.n;
+  const int unit = D.unit0 + blockIdx.x, tid = threadIdx.x, n = D.n;
   int phase = 0;
   float sc[KPT];
   if (u != nullptr) {
@@ -106,7 +106,7 @@ void launch_nuc_mask(const Dims& D, const float* novelty, uint8_t* mask, hipStre
 
 void launch_finalize_select(const Dims& D, const float* u, const uint8_t* mask, float* scores, int32_t* keep_idx,
                             hipStream_t s) {
-  const dim3 grid(D.units), block(kSelThreads);
+  const dim3 grid(D.units_run), block(kSelThreads);
   const int kpt = (D.n + kSelThreads - 1) / kSelThreads;
 #define CCD_LAUNCH(KPT) hipLaunchKernelGGL((finalize_select_kernel<KPT>), grid, block, 0, s, D, u, mask, scores, keep_idx)
   if (kpt <= 4) CCD_LAUNCH(4);

@@ -63,6 +63,8 @@ static Dims make_dims(const ccd_shape_t* s) {
   D.GP = D.G * s->P;
   D.pool_w = s->pool_w; D.pool_mode = s->pool_mode; D.dtype = s->dtype;
   D.units = s->B * s->L * s->Hkv;
+  D.unit0 = 0;
+  D.units_run = D.units;
   const double scale = s->scale > 0.f ? (double)s->scale : 1.0 / sqrt((double)(s->d > 0 ? s->d : 1));
   D.scale_log2 = (float)(scale * 1.4426950408889634074);
   D.kv_sb = s->kv_stride_b; D.kv_sl = s->kv_stride_l; D.kv_sh = s->kv_stride_h;
@@ -112,49 +114,64 @@ static int check_workspace(const Workspace& w, const void* ws, size_t ws_bytes) 
 }
 
 // ---- optional per-kernel timing of ccd_compress -------------------------------------------------------
-enum Stage { kStStats = 0, kStMerge, kStProb, kStSelect, kStCompact, kNumStages };
-static const char* const kStageNames[kNumStages] = {"score_stats", "score_merge", "score_prob", "select", "compact"};
+enum Stage { kStNuc = 0, kStStats, kStMerge, kStProb, kStSelect, kStCompact, kNumStages };
+static const char* const kStageNames[kNumStages] = {"nuc_mask", "score_stats", "score_merge", "score_prob", "select",
+                                                    "compact"};
 
+// Every profiled launch is bracketed by two events on the stream it runs on.
 struct Profiler {
   bool on = false;
   std::vector<hipEvent_t> pool;       // every event ever created
   size_t used = 0;                    // events handed out since the last collect
-  std::vector<int> marks;             // stage that ENDS at event i (-1: start of a call)
-  void mark(int stage, hipStream_t st) {
-    if (!on) return;
+  std::vector<int> stage_of;          // stage of the span that starts at event 2*i
+  int64_t calls = 0;
+  hipEvent_t next() {
     if (used == pool.size()) {
       hipEvent_t e;
-      if (hipEventCreate(&e) != hipSuccess) return;
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
       pool.push_back(e);
     }
-    (void)hipEventRecord(pool[used], st);
-    marks.resize(used + 1);
-    marks[used] = stage;
-    ++used;
+    return pool[used++];
+  }
+  void begin(int stage, hipStream_t st) {
+    if (!on) return;
+    hipEvent_t e = next();
+    if (e) (void)hipEventRecord(e, st);
+    stage_of.push_back(stage);
+  }
+  void end(hipStream_t st) {
+    if (!on) return;
+    hipEvent_t e = next();
+    if (e) (void)hipEventRecord(e, st);
   }
 };
 static Profiler g_prof;
 
 static int launch_status() { return hipGetLastError() == hipSuccess ? CCD_OK : CCD_ELAUNCH; }
 
-// steps a2-a3: raw CaP score u[unit, t]
+// steps a2-a3: raw CaP score u[unit, t] for the units D.unit0 .. D.unit0 + D.units_run - 1
 static void run_cap_scores(const Dims& D, const ScorePlan& pl, const Workspace& w, const void* Q, const void* K,
-                           char* ws, hipStream_t st, bool profile) {
+                           char* ws, hipStream_t st) {
   float2* part = reinterpret_cast<float2*>(ws + w.off_part);
   float* lse2 = reinterpret_cast<float*>(ws + w.off_lse);
   float* u = reinterpret_cast<float*>(ws + w.off_u);
   if (pl.use_mfma) {
+    g_prof.begin(kStStats, st);
     launch_stats_mfma(D, pl, Q, K, part, st);
-    if (profile) g_prof.mark(kStStats, st);
+    g_prof.end(st);
+    g_prof.begin(kStProb, st);
     launch_prob_mfma(D, pl, Q, K, part, u, st);
-    if (profile) g_prof.mark(kStProb, st);
+    g_prof.end(st);
   } else {
+    g_prof.begin(kStStats, st);
     launch_stats_valu(D, pl, Q, K, part, st);
-    if (profile) g_prof.mark(kStStats, st);
+    g_prof.end(st);
+    g_prof.begin(kStMerge, st);
     launch_merge(D, pl, part, lse2, st);
-    if (profile) g_prof.mark(kStMerge, st);
+    g_prof.end(st);
+    g_prof.begin(kStProb, st);
     launch_prob_valu(D, pl, Q, K, lse2, u, st);
-    if (profile) g_prof.mark(kStProb, st);
+    g_prof.end(st);
   }
 }
 
@@ -186,7 +203,7 @@ int ccd_score(const ccd_shape_t* shape, const void* Q_cat, const void* K, const 
   char* ws = static_cast<char*>(workspace);
   uint8_t* mask = reinterpret_cast<uint8_t*>(ws + w.off_mask);
   if (D.T > 0) launch_nuc_mask(D, novelty, mask, st);
-  run_cap_scores(D, pl, w, Q_cat, K, ws, st, false);
+  run_cap_scores(D, pl, w, Q_cat, K, ws, st);
   launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), mask, scores, nullptr, st);
   return launch_status();
 }
@@ -196,7 +213,8 @@ int ccd_select(const ccd_shape_t* shape, const float* scores, int32_t* keep_idx,
   if (rc != CCD_OK) return rc;
   if (scores == nullptr || keep_idx == nullptr) return CCD_EINVAL;
   const Dims D = make_dims(shape);
-  launch_finalize_select(D, nullptr, nullptr, const_cast<float*>(scores), keep_idx, static_cast<hipStream_t>(hip_stream));
+  launch_finalize_select(D, nullptr, nullptr, const_cast<float*>(scores), keep_idx,
+                         static_cast<hipStream_t>(hip_stream));
   return launch_status();
 }
 
@@ -230,14 +248,21 @@ int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
   uint8_t* mask = reinterpret_cast<uint8_t*>(ws + w.off_mask);
-  g_prof.mark(-1, st);
-  if (D.T > 0) launch_nuc_mask(D, novelty, mask, st);
-  run_cap_scores(D, pl, w, Q_cat, K, ws, st, true);
-  launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), mask, scores_opt, keep_idx, st);
-  g_prof.mark(kStSelect, st);
+  const float* u = reinterpret_cast<const float*>(ws + w.off_u);
   const bool per_head = shape->nov_stride_l != 0 || shape->nov_stride_h != 0;
+  if (g_prof.on) ++g_prof.calls;
+  if (D.T > 0) {
+    g_prof.begin(kStNuc, st);
+    launch_nuc_mask(D, novelty, mask, st);
+    g_prof.end(st);
+  }
+  run_cap_scores(D, pl, w, Q_cat, K, ws, st);
+  g_prof.begin(kStSelect, st);
+  launch_finalize_select(D, u, mask, scores_opt, keep_idx, st);
+  g_prof.end(st);
+  g_prof.begin(kStCompact, st);
   launch_compact(D, K, V, keep_idx, K, V, per_head ? novelty : nullptr, st);
-  g_prof.mark(kStCompact, st);
+  g_prof.end(st);
   return launch_status();
 }
 
@@ -261,17 +286,17 @@ const char* ccd_profile_stage_name(int stage) {
 int ccd_profile_collect(double* stage_ms, int64_t* calls) {
   if (stage_ms == nullptr || calls == nullptr) return CCD_EINVAL;
   for (int i = 0; i < kNumStages; ++i) stage_ms[i] = 0.0;
-  *calls = 0;
-  if (g_prof.used > 0 && hipEventSynchronize(g_prof.pool[g_prof.used - 1]) != hipSuccess) return CCD_ELAUNCH;
-  for (size_t i = 0; i < g_prof.used; ++i) {
-    const int stage = g_prof.marks[i];
-    if (stage < 0) { ++*calls; continue; }
+  *calls = g_prof.calls;
+  int rc = CCD_OK;
+  for (size_t i = 0; i + 1 < g_prof.used && i / 2 < g_prof.stage_of.size(); i += 2) {
+    if (hipEventSynchronize(g_prof.pool[i + 1]) != hipSuccess) { rc = CCD_ELAUNCH; break; }
     float ms = 0.f;
-    if (i > 0 && hipEventElapsedTime(&ms, g_prof.pool[i - 1], g_prof.pool[i]) == hipSuccess) stage_ms[stage] += ms;
+    if (hipEventElapsedTime(&ms, g_prof.pool[i], g_prof.pool[i + 1]) == hipSuccess) stage_ms[g_prof.stage_of[i / 2]] += ms;
   }
   g_prof.used = 0;
-  g_prof.marks.clear();
-  return CCD_OK;
+  g_prof.stage_of.clear();
+  g_prof.calls = 0;
+  return rc;
 }
 
 const char* ccd_strerror(int code) {
