@@ -22,6 +22,10 @@ import numpy as np
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 VALU_FP32_PEAK_TFLOPS = 157.3
+# HBM bytes per launch on the headline config from the committed rocprofv3 counter runs
+# (profiles/ccd_compress_c3_hbm_traffic.md: read requests x 128 B + WRITE_SIZE; a plain copy reads factor 1.00)
+MEASURED_TRAFFIC_C3 = {"score_stats": 287_500_000, "score_prob": 291_700_000, "compact": 539_200_000,
+                       "select": 4_300_000, "nuc_mask": 17_000}
 
 
 def algorithmic_bytes(cfg) -> dict:
@@ -55,6 +59,9 @@ def main() -> int:
     ap.add_argument("--config", default="c3")
     ap.add_argument("--score-path", type=int, default=0, help="0 auto, 1 vector ALU, 2 MFMA")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy a few times (reference for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--cpu-units", type=int, default=0, help="units the CPU oracle is timed on (0 = the whole call)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -94,6 +101,14 @@ def main() -> int:
     ws = ip.alloc_workspace(shape)
     keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream()
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def step(i):
         K, V = pots[i % len(pots)]
@@ -135,7 +150,8 @@ def main() -> int:
     else:
         roof = {"kernel": dom, "bound": "hbm", "achieved": ab[dom] / dom_s / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = MEASURED_TRAFFIC_C3.get(dom) if cfg.name == "c3" and args.score_path == 0 else None
+    roof["traffic_source"] = "profiles/ccd_compress_c3_hbm_traffic.md" if roof["traffic"] else None
     roof["avg_us"] = stage_avg_us[dom]
 
     call_gbps = ab["call"] / (ms_per_step * 1e-3) / 1e9
