@@ -57,7 +57,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--ring", type=int, default=3, help="independent pots cycled through")
     ap.add_argument("--config", default="c3")
-    ap.add_argument("--score-path", type=int, default=0, help="0 auto, 1 vector ALU, 2 MFMA")
+    ap.add_argument("--score-path", type=int, default=0, help="0 auto (matrix cores for bf16), 1 vector ALUs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for scaling rocprofv3's "

@@ -103,9 +103,8 @@ CCD_API int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, v
                  float* scores_opt, int32_t* keep_idx, void* workspace, size_t workspace_bytes,
                  void* hip_stream);
 
-/* Process-wide choice of the kernels that compute the attention logits of Eq. 2: 0 = automatic (matrix
- * cores for bf16, vector ALUs for fp32), 1 = vector ALUs, 2 = matrix cores where the dtype allows.  Meant
- * for profiling one path against the other; returns CCD_EINVAL for any other value. */
+/* Process-wide choice of kernels: 0 = automatic (bf16: matrix cores; fp32: vector ALUs), 1 = vector ALUs
+ * everywhere.  Meant for profiling one path against the other; returns CCD_EINVAL for any other value. */
 CCD_API int ccd_set_score_path(int path);
 
 /* Per-kernel timing of ccd_compress for benchmarks (host-side aid, off by default).  While enabled, each

@@ -18,336 +18,24 @@
 // The path is bound by the vector ALU (fma + exp2 + add per logit), not by the matrix cores, so the loop is
 // software pipelined inside each wave: the MFMAs of tile s+1 are issued between the ALU instructions that
 // consume tile s, and the scheduler is told to keep that interleave.
-#include "ccd_common.h"
+#include "ccd_score_mfma.h"
 
 namespace ccd {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-constexpr int kMT = 256;            // threads per workgroup (4 waves)
-constexpr int kStep = 32;           // tokens per tile
-constexpr int kBatch = 3;           // tiles per DMA batch
-constexpr int kDepth = 2 * kBatch;  // LDS ring slots: one batch is consumed while the other one lands
-constexpr int kQB = 2;              // 32-query blocks per wave
-constexpr int kQPerPass = 4 * kQB * 32;   // query rows a workgroup covers per sweep over its slice
-constexpr int kMaxSlice = 1024;     // slice limit (per-wave partial sums of pass 2 live in LDS)
-constexpr float kNegHuge = -1.0e30f;
-
-// row of the 32x32 accumulator tile held in register r by a lane of half `half` (lane / 32)
-__device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
-
-// block -> (unit, slice): consecutive blocks go to different XCDs, so the slices of one unit are placed on
-// blocks with the same residue mod 8 and share that XCD's L2 for their query fragments.
-__device__ __forceinline__ bool decode_block(const Dims& D, int n_slices, int& unit, int& slice) {
-  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-  unit = (j / n_slices) * 8 + xcd;     // index inside the launch's range of units
-  slice = j % n_slices;
-  return unit < D.units_run;
-}
-
-// K tiles go from HBM straight into LDS (global_load_lds_dwordx4): one wave instruction moves 64 x 16 bytes to
-// consecutive LDS addresses starting at M0, each lane choosing its own global address.  No padding is possible
-// in that scheme, so bank conflicts of the fragment reads are avoided by an XOR swizzle instead: the 16-byte
-// chunk c of row r is stored at chunk position c ^ swz(r) of that row.
-template <int HD>
-struct Tiles {
-  static constexpr int kRowBytes = HD * 2;
-  static constexpr int kChunksPerRow = HD / 8;                       // 16-byte chunks: 16 or 8
-  static constexpr int kRowsPerInstr = 64 / kChunksPerRow;           // rows one wave instruction moves
-  static constexpr int kInstrPerTile = kStep / kRowsPerInstr;        // 8 or 4
-  static constexpr int kInstrPerWave = kInstrPerTile / 4;            // 2 or 1
-  static constexpr int kSlotBytes = kStep * kRowBytes;
-  __device__ static __forceinline__ int swz(int row) { return HD == 128 ? (row & 15) : ((row >> 1) & 7); }
-};
-
-__device__ __forceinline__ void dma16(const void* gbase, uint32_t voff, uint32_t lds_addr) {
-  // gbase and lds_addr are wave-uniform; lane L's 16 bytes land at lds_addr + 16 * L
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase)
-               : "memory");
-}
-
-// DMA loads to LDS do not retire in issue order (measured: waiting for "all but the youngest n" let stale tiles
-// through), so the only safe wait is for everything this wave has in flight.
-__device__ __forceinline__ void wait_all_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
-// this wave's share of tile `tile` of the slice -> ring slot at LDS byte address slot_addr.  Rows past the end
-// of the pot re-read the last valid row: they are masked (pass 1) or never stored (pass 2).
-template <int HD>
-__device__ __forceinline__ void issue_tile(const uint16_t* Ku, int t0, int t1, int tile, uint32_t slot_addr, int wave,
-                                           int lane) {
-  const int tile_t0 = t0 + tile * kStep;
-  const uint16_t* base = Ku + (int64_t)tile_t0 * HD;
-  const int last = t1 - 1 - tile_t0;
-#pragma unroll
-  for (int i = 0; i < Tiles<HD>::kInstrPerWave; ++i) {
-    const int j = wave + 4 * i;
-    const int row = j * Tiles<HD>::kRowsPerInstr + lane / Tiles<HD>::kChunksPerRow;
-    const int c = (lane % Tiles<HD>::kChunksPerRow) ^ Tiles<HD>::swz(row);
-    const uint32_t voff = (uint32_t)(min(row, last) * Tiles<HD>::kRowBytes + c * 16);
-    dma16(base, voff, slot_addr + j * 1024);
-  }
-}
-
-// fragment reads of tile slot SLOT: koff[ks] is the lane's swizzled byte offset inside a slot
-template <int HD, int SLOT>
-__device__ __forceinline__ void load_k_frags(bf16x8 (&a)[HD / 16], const uint8_t* lds, const int (&koff)[HD / 16]) {
-#pragma unroll
-  for (int ks = 0; ks < HD / 16; ++ks)
-    a[ks] = *reinterpret_cast<const bf16x8*>(lds + SLOT * Tiles<HD>::kSlotBytes + koff[ks]);
-}
-
-template <int HD>
-__device__ __forceinline__ void load_q_frags(bf16x8 (&bq)[kQB][HD / 16], const Dims& D, UnitIdx ui, const uint16_t* Q,
-                                             int qbase, int col, int half) {
-#pragma unroll
-  for (int qb = 0; qb < kQB; ++qb) {
-    const int q = qbase + qb * 32 + col;
-    if (q < D.GP) {
-      const uint16_t* qp = Q + q_offset(D, ui, q) + half * 8;
-#pragma unroll
-      for (int ks = 0; ks < HD / 16; ++ks) bq[qb][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
-    } else {
-#pragma unroll
-      for (int ks = 0; ks < HD / 16; ++ks) bq[qb][ks] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-    }
-  }
-}
-
-// logits of one 32-token tile against the wave's 2 x 32 query rows; the two chains alternate so that
-// dependent MFMAs are never adjacent.  PASS 1: D[token][query], PASS 2: D[query][token].
-template <int HD, int PASS>
-__device__ __forceinline__ void logits(floatx16 (&acc)[kQB], const bf16x8 (&a)[HD / 16], const bf16x8 (&bq)[kQB][HD / 16]) {
-#pragma unroll
-  for (int qb = 0; qb < kQB; ++qb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[qb][r] = 0.f;
-#pragma unroll
-  for (int ks = 0; ks < HD / 16; ++ks)
-#pragma unroll
-    for (int qb = 0; qb < kQB; ++qb) {
-      if (PASS == 1) acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bq[qb][ks], acc[qb], 0, 0, 0);
-      else           acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[qb][ks], a[ks], acc[qb], 0, 0, 0);
-    }
-}
-
-// pass 1: fold the 16 token rows a lane holds into its query's running (max, sum); nvalid < 32 masks the tail
-template <bool MASKED>
-__device__ __forceinline__ void fold_stats(floatx16 (&acc)[kQB], float (&m_raw)[kQB], float (&Z)[kQB], float c, int half,
-                                           int nvalid) {
-#pragma unroll
-  for (int qb = 0; qb < kQB; ++qb) {
-    if (MASKED) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        if (acc_row(r, half) >= nvalid) acc[qb][r] = -INFINITY;
-    }
-    float t0 = fmaxf(fmaxf(acc[qb][0], acc[qb][1]), acc[qb][2]);
-    float t1 = fmaxf(fmaxf(acc[qb][3], acc[qb][4]), acc[qb][5]);
-    float t2 = fmaxf(fmaxf(acc[qb][6], acc[qb][7]), acc[qb][8]);
-    float t3 = fmaxf(fmaxf(acc[qb][9], acc[qb][10]), acc[qb][11]);
-    float t4 = fmaxf(fmaxf(acc[qb][12], acc[qb][13]), acc[qb][14]);
-    t0 = fmaxf(fmaxf(t0, t1), t2);
-    t3 = fmaxf(fmaxf(t3, t4), acc[qb][15]);
-    const float m_new = fmaxf(fmaxf(t0, t3), m_raw[qb]);
-    const float negm = -m_new * c;
-    float z0 = Z[qb] * fast_exp2((m_raw[qb] - m_new) * c), z1 = 0.f;   // exact difference first: m may be huge
-    m_raw[qb] = m_new;
-#pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-      z0 += fast_exp2(fmaf(acc[qb][r], c, negm));
-      z1 += fast_exp2(fmaf(acc[qb][r + 1], c, negm));
-    }
-    Z[qb] = z0 + z1;
-  }
-}
-
-// pass 2: probability of the lane's token under its 2 x 16 query rows, summed
-__device__ __forceinline__ float fold_prob(const floatx16 (&acc)[kQB], const float (&neg_lse)[kQB][16], float c) {
-  float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-  for (int qb = 0; qb < kQB; ++qb)
-#pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-      s0 += fast_exp2(fmaf(acc[qb][r], c, neg_lse[qb][r]));
-      s1 += fast_exp2(fmaf(acc[qb][r + 1], c, neg_lse[qb][r + 1]));
-    }
-  return s0 + s1;
-}
-
-// scheduling shape of one pipelined step: the LDS fragment reads first, a run of ALU work on the current tile
-// to cover their latency, then one MFMA of the next tile per group of ALU instructions
-template <int KS, int VALU_LEAD, int VALU_PER_MFMA>
-__device__ __forceinline__ void interleave_hint() {
-  __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);          // DS reads
-  __builtin_amdgcn_sched_group_barrier(0x002, VALU_LEAD, 0);   // VALU
-#pragma unroll
-  for (int i = 0; i < 2 * KS; ++i) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         // MFMA
-    __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_MFMA, 0);
-  }
-}
-
-// PASS 1 writes part[unit][slice][q] = (max2, sum); PASS 2 reads part (all slices), writes u[unit][t].
 template <int HD, int PASS>
 __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl, const uint16_t* __restrict__ Q,
                                                             const uint16_t* __restrict__ K, float2* __restrict__ part,
                                                             float* __restrict__ u) {
-  constexpr int KS = HD / 16;
-  constexpr int SLOTB = Tiles<HD>::kSlotBytes;
-  __shared__ __attribute__((aligned(1024))) uint8_t lds[kDepth * SLOTB];
-  __shared__ float up[PASS == 2 ? 4 : 1][PASS == 2 ? kMaxSlice : 1];   // per-wave partial sums (pass 2)
-  __shared__ float lse_s[PASS == 2 ? kQPerPass : 1];
-
-  const int slice_len = PASS == 1 ? pl.slice1 : pl.slice2;
-  const int n_slices = PASS == 1 ? pl.n_slices1 : pl.n_slices2;
+  __shared__ ScoreLds<HD, PASS> sm;
   int unit, slice;
-  if (!decode_block(D, n_slices, unit, slice)) return;
+  if (!decode_block(D, PASS == 1 ? pl.n_slices1 : pl.n_slices2, unit, slice)) return;
   // pass 2 walks the units backwards: the keys pass 1 read last are the ones most likely still held by the
   // memory-side cache
   if (PASS == 2) unit = D.units_run - 1 - unit;
   unit += D.unit0;
-  const UnitIdx ui = decode_unit(D, unit);
-  const uint16_t* Ku = K + kv_offset(D, ui);
-  const int t0 = slice * slice_len, t1 = min(D.n, t0 + slice_len);
-  const int S = (t1 - t0 + kStep - 1) / kStep;       // tiles in the slice (the last one may be partial)
-  const int S_full = (t1 - t0) / kStep;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63, col = lane & 31, half = lane >> 5;
-  const float c = D.scale_log2;
-  const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
-  int koff[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) koff[ks] = col * Tiles<HD>::kRowBytes + (((2 * ks + half) ^ Tiles<HD>::swz(col)) << 4);
-
-  for (int qc = 0; qc < D.GP; qc += kQPerPass) {
-    // start the K stream first: batch 0 is in flight while the query fragments are fetched
-#pragma unroll
-    for (int i = 0; i < kBatch; ++i)
-      if (i < S) issue_tile<HD>(Ku, t0, t1, i, lds_addr + i * SLOTB, wave, lane);
-
-    bf16x8 bq[kQB][KS];
-    load_q_frags<HD>(bq, D, ui, Q, qc + wave * (kQB * 32), col, half);
-
-    float m_raw[kQB], Z[kQB];
-    float neg_lse[kQB][16];
-    if (PASS == 1) {
-#pragma unroll
-      for (int qb = 0; qb < kQB; ++qb) { m_raw[qb] = kNegHuge; Z[qb] = 0.f; }
-    } else {
-      // merge the per-slice statistics of pass 1 into log2-sum-exp per query (thread = query of this sweep)
-      const int q = qc + threadIdx.x;
-      float lse = INFINITY;
-      if (q < D.GP) {
-        const float2* p = part + (int64_t)unit * pl.n_slices1 * D.GP + q;
-        float M = kNegHuge;
-        for (int j = 0; j < pl.n_slices1; ++j) M = fmaxf(M, p[(int64_t)j * D.GP].x);
-        float z = 0.f;
-        for (int j = 0; j < pl.n_slices1; ++j) {
-          const float2 v = p[(int64_t)j * D.GP];
-          z += v.y * fast_exp2(v.x - M);
-        }
-        lse = M + __log2f(z);
-      }
-      lse_s[threadIdx.x] = lse;
-    }
-    wait_all_dma();
-    __syncthreads();
-#pragma unroll
-    for (int i = kBatch; i < kDepth; ++i)      // batch 1 lands while batch 0 is consumed
-      if (i < S) issue_tile<HD>(Ku, t0, t1, i, lds_addr + i * SLOTB, wave, lane);
-    if (PASS == 2) {
-#pragma unroll
-      for (int qb = 0; qb < kQB; ++qb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) neg_lse[qb][r] = -lse_s[wave * (kQB * 32) + qb * 32 + acc_row(r, half)];
-    }
-    bf16x8 a[KS];
-    floatx16 accA[kQB], accB[kQB];
-    load_k_frags<HD, 0>(a, lds, koff);
-    logits<HD, PASS>(accA, a, bq);
-
-    // Step s (ring slot I = s mod 6) folds tile s on the ALU while the MFMAs of tile s+1 run.  Tiles arrive in
-    // batches of three: the batch that holds tile s+2 must have landed by the end of every step with
-    // s mod 3 == 1 (wait + barrier there, nowhere else); right after that barrier the slots of the batch
-    // consumed before are free, and the next batch (tiles s+4 .. s+6 seen from step s with s mod 3 == 2) is
-    // requested into them.
-#define CCD_STEP(I, CUR, NXT)                                                                     \
-    {                                                                                             \
-      if (s >= S_full) break;                                                                     \
-      if ((I) % kBatch == 2) {                                                                    \
-        _Pragma("unroll") for (int i = 0; i < kBatch; ++i)                                        \
-          if (s + 4 + i < S)                                                                      \
-            issue_tile<HD>(Ku, t0, t1, s + 4 + i, lds_addr + (((I) + 4 + i) % kDepth) * SLOTB, wave, lane); \
-      }                                                                                           \
-      load_k_frags<HD, ((I) + 1) % kDepth>(a, lds, koff);                                         \
-      logits<HD, PASS>(NXT, a, bq);                                                               \
-      if (PASS == 1) {                                                                            \
-        fold_stats<false>(CUR, m_raw, Z, c, half, 32);                                            \
-        interleave_hint<KS, 20, 6>();                                                             \
-      } else {                                                                                    \
-        float us = fold_prob(CUR, neg_lse, c);                                                    \
-        interleave_hint<KS, 14, 5>();                                                             \
-        us += __shfl_xor(us, 32);                                                                 \
-        if (half == 0) {                                                                          \
-          float* dst = &up[wave][s * kStep + col];                                                \
-          *dst = (qc == 0) ? us : *dst + us;                                                      \
-        }                                                                                         \
-      }                                                                                           \
-      if ((I) % kBatch == 1) {                                                                    \
-        wait_all_dma();                                                                           \
-        __builtin_amdgcn_s_barrier();                                                             \
-      }                                                                                           \
-      ++s;                                                                                        \
-    }
-    int s = 0;
-    while (true) {
-      CCD_STEP(0, accA, accB)
-      CCD_STEP(1, accB, accA)
-      CCD_STEP(2, accA, accB)
-      CCD_STEP(3, accB, accA)
-      CCD_STEP(4, accA, accB)
-      CCD_STEP(5, accB, accA)
-    }
-#undef CCD_STEP
-    static_assert(kDepth == 6 && kBatch == 3, "the step sequence above is written out for two batches of three");
-    // the logits of tile S_full - the partial tail tile, if there is one - are in accA or accB by parity
-    if (S > S_full) {
-      if (S_full & 1) {
-#pragma unroll
-        for (int qb = 0; qb < kQB; ++qb) accA[qb] = accB[qb];
-      }
-      if (PASS == 1) {
-        fold_stats<true>(accA, m_raw, Z, c, half, (t1 - t0) - S_full * kStep);
-      } else {
-        float us = fold_prob(accA, neg_lse, c);
-        us += __shfl_xor(us, 32);
-        if (half == 0) {
-          float* dst = &up[wave][S_full * kStep + col];
-          *dst = (qc == 0) ? us : *dst + us;
-        }
-      }
-    }
-    __syncthreads();   // ring, lse_s and up are reused by the next sweep / read below
-
-    if (PASS == 1) {
-      // the two lane halves hold different token rows of the same query: merge, lower half writes
-#pragma unroll
-      for (int qb = 0; qb < kQB; ++qb) {
-        const float m_o = __shfl_xor(m_raw[qb], 32), z_o = __shfl_xor(Z[qb], 32);
-        const float M = fmaxf(m_raw[qb], m_o);
-        const float z = Z[qb] * fast_exp2((m_raw[qb] - M) * c) + z_o * fast_exp2((m_o - M) * c);
-        const int q = qc + wave * (kQB * 32) + qb * 32 + col;
-        if (half == 0 && q < D.GP) part[((int64_t)unit * pl.n_slices1 + slice) * D.GP + q] = make_float2(M * c, z);
-      }
-    }
-  }
-  if (PASS == 2) {
-    float* uu = u + (int64_t)unit * D.n + t0;
-    for (int t = threadIdx.x; t < t1 - t0; t += kMT) uu[t] = (up[0][t] + up[1][t]) + (up[2][t] + up[3][t]);
-  }
+  score_pass_body<HD, PASS>(D, pl, unit, slice, Q, K, part, u, sm);
 }
 
 }  // namespace

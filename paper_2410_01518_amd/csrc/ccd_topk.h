@@ -81,7 +81,7 @@ __device__ __forceinline__ uint32_t block_rank(bool pred, TopkShared<THREADS>& s
 // (keys held in registers), KPT == 0 loops at run time (keys re-read from memory).
 // On return #{key > tau} < kk <= #{key >= tau} and need = kk - #{key > tau}.  Ends with a barrier.
 template <int THREADS, int KPT, class KeyFn>
-__device__ void radix_threshold(KeyFn key_of, int n, uint32_t kk, TopkShared<THREADS>& sh, int& phase, uint32_t& tau,
+__device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk, TopkShared<THREADS>& sh, int& phase, uint32_t& tau,
                                 uint32_t& need) {
   const int tid = threadIdx.x;
   constexpr int kBinsPerThread = kRadixBins / THREADS;
@@ -139,7 +139,7 @@ __device__ void radix_threshold(KeyFn key_of, int n, uint32_t kk, TopkShared<THR
 // The T tokens of largest novelty (Sec. 3.3.3 step 1): mask[t] = 1 for them, 0 otherwise, t < n.  NaN and -inf
 // never qualify; ties go to the lower index.  Every thread of the workgroup must call this.
 template <int THREADS>
-__device__ void nuc_mask_job(const float* __restrict__ nov, uint8_t* __restrict__ mask, int n, int T, TopkShared<THREADS>& sh) {
+__device__ __forceinline__ void nuc_mask_job(const float* __restrict__ nov, uint8_t* __restrict__ mask, int n, int T, TopkShared<THREADS>& sh) {
   const int tid = threadIdx.x;
   int phase = 0;
   uint32_t mine = 0;

@@ -12,7 +12,7 @@
 
 namespace ccd {
 
-static int g_score_path = 0;   // 0 auto, 1 vector ALU, 2 MFMA (profiling comparisons)
+static int g_score_path = 0;   // 0 auto (matrix cores for bf16), 1 vector ALUs everywhere
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -75,12 +75,21 @@ static Dims make_dims(const ccd_shape_t* s) {
 
 constexpr int kMinSlice = 256;   // smallest token slice any plan uses: sizes the per-slice statistics
 
+static ScorePlan plan_mfma(const Dims& D) {
+  ScorePlan pl{};
+  pl.use_mfma = 1;
+  pl.slice1 = 1024;
+  pl.slice2 = 1024;   // multiple of 32, at most mfma_max_slice()
+  pl.n_slices1 = (D.n + pl.slice1 - 1) / pl.slice1;
+  pl.n_slices2 = (D.n + pl.slice2 - 1) / pl.slice2;
+  return pl;
+}
+
 ScorePlan plan_score(const Dims& D) {
   ScorePlan pl{};
   pl.use_mfma = (D.dtype == CCD_BF16 && g_score_path != 1) ? 1 : 0;
   if (pl.use_mfma) {
-    pl.slice1 = 1024;
-    pl.slice2 = 1024;   // multiple of 32, at most mfma_max_slice()
+    return plan_mfma(D);
   } else {
     pl.slice1 = kMinSlice;
     pl.slice2 = 256;   // one token per thread
@@ -146,6 +155,18 @@ struct Profiler {
   }
 };
 static Profiler g_prof;
+
+// compute units of the current device (the persistent kernel launches two workgroups per CU)
+static int device_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
+    if (cus <= 0) cus = 256;
+  }
+  return cus;
+}
 
 static int launch_status() { return hipGetLastError() == hipSuccess ? CCD_OK : CCD_ELAUNCH; }
 
@@ -267,7 +288,7 @@ int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, 
 }
 
 int ccd_set_score_path(int path) {
-  if (path < 0 || path > 2) return CCD_EINVAL;
+  if (path < 0 || path > 1) return CCD_EINVAL;
   g_score_path = path;
   return CCD_OK;
 }
