@@ -41,7 +41,9 @@ void launch_prob_valu(const Dims& D, const ScorePlan& pl, const void* Q, const v
                       hipStream_t s);
 
 // the same two passes on the matrix cores (bf16 only)
-void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s);
+bool stats_hosts_nuc(const Dims& D, const ScorePlan& pl);   // may pass 1 also write the NuC mask?
+void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part,
+                       const float* novelty, uint8_t* nuc_mask, hipStream_t s);
 // (pass 2 merges the per-slice statistics itself: no merge launch on this path)
 void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float2* part, float* u,
                       hipStream_t s);

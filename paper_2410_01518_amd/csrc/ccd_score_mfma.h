@@ -7,9 +7,6 @@ namespace ccd {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-#ifndef CCD_EXP
-#define CCD_EXP 0
-#endif
 constexpr int kMT = 256;            // threads per workgroup (4 waves)
 constexpr int kStep = 32;           // tokens per tile
 constexpr int kBatch = 3;           // tiles per DMA batch
@@ -24,8 +21,8 @@ __device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 
 
 // block -> (unit, slice): consecutive blocks go to different XCDs, so the slices of one unit are placed on
 // blocks with the same residue mod 8 and share that XCD's L2 for their query fragments.
-__device__ __forceinline__ bool decode_block(const Dims& D, int n_slices, int& unit, int& slice) {
-  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+__device__ __forceinline__ bool decode_block(const Dims& D, int blk, int n_slices, int& unit, int& slice) {
+  const int xcd = blk & 7, j = blk >> 3;
   unit = (j / n_slices) * 8 + xcd;     // index inside the launch's range of units
   slice = j % n_slices;
   return unit < D.units_run;
@@ -184,11 +181,13 @@ struct ScoreLds {
 
 // One (unit, token slice) of one pass, executed by a workgroup of kMT threads.  Ends with every thread past a
 // barrier, so the LDS may be reused at once.
-template <int HD, int PASS>
+// side_job() is called once, by every thread, while the first K tiles are in flight (and before the query
+// fragments occupy their registers): a place for a small unrelated job whose memory latency then costs little.
+template <int HD, int PASS, class SideJob>
 __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& pl, int unit, int slice,
                                                 const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
                                                 float2* __restrict__ part, float* __restrict__ u,
-                                                ScoreLds<HD, PASS>& sm) {
+                                                ScoreLds<HD, PASS>& sm, SideJob side_job) {
   constexpr int KS = HD / 16;
   constexpr int SLOTB = Tiles<HD>::kSlotBytes;
   uint8_t* lds = sm.ring;
@@ -214,6 +213,7 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
     for (int i = 0; i < kBatch; ++i)
       if (i < S) issue_tile<HD>(Ku, t0, t1, i, lds_addr + i * SLOTB, wave, lane);
 
+    if (qc == 0) side_job();
     bf16x8 bq[kQB][KS];
     load_q_frags<HD>(bq, D, ui, Q, qc + wave * (kQB * 32), col, half);
 
@@ -263,7 +263,7 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
 #define CCD_STEP(I, CUR, NXT)                                                                     \
     {                                                                                             \
       if (s >= S_full) break;                                                                     \
-      if ((I) % kBatch == 2 && CCD_EXP != 1 && CCD_EXP != 2) {                                     \
+      if ((I) % kBatch == 2) {                                                                    \
         _Pragma("unroll") for (int i = 0; i < kBatch; ++i)                                        \
           if (s + 4 + i < S)                                                                      \
             issue_tile<HD>(Ku, t0, t1, s + 4 + i, lds_addr + (((I) + 4 + i) % kDepth) * SLOTB, wave, lane); \
@@ -284,7 +284,7 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
       }                                                                                           \
       if ((I) % kBatch == 1) {                                                                    \
         wait_all_dma();                                                                           \
-        if (CCD_EXP != 2) __builtin_amdgcn_s_barrier();                                           \
+        __builtin_amdgcn_s_barrier();                                                             \
       }                                                                                           \
       ++s;                                                                                        \
     }

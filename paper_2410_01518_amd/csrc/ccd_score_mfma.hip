@@ -19,37 +19,90 @@
 // software pipelined inside each wave: the MFMAs of tile s+1 are issued between the ALU instructions that
 // consume tile s, and the scheduler is told to keep that interleave.
 #include "ccd_score_mfma.h"
+#include "ccd_topk.h"
 
 namespace ccd {
 
 namespace {
 
+// NuC slots (Sec. 3.3.3 step 1) by rank counting, spread over the workgroups of pass 1: token t of a novelty row
+// is among the T most novel iff fewer than T tokens beat it (larger key, or equal key and lower index).  One wave
+// counts the rivals of one token, 64 at a time.  O(n^2) comparisons per row, but they are shared by every wave of
+// the launch, where a selection kernel of its own is a latency-bound chain of scans run by one workgroup per row.
+constexpr int kRankLoads = 16;
+__device__ __forceinline__ void nuc_rank_share(const Dims& D, const float* __restrict__ novelty,
+                                               uint8_t* __restrict__ mask, int blk, int n_blocks) {
+  const int lane = threadIdx.x & 63;
+  const int64_t total = (int64_t)D.B * D.n, stride = 4 * (int64_t)n_blocks;
+  for (int64_t gt = 4 * (int64_t)blk + (threadIdx.x >> 6); gt < total; gt += stride) {
+    const int b = (int)(gt / D.n), t = (int)(gt % D.n);
+    const float* row = novelty + (int64_t)b * D.nov_sb;
+    const uint32_t kt = novelty_key(row[t]);
+    uint32_t cnt = 0;
+    for (int j0 = lane; j0 < D.n; j0 += 64 * kRankLoads) {
+      float v[kRankLoads];                      // all loads of a round are in flight together
+#pragma unroll
+      for (int i = 0; i < kRankLoads; ++i) v[i] = j0 + 64 * i < D.n ? row[j0 + 64 * i] : -INFINITY;
+#pragma unroll
+      for (int i = 0; i < kRankLoads; ++i) {
+        const uint32_t kj = novelty_key(v[i]);   // rivals past the end get key 0 and an index above t: never counted
+        cnt += (kj > kt || (kj == kt && j0 + 64 * i < t)) ? 1u : 0u;
+      }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
+    if (lane == 0) mask[gt] = (kt != 0u && cnt < (uint32_t)max(D.T, 0)) ? 1 : 0;
+  }
+}
+
 template <int HD, int PASS>
 __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl, const uint16_t* __restrict__ Q,
                                                             const uint16_t* __restrict__ K, float2* __restrict__ part,
-                                                            float* __restrict__ u) {
+                                                            float* __restrict__ u, const float* __restrict__ novelty,
+                                                            uint8_t* __restrict__ nuc_mask) {
   __shared__ ScoreLds<HD, PASS> sm;
+  auto side_job = [&]() {
+    if (PASS == 1 && novelty != nullptr) nuc_rank_share(D, novelty, nuc_mask, blockIdx.x, gridDim.x);
+  };
   int unit, slice;
-  if (!decode_block(D, PASS == 1 ? pl.n_slices1 : pl.n_slices2, unit, slice)) return;
+  if (!decode_block(D, blockIdx.x, PASS == 1 ? pl.n_slices1 : pl.n_slices2, unit, slice)) {
+    side_job();
+    return;
+  }
   // pass 2 walks the units backwards: the keys pass 1 read last are the ones most likely still held by the
   // memory-side cache
   if (PASS == 2) unit = D.units_run - 1 - unit;
   unit += D.unit0;
-  score_pass_body<HD, PASS>(D, pl, unit, slice, Q, K, part, u, sm);
+  score_pass_body<HD, PASS>(D, pl, unit, slice, Q, K, part, u, sm, side_job);
 }
+
+constexpr int kRankMaxSteps = 256;   // rank-counting steps (of 64 rivals) a wave may be asked to do
+
+unsigned stats_grid(const Dims& D, const ScorePlan& pl) { return (unsigned)((D.units_run + 7) / 8 * 8) * pl.n_slices1; }
 
 }  // namespace
 
 int mfma_max_slice() { return kMaxSlice; }
 
-void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s) {
-  dim3 grid((unsigned)((D.units_run + 7) / 8 * 8) * pl.n_slices1), block(kMT);
+// true when the pass-1 launch can also mark the NuC slots: novelty shared by layers and heads (one row per
+// sequence), the full range of units, and a per-wave share of the rank counting that stays small
+bool stats_hosts_nuc(const Dims& D, const ScorePlan& pl) {
+  if (D.nov_sl != 0 || D.nov_sh != 0 || D.unit0 != 0 || D.units_run != D.units) return false;
+  const int64_t waves = 4 * (int64_t)stats_grid(D, pl);
+  const int64_t tokens_per_wave = ((int64_t)D.B * D.n + waves - 1) / waves;
+  return tokens_per_wave * ((D.n + 63) / 64) <= kRankMaxSteps;
+}
+
+// novelty != nullptr (only if stats_hosts_nuc): the launch also writes nuc_mask[B, n]
+void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part,
+                       const float* novelty, uint8_t* nuc_mask, hipStream_t s) {
+  dim3 grid(stats_grid(D, pl)), block(kMT);
   if (D.d == 64)
     hipLaunchKernelGGL((score_pass_kernel<64, 1>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
-                       (float*)nullptr);
+                       (float*)nullptr, novelty, nuc_mask);
   else
     hipLaunchKernelGGL((score_pass_kernel<128, 1>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
-                       (float*)nullptr);
+                       (float*)nullptr, novelty, nuc_mask);
 }
 
 void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float2* part, float* u,
@@ -57,10 +110,10 @@ void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const v
   dim3 grid((unsigned)((D.units_run + 7) / 8 * 8) * pl.n_slices2), block(kMT);
   if (D.d == 64)
     hipLaunchKernelGGL((score_pass_kernel<64, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
-                       const_cast<float2*>(part), u);
+                       const_cast<float2*>(part), u, (const float*)nullptr, (uint8_t*)nullptr);
   else
     hipLaunchKernelGGL((score_pass_kernel<128, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
-                       const_cast<float2*>(part), u);
+                       const_cast<float2*>(part), u, (const float*)nullptr, (uint8_t*)nullptr);
 }
 
 }  // namespace ccd

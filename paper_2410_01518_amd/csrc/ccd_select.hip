@@ -11,14 +11,16 @@ namespace ccd {
 namespace {
 
 constexpr int kSelThreads = 1024;
+constexpr int kStageMaxKpt = 16;   // rows of up to 16384 tokens (64 KiB) are staged in LDS for pooling
 
 // one workgroup per novelty row: per sequence when novelty is shared by layers and heads, else per unit
+template <int KPT>
 __global__ __launch_bounds__(kSelThreads) void nuc_mask_kernel(Dims D, const float* __restrict__ novelty,
                                                                uint8_t* __restrict__ mask) {
   __shared__ TopkShared<kSelThreads> sh;
   const bool shared_nov = D.nov_sl == 0 && D.nov_sh == 0;
   const float* nov = novelty + (shared_nov ? (int64_t)blockIdx.x * D.nov_sb : nov_offset(D, decode_unit(D, blockIdx.x)));
-  nuc_mask_job<kSelThreads>(nov, mask + (int64_t)blockIdx.x * D.n, D.n, D.T, sh);
+  nuc_mask_job<kSelThreads, KPT>(nov, mask + (int64_t)blockIdx.x * D.n, D.n, D.T, sh);
 }
 
 template <int KPT>
@@ -26,7 +28,10 @@ __global__ __launch_bounds__(kSelThreads) void finalize_select_kernel(Dims D, co
                                                                       const uint8_t* __restrict__ mask, float* scores,
                                                                       int32_t* __restrict__ keep_idx) {
   __shared__ TopkShared<kSelThreads> sh;
-  finalize_select_body<kSelThreads, KPT>(D, D.unit0 + blockIdx.x, u, mask, scores, keep_idx, sh);
+  constexpr int kStage = KPT <= kStageMaxKpt ? KPT * kSelThreads : 1;
+  __shared__ float u_stage[kStage];
+  finalize_select_body<kSelThreads, KPT>(D, D.unit0 + blockIdx.x, u, mask, scores, keep_idx, sh,
+                                         KPT <= kStageMaxKpt ? u_stage : nullptr);
 }
 
 }  // namespace
@@ -35,7 +40,14 @@ int select_max_tokens() { return 64 * kSelThreads; }
 
 void launch_nuc_mask(const Dims& D, const float* novelty, uint8_t* mask, hipStream_t s) {
   const bool shared_nov = D.nov_sl == 0 && D.nov_sh == 0;
-  hipLaunchKernelGGL(nuc_mask_kernel, dim3(shared_nov ? D.B : D.units), dim3(kSelThreads), 0, s, D, novelty, mask);
+  const dim3 grid(shared_nov ? D.B : D.units), block(kSelThreads);
+  const int kpt = (D.n + kSelThreads - 1) / kSelThreads;
+#define CCD_LAUNCH(KPT) hipLaunchKernelGGL((nuc_mask_kernel<KPT>), grid, block, 0, s, D, novelty, mask)
+  if (kpt <= 4) CCD_LAUNCH(4);
+  else if (kpt <= 16) CCD_LAUNCH(16);
+  else if (kpt <= 32) CCD_LAUNCH(32);
+  else CCD_LAUNCH(64);
+#undef CCD_LAUNCH
 }
 
 void launch_finalize_select(const Dims& D, const float* u, const uint8_t* mask, float* scores, int32_t* keep_idx,

@@ -24,15 +24,27 @@ __device__ __forceinline__ float pooled(const float* __restrict__ u, int t, int 
 // u != nullptr: score <- NuC lift (mask) of pooled u, written to `scores` if that is not null.
 // u == nullptr: score <- scores (must not be null).      keep_idx != nullptr: keep_idx <- top-k of score.
 // Executed by a whole workgroup of THREADS threads; thread t owns tokens t, t+THREADS, ... (at most KPT of them).
+// u_stage (LDS, n floats, or null): the unit's row of u is copied there first, so that the pooling window reads
+// LDS instead of issuing a chain of dependent global loads per token.
 template <int THREADS, int KPT>
 __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, const float* __restrict__ u,
                                                      const uint8_t* __restrict__ mask, float* scores,
-                                                     int32_t* __restrict__ keep_idx, TopkShared<THREADS>& sh) {
+                                                     int32_t* __restrict__ keep_idx, TopkShared<THREADS>& sh,
+                                                     float* u_stage) {
   const int tid = threadIdx.x, n = D.n;
   int phase = 0;
   float sc[KPT];
   if (u != nullptr) {
     const float* uu = u + (int64_t)unit * n;
+    if (u_stage != nullptr && D.pool_mode != 0 && D.pool_w > 1) {
+#pragma unroll
+      for (int j = 0; j < KPT; ++j) {
+        const int t = tid + j * THREADS;
+        if (t < n) u_stage[t] = uu[t];
+      }
+      __syncthreads();
+      uu = u_stage;
+    }
     const bool shared_nov = D.nov_sl == 0 && D.nov_sh == 0;
     const uint8_t* mrow = mask + (int64_t)(shared_nov ? decode_unit(D, unit).b : unit) * n;
 #pragma unroll

@@ -77,8 +77,8 @@ __device__ __forceinline__ uint32_t block_rank(bool pred, TopkShared<THREADS>& s
 }
 
 // Threshold of the kk largest of the keys of tokens 0 .. n-1, 1 <= kk <= n.  Thread tid owns tokens
-// tid + j*THREADS; key_of(j, t) returns the key of token t = tid + j*THREADS.  KPT > 0 unrolls j over 0..KPT-1
-// (keys held in registers), KPT == 0 loops at run time (keys re-read from memory).
+// tid + j*THREADS, j < KPT (n <= THREADS * KPT); key_of(j, t) returns the key of token t = tid + j*THREADS, which
+// the caller holds in registers.
 // On return #{key > tau} < kk <= #{key >= tau} and need = kk - #{key > tau}.  Ends with a barrier.
 template <int THREADS, int KPT, class KeyFn>
 __device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk, TopkShared<THREADS>& sh, int& phase, uint32_t& tau,
@@ -92,17 +92,10 @@ __device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk
     const uint32_t dmask = pass == 2 ? 1023u : 2047u;
     for (int i = tid; i < kRadixBins; i += THREADS) sh.hist[i] = 0;
     __syncthreads();
-    if constexpr (KPT > 0) {
 #pragma unroll
-      for (int j = 0; j < KPT; ++j) {
-        const int t = tid + j * THREADS;
-        if (t < n) {
-          const uint32_t key = key_of(j, t);
-          if ((key & hi_mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & dmask], 1u);
-        }
-      }
-    } else {
-      for (int j = 0, t = tid; t < n; ++j, t += THREADS) {
+    for (int j = 0; j < KPT; ++j) {
+      const int t = tid + j * THREADS;
+      if (t < n) {
         const uint32_t key = key_of(j, t);
         if ((key & hi_mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & dmask], 1u);
       }
@@ -137,27 +130,33 @@ __device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk
 }
 
 // The T tokens of largest novelty (Sec. 3.3.3 step 1): mask[t] = 1 for them, 0 otherwise, t < n.  NaN and -inf
-// never qualify; ties go to the lower index.  Every thread of the workgroup must call this.
-template <int THREADS>
+// never qualify; ties go to the lower index.  Every thread of the workgroup must call this.  Thread tid owns tokens
+// tid + j*THREADS, j < KPT (n <= THREADS * KPT), and keeps their keys in registers: novelty is read once.
+template <int THREADS, int KPT>
 __device__ __forceinline__ void nuc_mask_job(const float* __restrict__ nov, uint8_t* __restrict__ mask, int n, int T, TopkShared<THREADS>& sh) {
   const int tid = threadIdx.x;
   int phase = 0;
-  uint32_t mine = 0;
-  for (int t = tid; t < n; t += THREADS) mine += novelty_key(nov[t]) != 0u;
+  uint32_t key[KPT], mine = 0;
+#pragma unroll
+  for (int j = 0; j < KPT; ++j) {
+    const int t = tid + j * THREADS;
+    key[j] = t < n ? novelty_key(nov[t]) : 0u;
+    mine += key[j] != 0u;
+  }
   uint32_t eligible;
   block_exclusive_scan<THREADS>(mine, sh, phase, eligible);
   const uint32_t T_eff = min((uint32_t)max(T, 0), eligible);
   uint32_t tau = 0xFFFFFFFFu, need = 0;
-  if (T_eff > 0)
-    radix_threshold<THREADS, 0>([&](int, int t) { return novelty_key(nov[t]); }, n, T_eff, sh, phase, tau, need);
+  if (T_eff > 0) radix_threshold<THREADS, KPT>([&](int j, int) { return key[j]; }, n, T_eff, sh, phase, tau, need);
   uint32_t eq_base = 0;
-  for (int base = 0; base < n; base += THREADS) {
-    const int t = base + tid;
-    const uint32_t key = t < n ? novelty_key(nov[t]) : 0u;
-    const bool eq = T_eff > 0 && t < n && key == tau;
+#pragma unroll
+  for (int j = 0; j < KPT; ++j) {
+    if (j * THREADS >= n) continue;      // uniform: whole rounds beyond n are skipped
+    const int t = tid + j * THREADS;
+    const bool eq = T_eff > 0 && t < n && key[j] == tau;
     uint32_t tot;
     const uint32_t rank = block_rank<THREADS>(eq, sh, phase, tot);
-    if (t < n) mask[t] = (T_eff > 0 && (key > tau || (eq && eq_base + rank < need))) ? 1 : 0;
+    if (t < n) mask[t] = (T_eff > 0 && (key[j] > tau || (eq && eq_base + rank < need))) ? 1 : 0;
     eq_base += tot;
   }
 }

@@ -156,29 +156,25 @@ struct Profiler {
 };
 static Profiler g_prof;
 
-// compute units of the current device (the persistent kernel launches two workgroups per CU)
-static int device_cus() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
-    if (cus <= 0) cus = 256;
-  }
-  return cus;
-}
-
 static int launch_status() { return hipGetLastError() == hipSuccess ? CCD_OK : CCD_ELAUNCH; }
 
-// steps a2-a3: raw CaP score u[unit, t] for the units D.unit0 .. D.unit0 + D.units_run - 1
-static void run_cap_scores(const Dims& D, const ScorePlan& pl, const Workspace& w, const void* Q, const void* K,
-                           char* ws, hipStream_t st) {
+// NuC mask (step a1, when T > 0) and raw CaP score u[unit, t] (steps a2-a3).  On the matrix-core path the first
+// score pass marks the NuC slots on the side when it can; otherwise they take a kernel of their own.
+static void run_mask_and_cap_scores(const Dims& D, const ScorePlan& pl, const Workspace& w, const void* Q, const void* K,
+                                    const float* novelty, char* ws, hipStream_t st) {
   float2* part = reinterpret_cast<float2*>(ws + w.off_part);
   float* lse2 = reinterpret_cast<float*>(ws + w.off_lse);
   float* u = reinterpret_cast<float*>(ws + w.off_u);
+  uint8_t* mask = reinterpret_cast<uint8_t*>(ws + w.off_mask);
+  const bool nuc_in_stats = D.T > 0 && pl.use_mfma && stats_hosts_nuc(D, pl);
+  if (D.T > 0 && !nuc_in_stats) {
+    g_prof.begin(kStNuc, st);
+    launch_nuc_mask(D, novelty, mask, st);
+    g_prof.end(st);
+  }
   if (pl.use_mfma) {
     g_prof.begin(kStStats, st);
-    launch_stats_mfma(D, pl, Q, K, part, st);
+    launch_stats_mfma(D, pl, Q, K, part, nuc_in_stats ? novelty : nullptr, mask, st);
     g_prof.end(st);
     g_prof.begin(kStProb, st);
     launch_prob_mfma(D, pl, Q, K, part, u, st);
@@ -223,8 +219,7 @@ int ccd_score(const ccd_shape_t* shape, const void* Q_cat, const void* K, const 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
   uint8_t* mask = reinterpret_cast<uint8_t*>(ws + w.off_mask);
-  if (D.T > 0) launch_nuc_mask(D, novelty, mask, st);
-  run_cap_scores(D, pl, w, Q_cat, K, ws, st);
+  run_mask_and_cap_scores(D, pl, w, Q_cat, K, novelty, ws, st);
   launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), mask, scores, nullptr, st);
   return launch_status();
 }
@@ -272,12 +267,7 @@ int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, 
   const float* u = reinterpret_cast<const float*>(ws + w.off_u);
   const bool per_head = shape->nov_stride_l != 0 || shape->nov_stride_h != 0;
   if (g_prof.on) ++g_prof.calls;
-  if (D.T > 0) {
-    g_prof.begin(kStNuc, st);
-    launch_nuc_mask(D, novelty, mask, st);
-    g_prof.end(st);
-  }
-  run_cap_scores(D, pl, w, Q_cat, K, ws, st);
+  run_mask_and_cap_scores(D, pl, w, Q_cat, K, novelty, ws, st);
   g_prof.begin(kStSelect, st);
   launch_finalize_select(D, u, mask, scores_opt, keep_idx, st);
   g_prof.end(st);

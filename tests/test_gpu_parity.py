@@ -138,6 +138,39 @@ def test_scores_and_staged_calls(case, pool_mode, score_path):
     np.testing.assert_array_equal(kh, gu.replay_select(sh, cfg.k))                # (C) replay on the GPU's scores
 
 
+@pytest.mark.parametrize("per_head", [False, True])
+@pytest.mark.parametrize("score_path", [0, 1], indirect=True)
+@pytest.mark.parametrize("T", [1, 37, 200, 699])
+def test_nuc_slots_with_ties_and_non_finite_novelty(per_head, score_path, T):
+    """Sec. 3.3.3 step 1 on novelty rows full of equal values, NaN and -inf: the +inf entries of the scores must
+    sit exactly on the oracle's NuC slots (lowest index wins ties; NaN and -inf never take a slot)."""
+    cfg = _cfg(T=T, k=max(300, T))
+    print(f"nuc ties per_head={per_head} path={score_path} T={T}", flush=True)
+    inp = synth.make_inputs(cfg, per_head_novelty=per_head)
+    rng = np.random.default_rng(1234 + T)
+    nov = np.round(inp["novelty"] * 4) / 4            # a handful of distinct levels -> many ties
+    nov = nov.astype(np.float32)
+    bad = rng.random(nov.shape) < 0.15
+    nov[bad] = rng.choice(np.array([np.nan, -np.inf, np.inf], dtype=np.float32), size=int(bad.sum()))
+    if T == 699:
+        nov[..., 5:] = np.where(rng.random(nov[..., 5:].shape) < 0.9, -np.inf, nov[..., 5:])   # fewer eligible than T
+    inp["novelty"] = nov
+    dev = _upload(inp)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=T, pool_w=cfg.w, pool_mode=O.POOL_MAX)
+    ws = ip.alloc_workspace(shape)
+    scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
+    assert ip.ccd_score(shape, dev["Q_cat"], dev["K"], dev["novelty"], scores, ws) == ip.CCD_OK
+    torch.cuda.synchronize()
+    sh = gu.to_host(scores)
+    for b in range(cfg.B):
+        for l in range(cfg.L):
+            for h in range(cfg.Hkv):
+                row = nov[b, l, h] if per_head else nov[b]
+                want = O.nuc_slots(row, T)
+                got = np.flatnonzero(np.isposinf(sh[b, l, h]))
+                np.testing.assert_array_equal(got, want)
+
+
 # ------------------------------------------------------------------ fused ccd_compress
 
 def _run_fused(cfg, inp, pool_mode=O.POOL_MAX, per_head=False, want_scores=True):
