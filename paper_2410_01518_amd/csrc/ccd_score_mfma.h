@@ -181,13 +181,11 @@ struct ScoreLds {
 
 // One (unit, token slice) of one pass, executed by a workgroup of kMT threads.  Ends with every thread past a
 // barrier, so the LDS may be reused at once.
-// side_job() is called once, by every thread, while the first K tiles are in flight (and before the query
-// fragments occupy their registers): a place for a small unrelated job whose memory latency then costs little.
-template <int HD, int PASS, class SideJob>
+template <int HD, int PASS>
 __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& pl, int unit, int slice,
                                                 const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
                                                 float2* __restrict__ part, float* __restrict__ u,
-                                                ScoreLds<HD, PASS>& sm, SideJob side_job) {
+                                                ScoreLds<HD, PASS>& sm) {
   constexpr int KS = HD / 16;
   constexpr int SLOTB = Tiles<HD>::kSlotBytes;
   uint8_t* lds = sm.ring;
@@ -213,7 +211,6 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
     for (int i = 0; i < kBatch; ++i)
       if (i < S) issue_tile<HD>(Ku, t0, t1, i, lds_addr + i * SLOTB, wave, lane);
 
-    if (qc == 0) side_job();
     bf16x8 bq[kQB][KS];
     load_q_frags<HD>(bq, D, ui, Q, qc + wave * (kQB * 32), col, half);
 

@@ -29,20 +29,22 @@ namespace {
 // is among the T most novel iff fewer than T tokens beat it (larger key, or equal key and lower index).  One wave
 // counts the rivals of one token, 64 at a time.  O(n^2) comparisons per row, but they are shared by every wave of
 // the launch, where a selection kernel of its own is a latency-bound chain of scans run by one workgroup per row.
+// Not inlined on purpose: inside the score kernel its registers and scalar state disturbed the allocation of the
+// main loop (scalar spills in every step, about 8 us per launch); as a function of its own it costs a call.
 constexpr int kRankLoads = 16;
-__device__ __forceinline__ void nuc_rank_share(const Dims& D, const float* __restrict__ novelty,
-                                               uint8_t* __restrict__ mask, int blk, int n_blocks) {
+__device__ __attribute__((noinline)) void nuc_rank_share(const float* __restrict__ novelty, uint8_t* __restrict__ mask,
+                                                         int B, int n, int64_t nov_sb, int T, int blk, int n_blocks) {
   const int lane = threadIdx.x & 63;
-  const int64_t total = (int64_t)D.B * D.n, stride = 4 * (int64_t)n_blocks;
+  const int64_t total = (int64_t)B * n, stride = 4 * (int64_t)n_blocks;
   for (int64_t gt = 4 * (int64_t)blk + (threadIdx.x >> 6); gt < total; gt += stride) {
-    const int b = (int)(gt / D.n), t = (int)(gt % D.n);
-    const float* row = novelty + (int64_t)b * D.nov_sb;
+    const int b = (int)(gt / n), t = (int)(gt % n);
+    const float* row = novelty + (int64_t)b * nov_sb;
     const uint32_t kt = novelty_key(row[t]);
     uint32_t cnt = 0;
-    for (int j0 = lane; j0 < D.n; j0 += 64 * kRankLoads) {
+    for (int j0 = lane; j0 < n; j0 += 64 * kRankLoads) {
       float v[kRankLoads];                      // all loads of a round are in flight together
 #pragma unroll
-      for (int i = 0; i < kRankLoads; ++i) v[i] = j0 + 64 * i < D.n ? row[j0 + 64 * i] : -INFINITY;
+      for (int i = 0; i < kRankLoads; ++i) v[i] = j0 + 64 * i < n ? row[j0 + 64 * i] : -INFINITY;
 #pragma unroll
       for (int i = 0; i < kRankLoads; ++i) {
         const uint32_t kj = novelty_key(v[i]);   // rivals past the end get key 0 and an index above t: never counted
@@ -51,7 +53,7 @@ __device__ __forceinline__ void nuc_rank_share(const Dims& D, const float* __res
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
-    if (lane == 0) mask[gt] = (kt != 0u && cnt < (uint32_t)max(D.T, 0)) ? 1 : 0;
+    if (lane == 0) mask[gt] = (kt != 0u && cnt < (uint32_t)max(T, 0)) ? 1 : 0;
   }
 }
 
@@ -61,19 +63,15 @@ __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl
                                                             float* __restrict__ u, const float* __restrict__ novelty,
                                                             uint8_t* __restrict__ nuc_mask) {
   __shared__ ScoreLds<HD, PASS> sm;
-  auto side_job = [&]() {
-    if (PASS == 1 && novelty != nullptr) nuc_rank_share(D, novelty, nuc_mask, blockIdx.x, gridDim.x);
-  };
+  if (PASS == 1 && novelty != nullptr)
+    nuc_rank_share(novelty, nuc_mask, D.B, D.n, D.nov_sb, D.T, blockIdx.x, gridDim.x);
   int unit, slice;
-  if (!decode_block(D, blockIdx.x, PASS == 1 ? pl.n_slices1 : pl.n_slices2, unit, slice)) {
-    side_job();
-    return;
-  }
+  if (!decode_block(D, blockIdx.x, PASS == 1 ? pl.n_slices1 : pl.n_slices2, unit, slice)) return;
   // pass 2 walks the units backwards: the keys pass 1 read last are the ones most likely still held by the
   // memory-side cache
   if (PASS == 2) unit = D.units_run - 1 - unit;
   unit += D.unit0;
-  score_pass_body<HD, PASS>(D, pl, unit, slice, Q, K, part, u, sm, side_job);
+  score_pass_body<HD, PASS>(D, pl, unit, slice, Q, K, part, u, sm);
 }
 
 constexpr int kRankMaxSteps = 256;   // rank-counting steps (of 64 rivals) a wave may be asked to do
