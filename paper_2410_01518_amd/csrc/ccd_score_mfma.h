@@ -269,7 +269,7 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
       logits<HD, PASS>(NXT, a, bq);                                                               \
       if (PASS == 1) {                                                                            \
         fold_stats<false>(CUR, m_raw, Z, c, half, 32);                                            \
-        interleave_hint<KS, 20, 6>();                                                             \
+        interleave_hint<KS, 20, 8>();                                                             \
       } else {                                                                                    \
         float us = fold_prob(CUR, neg_lse, c);                                                    \
         interleave_hint<KS, 14, 5>();                                                             \

@@ -31,7 +31,7 @@ namespace {
 // the launch, where a selection kernel of its own is a latency-bound chain of scans run by one workgroup per row.
 // Not inlined on purpose: inside the score kernel its registers and scalar state disturbed the allocation of the
 // main loop (scalar spills in every step, about 8 us per launch); as a function of its own it costs a call.
-constexpr int kRankLoads = 16;
+constexpr int kRankLoads = 32;
 __device__ __attribute__((noinline)) void nuc_rank_share(const float* __restrict__ novelty, uint8_t* __restrict__ mask,
                                                          int B, int n, int64_t nov_sb, int T, int blk, int n_blocks) {
   const int lane = threadIdx.x & 63;
