@@ -53,21 +53,37 @@ __device__ __forceinline__ void dma16(const void* gbase, uint32_t voff, uint32_t
 // through), so the only safe wait is for everything this wave has in flight.
 __device__ __forceinline__ void wait_all_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// this wave's share of tile `tile` of the slice -> ring slot at LDS byte address slot_addr.  Rows past the end
-// of the pot re-read the last valid row: they are masked (pass 1) or never stored (pass 2).
+// this wave's share of tile `tile` of the slice -> ring slot at LDS byte address slot_addr.  voff_full holds the
+// lane offsets of the wave's kInstrPerWave instructions inside a full tile (computed once per workgroup).  Only the
+// last tile of a pot can be partial: its rows past the end re-read the last valid row; they are masked (pass 1) or
+// never stored (pass 2).
+template <int HD>
+__device__ __forceinline__ void tile_offsets(uint32_t (&voff_full)[Tiles<HD>::kInstrPerWave], int wave, int lane) {
+#pragma unroll
+  for (int i = 0; i < Tiles<HD>::kInstrPerWave; ++i) {
+    const int row = (wave + 4 * i) * Tiles<HD>::kRowsPerInstr + lane / Tiles<HD>::kChunksPerRow;
+    const int c = (lane % Tiles<HD>::kChunksPerRow) ^ Tiles<HD>::swz(row);
+    voff_full[i] = (uint32_t)(row * Tiles<HD>::kRowBytes + c * 16);
+  }
+}
+
 template <int HD>
 __device__ __forceinline__ void issue_tile(const uint16_t* Ku, int t0, int t1, int tile, uint32_t slot_addr, int wave,
-                                           int lane) {
+                                           int lane, const uint32_t (&voff_full)[Tiles<HD>::kInstrPerWave]) {
   const int tile_t0 = t0 + tile * kStep;
   const uint16_t* base = Ku + (int64_t)tile_t0 * HD;
   const int last = t1 - 1 - tile_t0;
+  if (last >= kStep - 1) {
 #pragma unroll
-  for (int i = 0; i < Tiles<HD>::kInstrPerWave; ++i) {
-    const int j = wave + 4 * i;
-    const int row = j * Tiles<HD>::kRowsPerInstr + lane / Tiles<HD>::kChunksPerRow;
-    const int c = (lane % Tiles<HD>::kChunksPerRow) ^ Tiles<HD>::swz(row);
-    const uint32_t voff = (uint32_t)(min(row, last) * Tiles<HD>::kRowBytes + c * 16);
-    dma16(base, voff, slot_addr + j * 1024);
+    for (int i = 0; i < Tiles<HD>::kInstrPerWave; ++i) dma16(base, voff_full[i], slot_addr + (wave + 4 * i) * 1024);
+  } else {
+#pragma unroll
+    for (int i = 0; i < Tiles<HD>::kInstrPerWave; ++i) {
+      const int j = wave + 4 * i;
+      const int row = j * Tiles<HD>::kRowsPerInstr + lane / Tiles<HD>::kChunksPerRow;
+      const int c = (lane % Tiles<HD>::kChunksPerRow) ^ Tiles<HD>::swz(row);
+      dma16(base, (uint32_t)(min(row, last) * Tiles<HD>::kRowBytes + c * 16), slot_addr + j * 1024);
+    }
   }
 }
 
@@ -204,12 +220,14 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
   int koff[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) koff[ks] = col * Tiles<HD>::kRowBytes + (((2 * ks + half) ^ Tiles<HD>::swz(col)) << 4);
+  uint32_t voff_full[Tiles<HD>::kInstrPerWave];
+  tile_offsets<HD>(voff_full, wave, lane);
 
   for (int qc = 0; qc < D.GP; qc += kQPerPass) {
     // start the K stream first: batch 0 is in flight while the query fragments are fetched
 #pragma unroll
     for (int i = 0; i < kBatch; ++i)
-      if (i < S) issue_tile<HD>(Ku, t0, t1, i, lds_addr + i * SLOTB, wave, lane);
+      if (i < S) issue_tile<HD>(Ku, t0, t1, i, lds_addr + i * SLOTB, wave, lane, voff_full);
 
     bf16x8 bq[kQB][KS];
     load_q_frags<HD>(bq, D, ui, Q, qc + wave * (kQB * 32), col, half);
@@ -240,7 +258,7 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
     __syncthreads();
 #pragma unroll
     for (int i = kBatch; i < kDepth; ++i)      // batch 1 lands while batch 0 is consumed
-      if (i < S) issue_tile<HD>(Ku, t0, t1, i, lds_addr + i * SLOTB, wave, lane);
+      if (i < S) issue_tile<HD>(Ku, t0, t1, i, lds_addr + i * SLOTB, wave, lane, voff_full);
     if (PASS == 2) {
 #pragma unroll
       for (int qb = 0; qb < kQB; ++qb)
@@ -263,7 +281,7 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
       if ((I) % kBatch == 2) {                                                                    \
         _Pragma("unroll") for (int i = 0; i < kBatch; ++i)                                        \
           if (s + 4 + i < S)                                                                      \
-            issue_tile<HD>(Ku, t0, t1, s + 4 + i, lds_addr + (((I) + 4 + i) % kDepth) * SLOTB, wave, lane); \
+            issue_tile<HD>(Ku, t0, t1, s + 4 + i, lds_addr + (((I) + 4 + i) % kDepth) * SLOTB, wave, lane, voff_full); \
       }                                                                                           \
       load_k_frags<HD, ((I) + 1) % kDepth>(a, lds, koff);                                         \
       logits<HD, PASS>(NXT, a, bq);                                                               \

@@ -26,7 +26,7 @@ namespace ccd {
 namespace {
 
 // NuC slots (Sec. 3.3.3 step 1) by rank counting, spread over the workgroups of pass 1: token t of a novelty row
-// is among the T most novel iff fewer than T tokens beat it (larger key, or equal key and lower index).  One wave
+// is among the T most novel iff fewer than T tokens beat it (larger value, or equal value and lower index).  One wave
 // counts the rivals of one token, 64 at a time.  O(n^2) comparisons per row, but they are shared by every wave of
 // the launch, where a selection kernel of its own is a latency-bound chain of scans run by one workgroup per row.
 // Not inlined on purpose: inside the score kernel its registers and scalar state disturbed the allocation of the
@@ -39,21 +39,23 @@ __device__ __attribute__((noinline)) void nuc_rank_share(const float* __restrict
   for (int64_t gt = 4 * (int64_t)blk + (threadIdx.x >> 6); gt < total; gt += stride) {
     const int b = (int)(gt / n), t = (int)(gt % n);
     const float* row = novelty + (int64_t)b * nov_sb;
-    const uint32_t kt = novelty_key(row[t]);
+    const float vt = row[t] + 0.0f;               // -0 counts as +0
+    const bool eligible = vt == vt && vt != -INFINITY;
+    // For an eligible t plain float compares order the rivals exactly as the keys do: NaN compares false, -inf is
+    // below every eligible value, and rivals past the end are given -inf.
     uint32_t cnt = 0;
-    for (int j0 = lane; j0 < n; j0 += 64 * kRankLoads) {
+    for (int base = 0; base < n; base += 64 * kRankLoads) {      // trip count uniform over the wave
+      const int j0 = base + lane;
       float v[kRankLoads];                      // all loads of a round are in flight together
 #pragma unroll
       for (int i = 0; i < kRankLoads; ++i) v[i] = j0 + 64 * i < n ? row[j0 + 64 * i] : -INFINITY;
 #pragma unroll
       for (int i = 0; i < kRankLoads; ++i) {
-        const uint32_t kj = novelty_key(v[i]);   // rivals past the end get key 0 and an index above t: never counted
-        cnt += (kj > kt || (kj == kt && j0 + 64 * i < t)) ? 1u : 0u;
+        const bool beats = v[i] > vt || (v[i] == vt && j0 + 64 * i < t);
+        cnt += __popcll(__ballot(beats));        // wave-wide count on the scalar unit
       }
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
-    if (lane == 0) mask[gt] = (kt != 0u && cnt < (uint32_t)max(T, 0)) ? 1 : 0;
+    if (lane == 0) mask[gt] = (eligible && cnt < (uint32_t)max(T, 0)) ? 1 : 0;
   }
 }
 
