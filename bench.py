@@ -3,10 +3,12 @@
 
 A step is one ccd_compress call over one full pot of the headline configuration (32 layers x 8 KV heads
 x 128, 32 query heads, pot 4096 -> 2048, 64 CaP query tokens, T = 1024 NuC slots, max-pool window 7, bf16,
-synthetic seeded data).  Steps cycle over rings of 3 pots (K, V), 4 catalyst-query sets and 5 novelty vectors
-(coprime periods), so that no call finds its cache warm from the previous one and every call scores its pot
-with queries and novelty it has not been compressed under before: the kept set is then spread over the whole
-pot, as in steady-state streaming where half of the pot is new context, and nearly every row moves.
+synthetic seeded data).  Every call of a pass gets a pot (K, V) that has not been compressed before (as many
+pots as warm-up + timed steps are resident in HBM, 0.5 GiB each; they are refilled with fresh seeded data between
+the passes), and the calls cycle over 4 catalyst-query sets and 5 novelty vectors.  No call finds its cache
+warm, and the kept set is spread over the whole pot, as in steady-state streaming where half of the pot is new
+context: nearly every kept row moves.  (Re-compressing the same few pots over and over instead lets copies of
+the best-scoring rows pile up in them, and after some dozens of calls a growing prefix of every pot stays put.)
 Prints one JSON line.
 """
 from __future__ import annotations
@@ -24,8 +26,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 VALU_FP32_PEAK_TFLOPS = 157.3
 # HBM bytes per launch on the headline config from the committed rocprofv3 counter runs
 # (profiles/ccd_compress_c3_hbm_traffic.md: read requests x 128 B + WRITE_SIZE; a plain copy reads factor 1.00)
-MEASURED_TRAFFIC_C3 = {"score_stats": 287_500_000, "score_prob": 291_700_000, "compact": 539_200_000,
-                       "select": 4_300_000, "nuc_mask": 17_000}
+MEASURED_TRAFFIC_C3 = {"score_stats": 287_900_000, "score_prob": 291_700_000, "compact": 539_600_000,
+                       "select": 4_300_000}
 
 
 def algorithmic_bytes(cfg) -> dict:
@@ -55,7 +57,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--ring", type=int, default=3, help="independent pots cycled through")
+    ap.add_argument("--ring", type=int, default=0,
+                    help="pots cycled through (0: one fresh pot per call of a pass, as far as 60 %% of free HBM allows)")
     ap.add_argument("--config", default="c3")
     ap.add_argument("--score-path", type=int, default=0, help="0 auto (matrix cores for bf16), 1 vector ALUs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -92,11 +95,25 @@ def main() -> int:
     def randn(*shape):                                   # further sets: same recipe drawn on the device
         return torch.randn(shape, generator=g, device=dev, dtype=torch.float32).to(tdt)
 
-    pots = [(dev0["K"], dev0["V"])] + [(randn(cfg.B, cfg.L, cfg.Hkv, cfg.N, cfg.d), randn(cfg.B, cfg.L, cfg.Hkv, cfg.N, cfg.d))
-                                       for _ in range(1, args.ring)]
-    qsets = [dev0["Q_cat"]] + [randn(cfg.B, cfg.L, cfg.Hq, cfg.P, cfg.d) for _ in range(args.ring)]
+    pot_bytes = 2 * dev0["K"].numel() * dev0["K"].element_size()
+    n_pots = args.ring if args.ring > 0 else args.steps + args.warmup
+    n_pots = max(1, min(n_pots, int(0.6 * torch.cuda.mem_get_info()[0]) // pot_bytes))
+
+    def fresh(t):                                        # same recipe as synth: N(0,1) rounded to the storage dtype
+        return t.normal_(generator=g)
+
+    def refill():                                        # pot 0 from the host copy, the others drawn anew
+        pots[0][0].copy_(upload(host0["K"]))
+        pots[0][1].copy_(upload(host0["V"]))
+        for K, V in pots[1:]:
+            fresh(K)
+            fresh(V)
+
+    pots = [(dev0["K"], dev0["V"])] + [(fresh(torch.empty_like(dev0["K"])), fresh(torch.empty_like(dev0["V"])))
+                                       for _ in range(1, n_pots)]
+    qsets = [dev0["Q_cat"]] + [randn(cfg.B, cfg.L, cfg.Hq, cfg.P, cfg.d) for _ in range(3)]
     novs = [dev0["novelty"]] + [torch.rand((cfg.B, cfg.N), generator=g, device=dev, dtype=torch.float32)
-                                for _ in range(args.ring + 1)]
+                                for _ in range(4)]
     shape = ip.make_shape(qsets[0], pots[0][0], novs[0], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=ip.CCD_POOL_MAX)
     ws = ip.alloc_workspace(shape)
     keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device=dev)
@@ -116,7 +133,7 @@ def main() -> int:
         assert rc == ip.CCD_OK, rc
 
     for i in range(args.warmup):
-        step(i)
+        step(args.steps + i)                             # the warm-up calls use the pots behind the timed ones
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -126,33 +143,45 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
     # the same K steps again with an event after every kernel: per-kernel average durations
+    # (between the bracketed kernels of that pass: which fraction of the kept rows each call really moved)
+    refill()
+    torch.cuda.synchronize()
+    ar = torch.arange(cfg.k, device=dev)
+    moved_acc = torch.zeros((), device=dev)
     ip.ccd_profile_enable(True)
     for i in range(args.steps):
         step(i)
+        moved_acc += (keep.to(torch.int64) != ar).float().mean()
     stage_ms, calls = ip.ccd_profile_collect()
     ip.ccd_profile_enable(False)
     stage_avg_us = {k: 1e3 * v / max(calls, 1) for k, v in stage_ms.items()}
 
-    # how much of the cache the last call actually moved (rows with keep_idx[j] != j)
-    moved = float((keep.to(torch.int64) != torch.arange(cfg.k, device=dev)).float().mean().item())
+    # how much of the cache a call actually moves (rows with keep_idx[j] != j), mean over the profiled calls
+    moved = float(moved_acc.item()) / max(args.steps, 1)
 
     ab = algorithmic_bytes(cfg)
-    dom = max(stage_avg_us, key=stage_avg_us.get)
-    dom_s = stage_avg_us[dom] * 1e-6
-    if dom in ("score_stats", "score_prob"):
-        flops = algorithmic_flops(cfg)
-        if args.score_path == 1 or cfg.dtype == "fp32":
-            roof = {"kernel": dom, "bound": "alu", "achieved": flops / dom_s / 1e12, "peak": VALU_FP32_PEAK_TFLOPS,
-                    "unit": "TFLOP/s"}
+    keep_bytes = cfg.units * cfg.k * 4
+    ab["call"] -= int((1.0 - moved) * 0.75 * (ab["compact"] - keep_bytes))       # only moved rows travel
+    ab["compact"] = int(moved * (ab["compact"] - keep_bytes)) + keep_bytes
+    def roofline_of(stage):
+        t = stage_avg_us[stage] * 1e-6
+        if stage in ("score_stats", "score_prob"):
+            flops = algorithmic_flops(cfg)
+            if args.score_path == 1 or cfg.dtype == "fp32":
+                r = {"kernel": stage, "bound": "alu", "achieved": flops / t / 1e12, "peak": VALU_FP32_PEAK_TFLOPS, "unit": "TFLOP/s"}
+            else:
+                r = {"kernel": stage, "bound": "mfma", "achieved": flops / t / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
         else:
-            roof = {"kernel": dom, "bound": "mfma", "achieved": flops / dom_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s"}
-    else:
-        roof = {"kernel": dom, "bound": "hbm", "achieved": ab[dom] / dom_s / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = MEASURED_TRAFFIC_C3.get(dom) if cfg.name == "c3" and args.score_path == 0 else None
-    roof["traffic_source"] = "profiles/ccd_compress_c3_hbm_traffic.md" if roof["traffic"] else None
-    roof["avg_us"] = stage_avg_us[dom]
+            r = {"kernel": stage, "bound": "hbm", "achieved": ab[stage] / t / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
+        r["frac"] = r["achieved"] / r["peak"]
+        r["traffic"] = MEASURED_TRAFFIC_C3.get(stage) if cfg.name == "c3" and args.score_path == 0 else None
+        r["traffic_source"] = "profiles/ccd_compress_c3_hbm_traffic.md" if r["traffic"] else None
+        r["avg_us"] = stage_avg_us[stage]
+        return r
+
+    dom = max(stage_avg_us, key=stage_avg_us.get)
+    roof = roofline_of(dom)
+    by_kernel = [roofline_of(st) for st in stage_avg_us if stage_avg_us[st] > 0 and st != dom]
 
     call_gbps = ab["call"] / (ms_per_step * 1e-3) / 1e9
     out = {
@@ -164,7 +193,7 @@ def main() -> int:
                                f"P{cfg.P} T{cfg.T} pool{cfg.w}", "ring": [len(pots), len(qsets), len(novs)], "score_path": args.score_path},
         "call_hbm": {"algorithmic_bytes": ab["call"], "achieved_GBps": call_gbps, "frac_of_peak": call_gbps / HBM_PEAK_GBPS},
         "stage_avg_us": stage_avg_us, "moved_row_fraction": moved,
-        "roofline": roof,
+        "roofline": roof, "roofline_other_kernels": by_kernel,
     }
 
     if not args.no_cpu_baseline:
