@@ -41,6 +41,7 @@ void launch_prob_valu(const Dims& D, const ScorePlan& pl, const void* Q, const v
                       hipStream_t s);
 
 // the same two passes on the matrix cores (bf16 only)
+int mfma_max_slice();   // longest token slice a workgroup of the matrix-core passes can take
 bool stats_hosts_nuc(const Dims& D, const ScorePlan& pl);   // may pass 1 also write the NuC mask?
 void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part,
                        const float* novelty, uint8_t* nuc_mask, hipStream_t s);

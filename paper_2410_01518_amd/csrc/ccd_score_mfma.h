@@ -9,11 +9,16 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kMT = 256;            // threads per workgroup (4 waves)
 constexpr int kStep = 32;           // tokens per tile
-constexpr int kBatch = 3;           // tiles per DMA batch
-constexpr int kDepth = 2 * kBatch;  // LDS ring slots: one batch is consumed while the other one lands
+// K tiles arrive in batches; the LDS ring holds two: one is consumed while the other one lands.  Pass 1 takes K cold
+// from HBM and uses batches of three tiles; pass 2 finds part of K in the memory-side cache, makes do with batches of
+// two and spends the LDS on partial sums for slices twice as long.
+template <int PASS> struct Ring {
+  static constexpr int kBatch = PASS == 1 ? 3 : 2;
+  static constexpr int kDepth = 2 * kBatch;
+};
 constexpr int kQB = 2;              // 32-query blocks per wave
 constexpr int kQPerPass = 4 * kQB * 32;   // query rows a workgroup covers per sweep over its slice
-constexpr int kMaxSlice = 1024;     // slice limit (per-wave partial sums of pass 2 live in LDS)
+constexpr int kMaxSlice = 2048;     // slice limit (per-wave partial sums of pass 2 live in LDS)
 constexpr float kNegHuge = -1.0e30f;
 
 // row of the 32x32 accumulator tile held in register r by a lane of half `half` (lane / 32)
@@ -190,7 +195,7 @@ __device__ __forceinline__ void interleave_hint() {
 // LDS of one score pass.  The K ring must stay first (DMA destinations are addressed relative to it).
 template <int HD, int PASS>
 struct ScoreLds {
-  __attribute__((aligned(1024))) uint8_t ring[kDepth * Tiles<HD>::kSlotBytes];
+  __attribute__((aligned(1024))) uint8_t ring[Ring<PASS>::kDepth * Tiles<HD>::kSlotBytes];
   float up[PASS == 2 ? 4 : 1][PASS == 2 ? kMaxSlice : 1];   // per-wave partial sums (pass 2)
   float lse_s[PASS == 2 ? kQPerPass : 1];
 };
@@ -204,6 +209,7 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
                                                 ScoreLds<HD, PASS>& sm) {
   constexpr int KS = HD / 16;
   constexpr int SLOTB = Tiles<HD>::kSlotBytes;
+  constexpr int kBatch = Ring<PASS>::kBatch, kDepth = Ring<PASS>::kDepth;
   uint8_t* lds = sm.ring;
   auto& up = sm.up;
   auto& lse_s = sm.lse_s;
@@ -270,18 +276,19 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
     load_k_frags<HD, 0>(a, lds, koff);
     logits<HD, PASS>(accA, a, bq);
 
-    // Step s (ring slot I = s mod 6) folds tile s on the ALU while the MFMAs of tile s+1 run.  Tiles arrive in
-    // batches of three: the batch that holds tile s+2 must have landed by the end of every step with
-    // s mod 3 == 1 (wait + barrier there, nowhere else); right after that barrier the slots of the batch
-    // consumed before are free, and the next batch (tiles s+4 .. s+6 seen from step s with s mod 3 == 2) is
+    // Step s (ring slot I = s mod kDepth) folds tile s on the ALU while the MFMAs of tile s+1 run.  Tiles arrive in
+    // batches of b = kBatch: the batch that holds tile s+2 must have landed by the end of every step with
+    // s mod b == b-2 (wait + barrier there, nowhere else); right after that barrier the slots of the batch
+    // consumed before are free, and the next batch (tiles s+b+1 .. s+2b seen from step s with s mod b == b-1) is
     // requested into them.
 #define CCD_STEP(I, CUR, NXT)                                                                     \
-    {                                                                                             \
+    if constexpr ((I) < kDepth) {                                                                 \
       if (s >= S_full) break;                                                                     \
-      if ((I) % kBatch == 2) {                                                                    \
+      if ((I) % kBatch == kBatch - 1) {                                                           \
         _Pragma("unroll") for (int i = 0; i < kBatch; ++i)                                        \
-          if (s + 4 + i < S)                                                                      \
-            issue_tile<HD>(Ku, t0, t1, s + 4 + i, lds_addr + (((I) + 4 + i) % kDepth) * SLOTB, wave, lane, voff_full); \
+          if (s + kBatch + 1 + i < S)                                                             \
+            issue_tile<HD>(Ku, t0, t1, s + kBatch + 1 + i,                                        \
+                           lds_addr + (((I) + kBatch + 1 + i) % kDepth) * SLOTB, wave, lane, voff_full); \
       }                                                                                           \
       load_k_frags<HD, ((I) + 1) % kDepth>(a, lds, koff);                                         \
       logits<HD, PASS>(NXT, a, bq);                                                               \
@@ -297,7 +304,7 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
           *dst = (qc == 0) ? us : *dst + us;                                                      \
         }                                                                                         \
       }                                                                                           \
-      if ((I) % kBatch == 1) {                                                                    \
+      if ((I) % kBatch == kBatch - 2) {                                                           \
         wait_all_dma();                                                                           \
         __builtin_amdgcn_s_barrier();                                                             \
       }                                                                                           \
@@ -313,7 +320,7 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
       CCD_STEP(5, accB, accA)
     }
 #undef CCD_STEP
-    static_assert(kDepth == 6 && kBatch == 3, "the step sequence above is written out for two batches of three");
+    static_assert(kDepth <= 6 && kDepth % 2 == 0, "the step sequence above is written out for up to six slots");
     // the logits of tile S_full - the partial tail tile, if there is one - are in accA or accB by parity
     if (S > S_full) {
       if (S_full & 1) {

@@ -1,6 +1,7 @@
 // Host side of libinfinipot: argument checks, workspace layout and kernel sequencing for the C ABI
 // declared in include/infinipot.h.  Everything here runs before any launch; the kernels live in the
 // ccd_*.hip files.
+#include <cstdlib>
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -75,11 +76,34 @@ static Dims make_dims(const ccd_shape_t* s) {
 
 constexpr int kMinSlice = 256;   // smallest token slice any plan uses: sizes the per-slice statistics
 
+// workgroup slots of the current device for the score kernels (two workgroups per compute unit)
+static int score_slots() {
+  static int slots = 0;
+  if (slots == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    int cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
+    slots = 2 * (cus > 0 ? cus : 256);
+  }
+  return slots;
+}
+
+// Token slice per workgroup: the longest of 2048 / 1024 / 512 / 256 that still gives every slot a workgroup.  Long
+// slices amortise the per-workgroup prologue, and a grid of exactly one round has no half-empty last round (the
+// headline shape: 256 units x 2 slices of 2048 = 512 workgroups on 512 slots, 6 us per pass less than 4 slices of
+// 1024 in two rounds).
+static int pick_slice(const Dims& D) {
+  const int64_t slots = score_slots();
+  for (int slice = mfma_max_slice(); slice > kMinSlice; slice /= 2)
+    if ((int64_t)D.units_run * ((D.n + slice - 1) / slice) >= slots) return slice;
+  return kMinSlice;
+}
+
 static ScorePlan plan_mfma(const Dims& D) {
   ScorePlan pl{};
   pl.use_mfma = 1;
-  pl.slice1 = 1024;
-  pl.slice2 = 1024;   // multiple of 32, at most mfma_max_slice()
+  pl.slice1 = pl.slice2 = pick_slice(D);   // multiples of 32, at most mfma_max_slice()
   pl.n_slices1 = (D.n + pl.slice1 - 1) / pl.slice1;
   pl.n_slices2 = (D.n + pl.slice2 - 1) / pl.slice2;
   return pl;
