@@ -21,6 +21,24 @@ constexpr int kQPerPass = 4 * kQB * 32;   // query rows a workgroup covers per s
 constexpr int kMaxSlice = 2048;     // slice limit (per-wave partial sums of pass 2 live in LDS)
 constexpr float kNegHuge = -1.0e30f;
 
+// The two workgroups that share a CU do not progress alike: the instruction arbiter serves the older wave first, so
+// one workgroup runs at full rate (A) and the other (B) at about half of it until A is done, and B then finishes
+// alone on a half-used CU (measured: A ends after 74 us, B after 104 us in pass 1).  Wave priorities even this out.
+// Workgroups draw alternating parities per CU (an atomic toggle indexed by the hardware CU id; its start value does
+// not matter).  Parity 0 runs at priority 2 for the first kPrioSwitch of its tiles and at priority 0 afterwards,
+// parity 1 stays at priority 1: first the one, then the other gets the issue slots, and with the switch at
+// f/(f+s) ~ 0.65 of the work (f, s = the full and the starved rate) both finish together.
+__device__ uint32_t g_cu_toggle[2048];
+constexpr float kPrioSwitch = 0.65f;
+
+__device__ __forceinline__ int cu_parity() {
+  uint32_t xcc, hw;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+  const uint32_t cu = ((xcc & 7u) << 8) | ((hw >> 8) & 0xFFu);   // XCC, shader engine, shader array, CU
+  return (int)(atomicXor(&g_cu_toggle[cu], 1u) & 1u);
+}
+
 // row of the 32x32 accumulator tile held in register r by a lane of half `half` (lane / 32)
 __device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
@@ -198,6 +216,7 @@ struct ScoreLds {
   __attribute__((aligned(1024))) uint8_t ring[Ring<PASS>::kDepth * Tiles<HD>::kSlotBytes];
   float up[PASS == 2 ? 4 : 1][PASS == 2 ? kMaxSlice : 1];   // per-wave partial sums (pass 2)
   float lse_s[PASS == 2 ? kQPerPass : 1];
+  int parity;
 };
 
 // One (unit, token slice) of one pass, executed by a workgroup of kMT threads.  Ends with every thread past a
@@ -229,6 +248,8 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
   uint32_t voff_full[Tiles<HD>::kInstrPerWave];
   tile_offsets<HD>(voff_full, wave, lane);
 
+  if (threadIdx.x == 0) sm.parity = cu_parity();     // read after the first barrier below
+  const int s_switch = (int)(kPrioSwitch * (float)S);
   for (int qc = 0; qc < D.GP; qc += kQPerPass) {
     // start the K stream first: batch 0 is in flight while the query fragments are fetched
 #pragma unroll
@@ -262,6 +283,9 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
     }
     wait_all_dma();
     __syncthreads();
+    const bool leads = sm.parity == 0;
+    if (leads) __builtin_amdgcn_s_setprio(2);
+    else       __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int i = kBatch; i < kDepth; ++i)      // batch 1 lands while batch 0 is consumed
       if (i < S) issue_tile<HD>(Ku, t0, t1, i, lds_addr + i * SLOTB, wave, lane, voff_full);
@@ -284,6 +308,7 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
 #define CCD_STEP(I, CUR, NXT)                                                                     \
     if constexpr ((I) < kDepth) {                                                                 \
       if (s >= S_full) break;                                                                     \
+      if (leads && s == s_switch) __builtin_amdgcn_s_setprio(0);                                  \
       if ((I) % kBatch == kBatch - 1) {                                                           \
         _Pragma("unroll") for (int i = 0; i < kBatch; ++i)                                        \
           if (s + kBatch + 1 + i < S)                                                             \
