@@ -1,9 +1,10 @@
 // Per-unit selection kernels: NuC slots (Sec. 3.3.3 step 1), pooling + NuC lift, and the final top-k
 // (Sec. 3.3.3 step 2 / App. B "Final Token Selection").  The selection machinery is in ccd_topk.h.
 //
-// finalize_select_kernel: one workgroup of 1024 threads per unit; thread t owns tokens t, t+1024, ... and keeps
-// their scores in registers.  Ballot/popcount prefix counts taken in token order give both the lowest-index
-// tie-break and the output slot of every kept token, so keep_idx comes out ascending without a sort.
+// finalize_select_kernel: one workgroup of 1024 threads per unit; every thread keeps the scores of its tokens in
+// registers (consecutive tokens for rows of up to 16384 tokens, which are staged in LDS; strided tokens for longer
+// rows).  Prefix counts taken in token order give both the lowest-index tie-break and the output slot of every kept
+// token, so keep_idx comes out ascending without a sort.
 #include "ccd_select_body.h"
 
 namespace ccd {
@@ -28,10 +29,10 @@ __global__ __launch_bounds__(kSelThreads) void finalize_select_kernel(Dims D, co
                                                                       const uint8_t* __restrict__ mask, float* scores,
                                                                       int32_t* __restrict__ keep_idx) {
   __shared__ TopkShared<kSelThreads> sh;
-  constexpr int kStage = KPT <= kStageMaxKpt ? KPT * kSelThreads : 1;
-  __shared__ float u_stage[kStage];
-  finalize_select_body<kSelThreads, KPT>(D, D.unit0 + blockIdx.x, u, mask, scores, keep_idx, sh,
-                                         KPT <= kStageMaxKpt ? u_stage : nullptr);
+  constexpr bool kStaged = KPT <= kStageMaxKpt;
+  __shared__ __attribute__((aligned(16))) float u_stage[kStaged ? KPT * kSelThreads + 2 * kStagePad : 4];
+  finalize_select_body<kSelThreads, KPT, kStaged>(D, D.unit0 + blockIdx.x, u, mask, scores, keep_idx, sh,
+                                                  kStaged ? u_stage : nullptr);
 }
 
 }  // namespace

@@ -21,12 +21,48 @@ __device__ __forceinline__ float pooled(const float* __restrict__ u, int t, int 
   return s / (float)w;
 }
 
+// Token ownership inside the workgroup.  Striped: thread t owns tokens t, t+THREADS, ... (coalesced global access
+// with any KPT).  Blocked: thread t owns the KPT consecutive tokens t*KPT ..: the pooling window of all of them is
+// KPT + 2r consecutive values, and ranks in token order need one workgroup scan instead of one per round.
+template <int THREADS, int KPT, bool BLOCKED>
+__device__ __forceinline__ int owned_token(int tid, int j) { return BLOCKED ? tid * KPT + j : tid + j * THREADS; }
+
+constexpr int kStagePad = 4;   // blocked pooling reads up to 4 tokens before and after a thread's tokens
+
+// Pooled scores of the KPT consecutive tokens of one thread from the LDS copy of the row (token t at
+// stage[t + kStagePad]), for windows of at most 2*kStagePad + 1: KPT/4 + 2 vector reads, the rest in registers.
+template <int KPT>
+__device__ __forceinline__ void pooled_block(float (&out)[KPT], const float* stage, int t0, int n, int w, int mode) {
+  static_assert(KPT % 4 == 0, "vector reads of four tokens");
+  float win[KPT + 2 * kStagePad];
+#pragma unroll
+  for (int i = 0; i < KPT / 4 + 2; ++i) {
+    const float4 v = *reinterpret_cast<const float4*>(stage + t0 + 4 * i);   // tokens t0 - 4 + 4i ..
+    win[4 * i] = v.x; win[4 * i + 1] = v.y; win[4 * i + 2] = v.z; win[4 * i + 3] = v.w;
+  }
+  const int r = w >> 1;
+#pragma unroll
+  for (int j = 0; j < KPT; ++j) {
+    const int t = t0 + j;
+    float m = win[j + kStagePad], sum = 0.f;
+#pragma unroll
+    for (int o = -kStagePad; o <= kStagePad; ++o) {
+      const bool in = o >= -r && o <= r && t + o >= 0 && t + o < n;
+      const float v = win[j + kStagePad + o];
+      m = in ? fmaxf(m, v) : m;
+      sum += in ? v : 0.f;
+    }
+    out[j] = mode == 1 ? m : sum / (float)w;
+  }
+}
+
 // u != nullptr: score <- NuC lift (mask) of pooled u, written to `scores` if that is not null.
 // u == nullptr: score <- scores (must not be null).      keep_idx != nullptr: keep_idx <- top-k of score.
-// Executed by a whole workgroup of THREADS threads; thread t owns tokens t, t+THREADS, ... (at most KPT of them).
-// u_stage (LDS, n floats, or null): the unit's row of u is copied there first, so that the pooling window reads
-// LDS instead of issuing a chain of dependent global loads per token.
-template <int THREADS, int KPT>
+// Executed by a whole workgroup of THREADS threads, each owning at most KPT tokens (n <= THREADS * KPT).
+// u_stage (LDS, THREADS * KPT + 2 * kStagePad floats, 16-byte aligned, or null): the unit's row of u is copied there
+// first, so that the pooling window reads LDS instead of issuing a chain of dependent global loads per token.
+// BLOCKED needs u_stage.
+template <int THREADS, int KPT, bool BLOCKED>
 __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, const float* __restrict__ u,
                                                      const uint8_t* __restrict__ mask, float* scores,
                                                      int32_t* __restrict__ keep_idx, TopkShared<THREADS>& sh,
@@ -36,23 +72,33 @@ __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, co
   float sc[KPT];
   if (u != nullptr) {
     const float* uu = u + (int64_t)unit * n;
-    if (u_stage != nullptr && D.pool_mode != 0 && D.pool_w > 1) {
+    const bool pooling = D.pool_mode != 0 && D.pool_w > 1;
+    if (u_stage != nullptr && pooling) {
 #pragma unroll
       for (int j = 0; j < KPT; ++j) {
-        const int t = tid + j * THREADS;
-        if (t < n) u_stage[t] = uu[t];
+        const int t = tid + j * THREADS;            // striped copy: coalesced
+        if (t < n) u_stage[t + kStagePad] = uu[t];
       }
       __syncthreads();
-      uu = u_stage;
+      uu = u_stage + kStagePad;
     }
     const bool shared_nov = D.nov_sl == 0 && D.nov_sh == 0;
     const uint8_t* mrow = mask + (int64_t)(shared_nov ? decode_unit(D, unit).b : unit) * n;
+    if (BLOCKED && pooling && D.pool_w <= 2 * kStagePad + 1) {
+      pooled_block<KPT>(sc, u_stage, tid * KPT, n, D.pool_w, D.pool_mode);
+    } else {
+#pragma unroll
+      for (int j = 0; j < KPT; ++j) {
+        const int t = owned_token<THREADS, KPT, BLOCKED>(tid, j);
+        sc[j] = t < n ? pooled(uu, t, n, D.pool_w, D.pool_mode) : 0.f;
+      }
+    }
 #pragma unroll
     for (int j = 0; j < KPT; ++j) {
-      const int t = tid + j * THREADS;
+      const int t = owned_token<THREADS, KPT, BLOCKED>(tid, j);
+      float v = sc[j];
       sc[j] = -INFINITY;
       if (t < n) {
-        float v = pooled(uu, t, n, D.pool_w, D.pool_mode);
         if (fabsf(v) < FLT_MIN) v = 0.f;
         sc[j] = (D.T > 0 && mrow[t]) ? INFINITY : v;
         if (scores != nullptr) scores[(int64_t)unit * n + t] = sc[j];
@@ -61,7 +107,7 @@ __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, co
   } else {
 #pragma unroll
     for (int j = 0; j < KPT; ++j) {
-      const int t = tid + j * THREADS;
+      const int t = owned_token<THREADS, KPT, BLOCKED>(tid, j);
       sc[j] = t < n ? scores[(int64_t)unit * n + t] : -INFINITY;
     }
   }
@@ -72,20 +118,44 @@ __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, co
 #pragma unroll
     for (int j = 0; j < KPT; ++j) key[j] = score_key(sc[j]);
     uint32_t tau, need;
-    radix_threshold<THREADS, KPT>([&](int j, int) { return key[j]; }, n, (uint32_t)D.k, sh, phase, tau, need);
-    uint32_t eq_base = 0, out_base = 0;
+    radix_threshold<THREADS, KPT, BLOCKED>([&](int j, int) { return key[j]; }, n, (uint32_t)D.k, sh, phase, tau, need);
+    if (BLOCKED) {
+      // token order is thread order, then j: one scan over the per-thread counts of threshold ties, one over the
+      // per-thread counts of selected tokens
+      uint32_t n_eq = 0;
 #pragma unroll
-    for (int j = 0; j < KPT; ++j) {
-      if (j * THREADS >= n) continue;      // uniform: whole rounds beyond n are skipped
-      const int t = tid + j * THREADS;
-      const bool eq = t < n && key[j] == tau;
+      for (int j = 0; j < KPT; ++j) n_eq += (tid * KPT + j < n && key[j] == tau) ? 1u : 0u;
       uint32_t tot;
-      const uint32_t erank = block_rank<THREADS>(eq, sh, phase, tot);
-      const bool sel = t < n && (key[j] > tau || (eq && eq_base + erank < need));
-      eq_base += tot;
-      const uint32_t srank = block_rank<THREADS>(sel, sh, phase, tot);
-      if (sel) out[out_base + srank] = t;
-      out_base += tot;
+      uint32_t eq_rank = block_exclusive_scan<THREADS>(n_eq, sh, phase, tot);
+      uint32_t sel_bits = 0, n_sel = 0;
+#pragma unroll
+      for (int j = 0; j < KPT; ++j) {
+        const bool valid = tid * KPT + j < n;
+        const bool eq = valid && key[j] == tau;
+        const bool sel = valid && (key[j] > tau || (eq && eq_rank < need));
+        eq_rank += eq ? 1u : 0u;
+        sel_bits |= sel ? (1u << j) : 0u;
+        n_sel += sel ? 1u : 0u;
+      }
+      uint32_t pos = block_exclusive_scan<THREADS>(n_sel, sh, phase, tot);
+#pragma unroll
+      for (int j = 0; j < KPT; ++j)
+        if (sel_bits & (1u << j)) out[pos++] = tid * KPT + j;
+    } else {
+      uint32_t eq_base = 0, out_base = 0;
+#pragma unroll
+      for (int j = 0; j < KPT; ++j) {
+        if (j * THREADS >= n) continue;      // uniform: whole rounds beyond n are skipped
+        const int t = tid + j * THREADS;
+        const bool eq = t < n && key[j] == tau;
+        uint32_t tot;
+        const uint32_t erank = block_rank<THREADS>(eq, sh, phase, tot);
+        const bool sel = t < n && (key[j] > tau || (eq && eq_base + erank < need));
+        eq_base += tot;
+        const uint32_t srank = block_rank<THREADS>(sel, sh, phase, tot);
+        if (sel) out[out_base + srank] = t;
+        out_base += tot;
+      }
     }
   }
 }

@@ -76,11 +76,11 @@ __device__ __forceinline__ uint32_t block_rank(bool pred, TopkShared<THREADS>& s
   return before + r;
 }
 
-// Threshold of the kk largest of the keys of tokens 0 .. n-1, 1 <= kk <= n.  Thread tid owns tokens
-// tid + j*THREADS, j < KPT (n <= THREADS * KPT); key_of(j, t) returns the key of token t = tid + j*THREADS, which
-// the caller holds in registers.
+// Threshold of the kk largest of the keys of tokens 0 .. n-1, 1 <= kk <= n.  Thread tid owns KPT tokens
+// (n <= THREADS * KPT): tid + j*THREADS, or tid*KPT + j when BLOCKED; key_of(j, t) returns the key of the thread's
+// j-th token t, which the caller holds in registers.
 // On return #{key > tau} < kk <= #{key >= tau} and need = kk - #{key > tau}.  Ends with a barrier.
-template <int THREADS, int KPT, class KeyFn>
+template <int THREADS, int KPT, bool BLOCKED = false, class KeyFn>
 __device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk, TopkShared<THREADS>& sh, int& phase, uint32_t& tau,
                                 uint32_t& need) {
   const int tid = threadIdx.x;
@@ -94,7 +94,7 @@ __device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < KPT; ++j) {
-      const int t = tid + j * THREADS;
+      const int t = BLOCKED ? tid * KPT + j : tid + j * THREADS;
       if (t < n) {
         const uint32_t key = key_of(j, t);
         if ((key & hi_mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & dmask], 1u);
