@@ -27,7 +27,7 @@ VALU_FP32_PEAK_TFLOPS = 157.3
 # HBM bytes per launch on the headline config from the committed rocprofv3 counter runs
 # (profiles/ccd_compress_c3_hbm_traffic.md: read requests x 128 B + WRITE_SIZE; a plain copy reads factor 1.00)
 MEASURED_TRAFFIC_C3 = {"score_stats": 287_900_000, "score_prob": 291_700_000, "compact": 539_600_000,
-                       "select": 4_300_000}
+                       "select": 4_300_000, "select_compact": None}
 
 
 def algorithmic_bytes(cfg) -> dict:
@@ -43,6 +43,8 @@ def algorithmic_bytes(cfg) -> dict:
         "score_prob": kbytes + qbytes + u * N * 4,
         "select": u * N * 4 + cfg.B * N * 4 + u * k * 4,
         "compact": 4 * rows + u * k * 4,
+        # selection and compaction in one kernel: keep_idx is written once and never read back
+        "select_compact": u * N * 4 + cfg.B * N * 4 + u * k * 4 + 4 * rows,
         # whole call: K read once, Q_cat once, kept V rows read once, K' and V' written once, keep_idx, novelty
         "call": kbytes + qbytes + rows + 2 * rows + u * k * 4 + cfg.B * N * 4,
     }
@@ -161,8 +163,10 @@ def main() -> int:
 
     ab = algorithmic_bytes(cfg)
     keep_bytes = cfg.units * cfg.k * 4
-    ab["call"] -= int((1.0 - moved) * 0.75 * (ab["compact"] - keep_bytes))       # only moved rows travel
-    ab["compact"] = int(moved * (ab["compact"] - keep_bytes)) + keep_bytes
+    row_bytes = ab["compact"] - keep_bytes                                        # K and V rows read and written
+    ab["call"] -= int((1.0 - moved) * 0.75 * row_bytes)                          # only moved rows travel
+    ab["compact"] -= int((1.0 - moved) * row_bytes)
+    ab["select_compact"] -= int((1.0 - moved) * row_bytes)
     def roofline_of(stage):
         t = stage_avg_us[stage] * 1e-6
         if stage in ("score_stats", "score_prob"):

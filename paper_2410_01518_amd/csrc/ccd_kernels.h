@@ -55,6 +55,10 @@ void launch_nuc_mask(const Dims& D, const float* novelty, uint8_t* mask, hipStre
 void launch_finalize_select(const Dims& D, const float* u, const uint8_t* mask, float* scores,
                             int32_t* keep_idx, hipStream_t s);
 
+// selection and compaction of a unit in one workgroup (rows short enough to be staged in LDS)
+bool select_compact_supported(const Dims& D);
+void launch_select_compact(const Dims& D, const float* u, const uint8_t* mask, float* scores, int32_t* keep_idx, void* K,
+                           void* V, float* novelty, hipStream_t s);
 int select_max_tokens();   // largest n the selection kernel handles
 
 void launch_compact(const Dims& D, const void* Ksrc, const void* Vsrc, const int32_t* keep_idx,

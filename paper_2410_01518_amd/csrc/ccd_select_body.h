@@ -61,12 +61,13 @@ __device__ __forceinline__ void pooled_block(float (&out)[KPT], const float* sta
 // Executed by a whole workgroup of THREADS threads, each owning at most KPT tokens (n <= THREADS * KPT).
 // u_stage (LDS, THREADS * KPT + 2 * kStagePad floats, 16-byte aligned, or null): the unit's row of u is copied there
 // first, so that the pooling window reads LDS instead of issuing a chain of dependent global loads per token.
-// BLOCKED needs u_stage.
+// BLOCKED needs u_stage.  keep_lds (BLOCKED only, or null): a second copy of the kept indices, k entries in LDS; it
+// may alias u_stage.  Ends without a barrier.
 template <int THREADS, int KPT, bool BLOCKED>
 __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, const float* __restrict__ u,
                                                      const uint8_t* __restrict__ mask, float* scores,
                                                      int32_t* __restrict__ keep_idx, TopkShared<THREADS>& sh,
-                                                     float* u_stage) {
+                                                     float* u_stage, int32_t* keep_lds = nullptr) {
   const int tid = threadIdx.x, n = D.n;
   int phase = 0;
   float sc[KPT];
@@ -112,8 +113,8 @@ __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, co
     }
   }
 
-  if (keep_idx != nullptr) {
-    int32_t* out = keep_idx + (int64_t)unit * D.k;
+  if (keep_idx != nullptr || keep_lds != nullptr) {
+    int32_t* out = keep_idx != nullptr ? keep_idx + (int64_t)unit * D.k : nullptr;
     uint32_t key[KPT];
 #pragma unroll
     for (int j = 0; j < KPT; ++j) key[j] = score_key(sc[j]);
@@ -140,7 +141,11 @@ __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, co
       uint32_t pos = block_exclusive_scan<THREADS>(n_sel, sh, phase, tot);
 #pragma unroll
       for (int j = 0; j < KPT; ++j)
-        if (sel_bits & (1u << j)) out[pos++] = tid * KPT + j;
+        if (sel_bits & (1u << j)) {
+          if (out != nullptr) out[pos] = tid * KPT + j;
+          if (keep_lds != nullptr) keep_lds[pos] = tid * KPT + j;
+          ++pos;
+        }
     } else {
       uint32_t eq_base = 0, out_base = 0;
 #pragma unroll

@@ -147,9 +147,9 @@ static int check_workspace(const Workspace& w, const void* ws, size_t ws_bytes) 
 }
 
 // ---- optional per-kernel timing of ccd_compress -------------------------------------------------------
-enum Stage { kStNuc = 0, kStStats, kStMerge, kStProb, kStSelect, kStCompact, kNumStages };
+enum Stage { kStNuc = 0, kStStats, kStMerge, kStProb, kStSelect, kStCompact, kStSelCompact, kNumStages };
 static const char* const kStageNames[kNumStages] = {"nuc_mask", "score_stats", "score_merge", "score_prob", "select",
-                                                    "compact"};
+                                                    "compact",  "select_compact"};
 
 // Every profiled launch is bracketed by two events on the stream it runs on.
 struct Profiler {
@@ -292,6 +292,12 @@ int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, 
   const bool per_head = shape->nov_stride_l != 0 || shape->nov_stride_h != 0;
   if (g_prof.on) ++g_prof.calls;
   run_mask_and_cap_scores(D, pl, w, Q_cat, K, novelty, ws, st);
+  if (select_compact_supported(D)) {
+    g_prof.begin(kStSelCompact, st);
+    launch_select_compact(D, u, mask, scores_opt, keep_idx, K, V, per_head ? novelty : nullptr, st);
+    g_prof.end(st);
+    return launch_status();
+  }
   g_prof.begin(kStSelect, st);
   launch_finalize_select(D, u, mask, scores_opt, keep_idx, st);
   g_prof.end(st);
