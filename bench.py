@@ -26,8 +26,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 VALU_FP32_PEAK_TFLOPS = 157.3
 # HBM bytes per launch on the headline config from the committed rocprofv3 counter runs
 # (profiles/ccd_compress_c3_hbm_traffic.md: read requests x 128 B + WRITE_SIZE; a plain copy reads factor 1.00)
-MEASURED_TRAFFIC_C3 = {"score_stats": 287_900_000, "score_prob": 291_700_000, "compact": 539_600_000,
-                       "select": 4_300_000, "select_compact": None}
+MEASURED_TRAFFIC_C3 = {"score_stats": 287_600_000, "score_prob": 290_600_000, "select_compact": 543_100_000}
 
 
 def algorithmic_bytes(cfg) -> dict:
