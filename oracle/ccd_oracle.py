@@ -33,12 +33,21 @@ Steps, per unit (sequence b, layer l, KV head h), in the paper's order:
                 top-k per head; ties go to the lower index; the kept indices
                 are emitted in ascending (temporal) order.
   compact       App. B: K' = K[keep], V' = V[keep] (bit copies).
+  cr_rope       Sec. 3.5 (CR-RoPE): the pot holds keys before the rotary embedding; after a
+                distillation the kept entries get the rotary embedding of positions
+                0 .. |C|-1 (their new places), whatever their original positions were.
 
 Parity status of the choices the paper does not fix (pool mode, the GQA
 reduction, softmax over context tokens only, +inf sentinel, per-head carried
 novelty): pinned by the benchmark's wording only - "parity unpinned" against
 the paper for those choices.  All arithmetic (softmax-sum, pooling, top-k,
 gather) is pinned by the tests in tests/test_oracle_pins.py.
+
+CR-RoPE: the paper names RoPE without fixing the pairing of dimensions; the
+half-split pairing (dimension i with i + d/2) of the LLaMA / Mistral models it
+evaluates is used - "parity unpinned" for that choice.  The rotation itself
+is pinned in tests/test_oracle_rope_pins.py.  Angle tables are inputs (the
+caller's rope base and scaling), as are the positions.
 """
 from __future__ import annotations
 
@@ -139,6 +148,52 @@ def compact(X: np.ndarray, keep: np.ndarray) -> np.ndarray:
     return X[np.asarray(keep, dtype=np.int64)].copy()
 
 
+def rope_tables(n_pos: int, d: int, base: float = 10000.0):
+    """cos, sin [n_pos, d/2] of the angles p * base**(-2i/d) (RoPE's frequencies), as float32 tables.
+
+    The tables are the INPUT of the re-application (library and oracle read the same fp32 values)."""
+    i = np.arange(d // 2, dtype=np.float64)
+    ang = np.arange(n_pos, dtype=np.float64)[:, None] * base ** (-2.0 * i / d)[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def rope_rotate(X: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
+    """Rotary embedding of the rows of X [n, d] (fp64) by the angles whose cos/sin are given, [n, d/2].
+
+    Dimension i is paired with dimension i + d/2 and the pair is rotated by angle[n, i]:
+        y_i       = x_i * cos - x_{i+d/2} * sin
+        y_{i+d/2} = x_{i+d/2} * cos + x_i * sin
+    """
+    X = np.asarray(X, dtype=np.float64)
+    h = X.shape[-1] // 2
+    c, s = np.asarray(cos, dtype=np.float64), np.asarray(sin, dtype=np.float64)
+    x1, x2 = X[..., :h], X[..., h:]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def round_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """fp64 -> bf16 storage bits, round to nearest even, straight from the fp64 value (8 significant bits).
+
+    Normal range only (|x| in [2^-126, 2^127]); a zero keeps its sign.  Overflow and subnormals are not needed here."""
+    x = np.asarray(x, dtype=np.float64)
+    m, e = np.frexp(x)                       # x = m * 2^e, 0.5 <= |m| < 1
+    q = np.rint(m * 256.0)                   # 8 significant bits, ties to even
+    y = np.ldexp(q, e - 8).astype(np.float32)   # exactly representable in fp32
+    return (y.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+def cr_rope(K_kept: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
+    """Sec. 3.5: rotary embedding of the kept (pre-RoPE) keys at their NEW positions 0 .. k-1.
+
+    K_kept [k, d] in storage form (bf16 bits or fp32); cos/sin tables with at least k rows.  The result is
+    rounded once to the storage type."""
+    k = K_kept.shape[0]
+    y = rope_rotate(to_f64(K_kept), cos[:k], sin[:k])
+    if np.asarray(K_kept).dtype == np.uint16:
+        return round_bf16_bits(y)
+    return y.astype(np.float32)
+
+
 def score_unit(Q, K, novelty, *, T, scale, pool_w, pool_mode):
     """Final fp32 scores of one unit. Q [G*P, d], K [n, d] raw inputs; novelty [n] fp32."""
     u = cap_scores(to_f64(Q), to_f64(K), scale)
@@ -151,7 +206,7 @@ def default_scale(d: int) -> float:
 
 
 def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=None,
-             n_valid=None, units=None):
+             n_valid=None, units=None, rope_cos=None, rope_sin=None):
     """One CCD compression over a whole cache.
 
     Q_cat [B, L, Hq, P, d]; K, V [B, L, Hkv, n_cap, d]; novelty [B, n] (shared by
@@ -159,7 +214,8 @@ def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=
     with scores [B, L, Hkv, n] fp32, keep_idx [B, L, Hkv, k] int32, K', V'
     [B, L, Hkv, k, d] and, for per-head novelty, novelty' [B, L, Hkv, k].
     `units` optionally restricts the work to a list of (b, l, h) triples; the
-    other entries of the outputs stay zero.
+    other entries of the outputs stay zero.  With rope_cos / rope_sin [>= k, d/2] the
+    dict also holds K_rot [B, L, Hkv, k, d]: the kept keys after CR-RoPE (Sec. 3.5).
     """
     B, L, Hq, P, d = Q_cat.shape
     Hkv, n_cap = K.shape[2], K.shape[3]
@@ -173,6 +229,7 @@ def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=
     Kc = np.zeros((B, L, Hkv, k, d), dtype=K.dtype)
     Vc = np.zeros((B, L, Hkv, k, d), dtype=V.dtype)
     novc = np.zeros((B, L, Hkv, k), dtype=np.float32) if per_head else None
+    Krot = np.zeros((B, L, Hkv, k, d), dtype=K.dtype) if rope_cos is not None else None
     todo = units if units is not None else [(b, l, h) for b in range(B) for l in range(L) for h in range(Hkv)]
     for (b, l, h) in todo:
         Qu = Q_cat[b, l, h * G:(h + 1) * G].reshape(G * P, d)
@@ -185,4 +242,6 @@ def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=
         Vc[b, l, h] = compact(V[b, l, h], keep)
         if per_head:
             novc[b, l, h] = compact(novelty[b, l, h], keep)
-    return {"scores": scores, "keep_idx": keep_idx, "K": Kc, "V": Vc, "novelty": novc}
+        if Krot is not None:
+            Krot[b, l, h] = cr_rope(Kc[b, l, h], rope_cos, rope_sin)
+    return {"scores": scores, "keep_idx": keep_idx, "K": Kc, "V": Vc, "novelty": novc, "K_rot": Krot}
