@@ -62,6 +62,8 @@ def main() -> int:
                     help="pots cycled through (0: one fresh pot per call of a pass, as far as 60 %% of free HBM allows)")
     ap.add_argument("--config", default="c3")
     ap.add_argument("--score-path", type=int, default=0, help="0 auto (matrix cores for bf16), 1 vector ALUs")
+    ap.add_argument("--rope", action="store_true",
+                    help="time ccd_compress_rope (CR-RoPE of the kept keys written on the side) instead of ccd_compress")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for scaling rocprofv3's "
@@ -128,9 +130,18 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    if args.rope:
+        cos_h, sin_h = synth.rope_tables(cfg.k, cfg.d)
+        rope_cos, rope_sin = torch.from_numpy(cos_h).to(dev), torch.from_numpy(sin_h).to(dev)
+        k_rot = torch.empty_like(dev0["K"])
+
     def step(i):
         K, V = pots[i % len(pots)]
-        rc = ip.ccd_compress(shape, qsets[i % len(qsets)], K, V, novs[i % len(novs)], keep, ws, stream=stream)
+        if args.rope:
+            rc = ip.ccd_compress_rope(shape, qsets[i % len(qsets)], K, V, novs[i % len(novs)], keep, rope_cos, rope_sin,
+                                      k_rot, ws, stream=stream)
+        else:
+            rc = ip.ccd_compress(shape, qsets[i % len(qsets)], K, V, novs[i % len(novs)], keep, ws, stream=stream)
         assert rc == ip.CCD_OK, rc
 
     for i in range(args.warmup):
@@ -166,6 +177,10 @@ def main() -> int:
     ab["call"] -= int((1.0 - moved) * 0.75 * row_bytes)                          # only moved rows travel
     ab["compact"] -= int((1.0 - moved) * row_bytes)
     ab["select_compact"] -= int((1.0 - moved) * row_bytes)
+    if args.rope:                                # every kept K row is read (moved or not) and K_rot is written
+        extra = int((1.0 - moved) * row_bytes / 4) + row_bytes // 4
+        ab["select_compact"] += extra
+        ab["call"] += extra
     def roofline_of(stage):
         t = stage_avg_us[stage] * 1e-6
         if stage in ("score_stats", "score_prob"):
@@ -177,7 +192,7 @@ def main() -> int:
         else:
             r = {"kernel": stage, "bound": "hbm", "achieved": ab[stage] / t / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
         r["frac"] = r["achieved"] / r["peak"]
-        r["traffic"] = MEASURED_TRAFFIC_C3.get(stage) if cfg.name == "c3" and args.score_path == 0 else None
+        r["traffic"] = MEASURED_TRAFFIC_C3.get(stage) if cfg.name == "c3" and args.score_path == 0 and not args.rope else None
         r["traffic_source"] = "profiles/ccd_compress_c3_hbm_traffic.md" if r["traffic"] else None
         r["avg_us"] = stage_avg_us[stage]
         return r
@@ -188,7 +203,9 @@ def main() -> int:
 
     call_gbps = ab["call"] / (ms_per_step * 1e-3) / 1e9
     out = {
-        "metric": "ccd_compress calls/s (fused score+select+compact, 32L x 8KV x 128d pot 4096->2048)",
+        "metric": ("ccd_compress_rope calls/s (fused score+select+compact+CR-RoPE, 32L x 8KV x 128d pot 4096->2048)"
+                   if args.rope else
+                   "ccd_compress calls/s (fused score+select+compact, 32L x 8KV x 128d pot 4096->2048)"),
         "value": 1e3 / ms_per_step, "unit": "calls/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",

@@ -103,6 +103,24 @@ CCD_API int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, v
                  float* scores_opt, int32_t* keep_idx, void* workspace, size_t workspace_bytes,
                  void* hip_stream);
 
+/* CR-RoPE (Sec. 3.5).  The pot stores keys BEFORE the rotary position embedding; after a distillation the kept
+ * keys are embedded at their NEW positions 0 .. |C|-1.  ccd_cr_rope writes, for every unit, K_rot[j] = the rotary
+ * embedding at position j of row j of K, for j < count (0 <= count <= n_cap); rows >= count of K_rot are left as they
+ * are.  K_rot has the layout and strides of K and must not be K.  rope_cos and rope_sin are fp32 device tables
+ * [>= count, d/2], dense (row stride d/2), 16-byte aligned: entry [p, i] is the cosine / sine of the angle of position
+ * p for the pair (i, i + d/2): y_i = x_i cos - x_{i+d/2} sin, y_{i+d/2} = x_{i+d/2} cos + x_i sin (the caller's rope
+ * base and scaling are in the tables).  Computed in fp32, rounded once to the cache's type (bf16: nearest even).
+ * Only B, L, Hkv, d, n_valid, n_cap, k, dtype and the kv strides of the shape are read. */
+CCD_API int ccd_cr_rope(const ccd_shape_t* shape, const void* K, const float* rope_cos, const float* rope_sin,
+                int32_t count, void* K_rot, void* hip_stream);
+
+/* ccd_compress with CR-RoPE in the same pass: as ccd_compress, and K_rot[j] = the rotary embedding at position j of
+ * the j-th kept key, j < k (tables with at least k rows).  The pot itself keeps the un-embedded keys.  K_rot must
+ * not be NULL, K or V.  On CCD_NOOP nothing is written, K_rot included. */
+CCD_API int ccd_compress_rope(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty,
+                      float* scores_opt, int32_t* keep_idx, const float* rope_cos, const float* rope_sin,
+                      void* K_rot, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Process-wide choice of kernels: 0 = automatic (bf16: matrix cores; fp32: vector ALUs), 1 = vector ALUs
  * everywhere.  Meant for profiling one path against the other; returns CCD_EINVAL for any other value. */
 CCD_API int ccd_set_score_path(int path);

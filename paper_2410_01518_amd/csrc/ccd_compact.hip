@@ -7,6 +7,7 @@
 // [c*R, (c+1)*R), and every later chunk reads only rows >= (c+1)*R, so the only reads a store could overtake
 // are those of its own chunk, which the barrier orders.  Out of place the same code runs without the barrier.
 #include "ccd_common.h"
+#include "ccd_rope.h"
 #include "ccd_select_body.h"
 
 namespace ccd {
@@ -96,11 +97,14 @@ __global__ __launch_bounds__(kCpThreads) void compact_novelty_kernel(Dims D, con
 // runs as fast as with a workgroup per tensor (measured 88.5 against 89.3 us).
 constexpr int kScUnroll = 2;
 
-template <int KPT, int ROWB>
+// ROPE (CR-RoPE, Sec. 3.5): the kernel also writes Krot[j] = rotary embedding at position j of the kept key j, for all
+// j < k (rows that stay where they are included, so every kept K row is read); the pot itself keeps the plain keys.
+template <int KPT, int ROWB, bool ROPE, bool BF16>
 __global__ __launch_bounds__(kCpThreads) void select_compact_kernel(Dims D, const float* __restrict__ u,
                                                                     const uint8_t* __restrict__ mask, float* scores,
                                                                     int32_t* __restrict__ keep_idx, char* Kbuf,
-                                                                    char* Vbuf) {
+                                                                    char* Vbuf, const float* __restrict__ rope_cos,
+                                                                    const float* __restrict__ rope_sin, char* Krot) {
   __shared__ TopkShared<kCpThreads> sh;
   __shared__ __attribute__((aligned(16))) float u_stage[KPT * kCpThreads + 2 * kStagePad];
   int32_t* keep_lds = reinterpret_cast<int32_t*>(u_stage);
@@ -113,11 +117,15 @@ __global__ __launch_bounds__(kCpThreads) void select_compact_kernel(Dims D, cons
   const int64_t ubytes = kv_offset(D, decode_unit(D, unit)) * (int64_t)(ROWB / D.d);
   char* kb = Kbuf + ubytes;
   char* vb = Vbuf + ubytes;
-  const int lane_off = (threadIdx.x % kLanesPerRow) * 16;
+  char* rb = ROPE ? Krot + ubytes : nullptr;
+  const int lane_in_row = threadIdx.x % kLanesPerRow;
+  const int lane_off = lane_in_row * 16;
   const int row_in_pass = threadIdx.x / kLanesPerRow;
+  const int half_d = D.d / 2;
   for (int base = 0; base < D.k; base += kRowsPerPass * kScUnroll) {
     uint4 a[kScUnroll], b[kScUnroll];
     bool move[kScUnroll];
+    RopeCoef<ROWB, BF16> coef[ROPE ? kScUnroll : 1];
 #pragma unroll
     for (int i = 0; i < kScUnroll; ++i) {
       const int j = base + i * kRowsPerPass + row_in_pass;
@@ -125,10 +133,9 @@ __global__ __launch_bounds__(kCpThreads) void select_compact_kernel(Dims D, cons
       if (j < D.k) {
         const int sidx = keep_lds[j];             // written by this workgroup: ascending, in [j, n)
         move[i] = sidx != j;
-        if (move[i]) {
-          a[i] = load_streaming(kb + (int64_t)sidx * ROWB + lane_off);
-          b[i] = load_streaming(vb + (int64_t)sidx * ROWB + lane_off);
-        }
+        if (move[i] || ROPE) a[i] = load_streaming(kb + (int64_t)sidx * ROWB + lane_off);
+        if (move[i]) b[i] = load_streaming(vb + (int64_t)sidx * ROWB + lane_off);
+        if (ROPE) coef[i].load(lane_in_row, rope_cos + (int64_t)j * half_d, rope_sin + (int64_t)j * half_d);
       }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -140,31 +147,75 @@ __global__ __launch_bounds__(kCpThreads) void select_compact_kernel(Dims D, cons
         store_streaming(kb + (int64_t)j * ROWB + lane_off, a[i]);
         store_streaming(vb + (int64_t)j * ROWB + lane_off, b[i]);
       }
+      if (ROPE && j < D.k)
+        store_streaming(rb + (int64_t)j * ROWB + lane_off, rope_lane<ROWB, BF16>(a[i], lane_in_row, coef[ROPE ? i : 0]));
     }
   }
+}
+
+// Stand-alone CR-RoPE: Krot[j] = rotary embedding at position j of K[j], j < count, for every unit of the launch.
+template <int ROWB, bool BF16>
+__global__ __launch_bounds__(256) void rope_rows_kernel(Dims D, const char* __restrict__ Kbuf,
+                                                        const float* __restrict__ rope_cos,
+                                                        const float* __restrict__ rope_sin, int count, char* Krot) {
+  constexpr int kLanesPerRow = ROWB / 16;
+  constexpr int kRowsPerBlock = 256 / kLanesPerRow;
+  const int blocks_per_unit = (count + kRowsPerBlock - 1) / kRowsPerBlock;
+  const int unit = D.unit0 + blockIdx.x / blocks_per_unit;
+  const int64_t ubytes = kv_offset(D, decode_unit(D, unit)) * (int64_t)(ROWB / D.d);
+  const int lane_in_row = threadIdx.x % kLanesPerRow;
+  const int j = (blockIdx.x % blocks_per_unit) * kRowsPerBlock + threadIdx.x / kLanesPerRow;
+  if (j >= count) return;                                      // whole rows leave together
+  const int half_d = D.d / 2;
+  const uint4 x = load_streaming(Kbuf + ubytes + (int64_t)j * ROWB + lane_in_row * 16);
+  RopeCoef<ROWB, BF16> coef;
+  coef.load(lane_in_row, rope_cos + (int64_t)j * half_d, rope_sin + (int64_t)j * half_d);
+  store_streaming(Krot + ubytes + (int64_t)j * ROWB + lane_in_row * 16, rope_lane<ROWB, BF16>(x, lane_in_row, coef));
 }
 
 }  // namespace
 
 bool select_compact_supported(const Dims& D) { return D.n <= 16 * kCpThreads; }
 
-// pooling + NuC lift + top-k + in-place compaction of K and V; per-head novelty (if given) follows in its own kernel
+// pooling + NuC lift + top-k + in-place compaction of K and V; per-head novelty (if given) follows in its own kernel.
+// Krot != nullptr: CR-RoPE of the kept keys on the side (rope_cos / rope_sin: [>= k, d/2] fp32).
 void launch_select_compact(const Dims& D, const float* u, const uint8_t* mask, float* scores, int32_t* keep_idx, void* K,
-                           void* V, float* novelty, hipStream_t s) {
+                           void* V, float* novelty, const float* rope_cos, const float* rope_sin, void* Krot,
+                           hipStream_t s) {
   const int rowb = D.d * (D.dtype == 0 ? 4 : 2);
   const dim3 grid(D.units_run), block(kCpThreads);
-#define CCD_LAUNCH(KPT, RB) \
-  hipLaunchKernelGGL((select_compact_kernel<KPT, RB>), grid, block, 0, s, D, u, mask, scores, keep_idx, (char*)K, (char*)V)
-#define CCD_LAUNCH_RB(KPT)            \
-  if (rowb == 128) CCD_LAUNCH(KPT, 128);   \
-  else if (rowb == 256) CCD_LAUNCH(KPT, 256); \
-  else CCD_LAUNCH(KPT, 512)
-  if (D.n <= 4 * kCpThreads) { CCD_LAUNCH_RB(4); }
-  else { CCD_LAUNCH_RB(16); }
+#define CCD_LAUNCH(KPT, RB, ROPE, BF)                                                                                  \
+  hipLaunchKernelGGL((select_compact_kernel<KPT, RB, ROPE, BF>), grid, block, 0, s, D, u, mask, scores, keep_idx, (char*)K, \
+                     (char*)V, rope_cos, rope_sin, (char*)Krot)
+#define CCD_LAUNCH_RB(KPT, ROPE)                                         \
+  if (rowb == 128) CCD_LAUNCH(KPT, 128, ROPE, true);                      \
+  else if (rowb == 256 && D.dtype == 1) CCD_LAUNCH(KPT, 256, ROPE, true);  \
+  else if (rowb == 256) CCD_LAUNCH(KPT, 256, ROPE, false);                 \
+  else CCD_LAUNCH(KPT, 512, ROPE, false)
+  const bool small = D.n <= 4 * kCpThreads;
+  if (Krot == nullptr) {
+    if (small) { CCD_LAUNCH_RB(4, false); } else { CCD_LAUNCH_RB(16, false); }
+  } else {
+    if (small) { CCD_LAUNCH_RB(4, true); } else { CCD_LAUNCH_RB(16, true); }
+  }
 #undef CCD_LAUNCH_RB
 #undef CCD_LAUNCH
   if (novelty != nullptr)
     hipLaunchKernelGGL(compact_novelty_kernel, dim3(D.units_run), block, 0, s, D, keep_idx, novelty);
+}
+
+void launch_rope_rows(const Dims& D, const void* K, const float* rope_cos, const float* rope_sin, int count, void* Krot,
+                      hipStream_t s) {
+  const int rowb = D.d * (D.dtype == 0 ? 4 : 2);
+  const int rows_per_block = 256 / (rowb / 16);
+  const dim3 grid((unsigned)((count + rows_per_block - 1) / rows_per_block) * (unsigned)D.units_run), block(256);
+#define CCD_LAUNCH(RB, BF) \
+  hipLaunchKernelGGL((rope_rows_kernel<RB, BF>), grid, block, 0, s, D, (const char*)K, rope_cos, rope_sin, count, (char*)Krot)
+  if (rowb == 128) CCD_LAUNCH(128, true);
+  else if (rowb == 256 && D.dtype == 1) CCD_LAUNCH(256, true);
+  else if (rowb == 256) CCD_LAUNCH(256, false);
+  else CCD_LAUNCH(512, false);
+#undef CCD_LAUNCH
 }
 
 void launch_compact(const Dims& D, const void* Ksrc, const void* Vsrc, const int32_t* keep_idx, void* Kdst, void* Vdst,

@@ -58,7 +58,11 @@ void launch_finalize_select(const Dims& D, const float* u, const uint8_t* mask, 
 // selection and compaction of a unit in one workgroup (rows short enough to be staged in LDS)
 bool select_compact_supported(const Dims& D);
 void launch_select_compact(const Dims& D, const float* u, const uint8_t* mask, float* scores, int32_t* keep_idx, void* K,
-                           void* V, float* novelty, hipStream_t s);
+                           void* V, float* novelty, const float* rope_cos, const float* rope_sin, void* Krot,
+                           hipStream_t s);
+// CR-RoPE of the first `count` rows of every unit (Sec. 3.5): Krot[j] = rotary embedding at position j of K[j]
+void launch_rope_rows(const Dims& D, const void* K, const float* rope_cos, const float* rope_sin, int count, void* Krot,
+                      hipStream_t s);
 int select_max_tokens();   // largest n the selection kernel handles
 
 void launch_compact(const Dims& D, const void* Ksrc, const void* Vsrc, const int32_t* keep_idx,

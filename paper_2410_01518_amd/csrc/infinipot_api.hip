@@ -272,13 +272,19 @@ int ccd_compact(const ccd_shape_t* shape, const void* K_src, const void* V_src, 
   return launch_status();
 }
 
-int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
-                 int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* hip_stream) {
+// ccd_compress, optionally with CR-RoPE of the kept keys on the side (K_rot != nullptr)
+static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
+                         int32_t* keep_idx, const float* rope_cos, const float* rope_sin, void* K_rot, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
   int rc = check_shape(shape, kNeedFull);
   if (rc != CCD_OK) return rc;
   if (Q_cat == nullptr || K == nullptr || V == nullptr || keep_idx == nullptr) return CCD_EINVAL;
   if (novelty == nullptr && shape->T > 0) return CCD_EINVAL;
   if (!aligned16(Q_cat) || !aligned16(K) || !aligned16(V)) return CCD_EALIGN;
+  if (K_rot != nullptr) {
+    if (rope_cos == nullptr || rope_sin == nullptr || K_rot == K || K_rot == V) return CCD_EINVAL;
+    if (!aligned16(K_rot) || !aligned16(rope_cos) || !aligned16(rope_sin)) return CCD_EALIGN;
+  }
   const Dims D = make_dims(shape);
   const ScorePlan pl = plan_score(D);
   const Workspace w = layout_workspace(D);
@@ -294,7 +300,8 @@ int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, 
   run_mask_and_cap_scores(D, pl, w, Q_cat, K, novelty, ws, st);
   if (select_compact_supported(D)) {
     g_prof.begin(kStSelCompact, st);
-    launch_select_compact(D, u, mask, scores_opt, keep_idx, K, V, per_head ? novelty : nullptr, st);
+    launch_select_compact(D, u, mask, scores_opt, keep_idx, K, V, per_head ? novelty : nullptr, rope_cos, rope_sin, K_rot,
+                          st);
     g_prof.end(st);
     return launch_status();
   }
@@ -303,7 +310,35 @@ int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, 
   g_prof.end(st);
   g_prof.begin(kStCompact, st);
   launch_compact(D, K, V, keep_idx, K, V, per_head ? novelty : nullptr, st);
+  if (K_rot != nullptr) launch_rope_rows(D, K, rope_cos, rope_sin, D.k, K_rot, st);
   g_prof.end(st);
+  return launch_status();
+}
+
+int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
+                 int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, nullptr, nullptr, nullptr, workspace,
+                       workspace_bytes, hip_stream);
+}
+
+int ccd_compress_rope(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
+                      int32_t* keep_idx, const float* rope_cos, const float* rope_sin, void* K_rot, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  if (K_rot == nullptr) return CCD_EINVAL;
+  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, rope_cos, rope_sin, K_rot, workspace,
+                       workspace_bytes, hip_stream);
+}
+
+int ccd_cr_rope(const ccd_shape_t* shape, const void* K, const float* rope_cos, const float* rope_sin, int32_t count,
+                void* K_rot, void* hip_stream) {
+  int rc = check_shape(shape, kNeedKV);
+  if (rc != CCD_OK) return rc;
+  if (K == nullptr || K_rot == nullptr || rope_cos == nullptr || rope_sin == nullptr || K_rot == K) return CCD_EINVAL;
+  if (count < 0 || count > shape->n_cap) return CCD_EINVAL;
+  if (!aligned16(K) || !aligned16(K_rot) || !aligned16(rope_cos) || !aligned16(rope_sin)) return CCD_EALIGN;
+  if (count == 0) return CCD_OK;
+  const Dims D = make_dims(shape);
+  launch_rope_rows(D, K, rope_cos, rope_sin, count, K_rot, static_cast<hipStream_t>(hip_stream));
   return launch_status();
 }
 

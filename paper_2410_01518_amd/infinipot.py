@@ -20,8 +20,8 @@ CCD_EINVAL, CCD_EUNSUPPORTED, CCD_EALIGN, CCD_EWORKSPACE, CCD_ELAUNCH = -1, -2, 
 CCD_FP32, CCD_BF16 = 0, 1
 CCD_POOL_NONE, CCD_POOL_MAX, CCD_POOL_AVG = 0, 1, 2
 
-EXPORTS = ("ccd_workspace_bytes", "ccd_score", "ccd_select", "ccd_compact", "ccd_compress",
-           "ccd_set_score_path", "ccd_profile_enable", "ccd_profile_stages", "ccd_profile_stage_name",
+EXPORTS = ("ccd_workspace_bytes", "ccd_score", "ccd_select", "ccd_compact", "ccd_compress", "ccd_cr_rope",
+           "ccd_compress_rope", "ccd_set_score_path", "ccd_profile_enable", "ccd_profile_stages", "ccd_profile_stage_name",
            "ccd_profile_collect", "ccd_strerror")
 
 
@@ -63,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.ccd_compact.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
         L.ccd_compress.restype = ctypes.c_int
         L.ccd_compress.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ccd_cr_rope.restype = ctypes.c_int
+        L.ccd_cr_rope.argtypes = [sp, vp, vp, vp, ctypes.c_int32, vp, vp]
+        L.ccd_compress_rope.restype = ctypes.c_int
+        L.ccd_compress_rope.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.ccd_set_score_path.restype = ctypes.c_int
         L.ccd_set_score_path.argtypes = [ctypes.c_int]
         L.ccd_profile_enable.restype = ctypes.c_int
@@ -162,6 +166,18 @@ def ccd_compress(shape, Q_cat, K, V, novelty, keep_idx, workspace, scores=None, 
     return _check(lib().ccd_compress(ctypes.byref(shape), _ptr(Q_cat), _ptr(K), _ptr(V), _ptr(novelty), _ptr(scores),
                                      _ptr(keep_idx), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                      _stream(stream)))
+
+
+def ccd_cr_rope(shape, K, rope_cos, rope_sin, count, K_rot, stream=None) -> int:
+    return _check(lib().ccd_cr_rope(ctypes.byref(shape), _ptr(K), _ptr(rope_cos), _ptr(rope_sin), int(count), _ptr(K_rot),
+                                    _stream(stream)))
+
+
+def ccd_compress_rope(shape, Q_cat, K, V, novelty, keep_idx, rope_cos, rope_sin, K_rot, workspace, scores=None,
+                      stream=None) -> int:
+    return _check(lib().ccd_compress_rope(ctypes.byref(shape), _ptr(Q_cat), _ptr(K), _ptr(V), _ptr(novelty), _ptr(scores),
+                                          _ptr(keep_idx), _ptr(rope_cos), _ptr(rope_sin), _ptr(K_rot), _ptr(workspace),
+                                          0 if workspace is None else workspace.numel(), _stream(stream)))
 
 
 def ccd_set_score_path(path: int) -> int:

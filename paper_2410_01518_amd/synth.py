@@ -92,3 +92,10 @@ def make_inputs(cfg: CCDConfig, *, per_head_novelty: bool = False, seed: int | N
 def scaled(cfg: CCDConfig, **kw) -> CCDConfig:
     """A copy of a configuration with some fields replaced (test-sized variants)."""
     return replace(cfg, **kw)
+
+
+def rope_tables(n_pos: int, d: int, base: float = 10000.0):
+    """Input tables of the rotary embedding: cos, sin [n_pos, d/2] fp32 of the angles p * base**(-2i/d)."""
+    i = np.arange(d // 2, dtype=np.float64)
+    ang = np.arange(n_pos, dtype=np.float64)[:, None] * base ** (-2.0 * i / d)[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)

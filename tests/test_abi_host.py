@@ -118,6 +118,30 @@ def test_null_misaligned_and_workspace_errors():
     assert L.ccd_set_score_path(7) == ip.CCD_EINVAL and L.ccd_set_score_path(0) == ip.CCD_OK
 
 
+def test_cr_rope_argument_errors_are_decided_on_the_host():
+    s = _shape()
+    L = ip.lib()
+    ws_bytes = ip.ccd_workspace_bytes(s)
+    P2 = P + 0x100000
+
+    def rope(K=P, cos=P, sin=P, count=10, Krot=P2):
+        return L.ccd_cr_rope(ctypes.byref(s), K, cos, sin, count, Krot, None)
+
+    assert rope(K=None) == ip.CCD_EINVAL and rope(cos=None) == ip.CCD_EINVAL and rope(sin=None) == ip.CCD_EINVAL
+    assert rope(Krot=None) == ip.CCD_EINVAL and rope(Krot=P) == ip.CCD_EINVAL          # K_rot must not be K
+    assert rope(count=-1) == ip.CCD_EINVAL and rope(count=s.n_cap + 1) == ip.CCD_EINVAL
+    assert rope(cos=P + 4) == ip.CCD_EALIGN and rope(Krot=P2 + 8) == ip.CCD_EALIGN
+    assert rope(count=0) == ip.CCD_OK                                                   # nothing to do, nothing launched
+
+    def crope(cos=P, sin=P, Krot=P2, shape=s):
+        return L.ccd_compress_rope(ctypes.byref(shape), P, P, P, P, None, P, cos, sin, Krot, 0x10000, ws_bytes, None)
+
+    assert crope(Krot=None) == ip.CCD_EINVAL and crope(cos=None) == ip.CCD_EINVAL and crope(sin=None) == ip.CCD_EINVAL
+    assert crope(Krot=P) == ip.CCD_EINVAL                                               # aliases K (and V)
+    assert crope(sin=P + 4) == ip.CCD_EALIGN
+    assert crope(shape=_shape(n_valid=300, n_cap=512, k=256)) == ip.CCD_NOOP            # pot not full: nothing launched
+
+
 def test_pot_not_full_is_a_noop_decided_on_the_host():
     # Sec. 3.2: distillation only happens once the cache is full.  The fake pointers prove nothing is launched.
     assert _compress(_shape(n_valid=300, n_cap=512, k=256)) == ip.CCD_NOOP
