@@ -227,8 +227,9 @@ def main() -> int:
         sample = [(u // (cfg.L * cfg.Hkv), (u // cfg.Hkv) % cfg.L, u % cfg.Hkv)
                   for u in np.linspace(0, cfg.units - 1, n_units).astype(int)]
         c0 = time.perf_counter()
+        rope_kw = dict(rope_cos=cos_h, rope_sin=sin_h) if args.rope else {}
         O.compress(host0["Q_cat"], host0["K"], host0["V"], host0["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w,
-                   pool_mode=O.POOL_MAX, units=sample)
+                   pool_mode=O.POOL_MAX, units=sample, **rope_kw)
         c1 = time.perf_counter()
         per_call = (c1 - c0) * cfg.units / n_units
         out["cpu_baseline"] = {"value": 1.0 / per_call, "unit": "calls/s", "cores": threads, "kind": "oracle",

@@ -154,23 +154,38 @@ __global__ __launch_bounds__(kCpThreads) void select_compact_kernel(Dims D, cons
 }
 
 // Stand-alone CR-RoPE: Krot[j] = rotary embedding at position j of K[j], j < count, for every unit of the launch.
+// A thread handles kRopeUnroll rows (all their loads in flight together).
+constexpr int kRopeUnroll = 4;
+
 template <int ROWB, bool BF16>
 __global__ __launch_bounds__(256) void rope_rows_kernel(Dims D, const char* __restrict__ Kbuf,
                                                         const float* __restrict__ rope_cos,
                                                         const float* __restrict__ rope_sin, int count, char* Krot) {
   constexpr int kLanesPerRow = ROWB / 16;
-  constexpr int kRowsPerBlock = 256 / kLanesPerRow;
+  constexpr int kRowsPerPass = 256 / kLanesPerRow;
+  constexpr int kRowsPerBlock = kRowsPerPass * kRopeUnroll;
   const int blocks_per_unit = (count + kRowsPerBlock - 1) / kRowsPerBlock;
   const int unit = D.unit0 + blockIdx.x / blocks_per_unit;
   const int64_t ubytes = kv_offset(D, decode_unit(D, unit)) * (int64_t)(ROWB / D.d);
   const int lane_in_row = threadIdx.x % kLanesPerRow;
-  const int j = (blockIdx.x % blocks_per_unit) * kRowsPerBlock + threadIdx.x / kLanesPerRow;
-  if (j >= count) return;                                      // whole rows leave together
+  const int j0 = (blockIdx.x % blocks_per_unit) * kRowsPerBlock + threadIdx.x / kLanesPerRow;
   const int half_d = D.d / 2;
-  const uint4 x = load_streaming(Kbuf + ubytes + (int64_t)j * ROWB + lane_in_row * 16);
-  RopeCoef<ROWB, BF16> coef;
-  coef.load(lane_in_row, rope_cos + (int64_t)j * half_d, rope_sin + (int64_t)j * half_d);
-  store_streaming(Krot + ubytes + (int64_t)j * ROWB + lane_in_row * 16, rope_lane<ROWB, BF16>(x, lane_in_row, coef));
+  uint4 x[kRopeUnroll];
+  RopeCoef<ROWB, BF16> coef[kRopeUnroll];
+#pragma unroll
+  for (int i = 0; i < kRopeUnroll; ++i) {
+    const int j = j0 + i * kRowsPerPass;
+    if (j < count) {                                           // whole rows: both lanes of a pair agree
+      x[i] = load_streaming(Kbuf + ubytes + (int64_t)j * ROWB + lane_in_row * 16);
+      coef[i].load(lane_in_row, rope_cos + (int64_t)j * half_d, rope_sin + (int64_t)j * half_d);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kRopeUnroll; ++i) {
+    const int j = j0 + i * kRowsPerPass;
+    if (j < count)
+      store_streaming(Krot + ubytes + (int64_t)j * ROWB + lane_in_row * 16, rope_lane<ROWB, BF16>(x[i], lane_in_row, coef[i]));
+  }
 }
 
 }  // namespace
@@ -207,7 +222,7 @@ void launch_select_compact(const Dims& D, const float* u, const uint8_t* mask, f
 void launch_rope_rows(const Dims& D, const void* K, const float* rope_cos, const float* rope_sin, int count, void* Krot,
                       hipStream_t s) {
   const int rowb = D.d * (D.dtype == 0 ? 4 : 2);
-  const int rows_per_block = 256 / (rowb / 16);
+  const int rows_per_block = 256 / (rowb / 16) * kRopeUnroll;
   const dim3 grid((unsigned)((count + rows_per_block - 1) / rows_per_block) * (unsigned)D.units_run), block(256);
 #define CCD_LAUNCH(RB, BF) \
   hipLaunchKernelGGL((rope_rows_kernel<RB, BF>), grid, block, 0, s, D, (const char*)K, rope_cos, rope_sin, count, (char*)Krot)
