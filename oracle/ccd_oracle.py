@@ -33,6 +33,11 @@ Steps, per unit (sequence b, layer l, KV head h), in the paper's order:
                 top-k per head; ties go to the lower index; the kept indices
                 are emitted in ascending (temporal) order.
   compact       App. B: K' = K[keep], V' = V[keep] (bit copies).
+  nuc_from_logits  Sec. 3.3.2, Eq. 3 / App. B "Calculate NuC Score": the novelty of a token is its cross
+                entropy under the model, n_t = -log P(x_t | context), read off the logits row that
+                predicts x_t.  (Which context the model saw - the compressed one of Eq. 4 - is the
+                model's forward pass, outside this step; the alignment of logits rows and labels is
+                the caller's: row r must be the prediction FOR label r.)
   cr_rope       Sec. 3.5 (CR-RoPE): the pot holds keys before the rotary embedding; after a
                 distillation the kept entries get the rotary embedding of positions
                 0 .. |C|-1 (their new places), whatever their original positions were.
@@ -146,6 +151,23 @@ def select(scores: np.ndarray, k: int) -> np.ndarray:
 def compact(X: np.ndarray, keep: np.ndarray) -> np.ndarray:
     """Rows of X at the kept indices, in that order (a copy of the stored bits)."""
     return X[np.asarray(keep, dtype=np.int64)].copy()
+
+
+def nuc_from_logits(logits: np.ndarray, labels: np.ndarray) -> np.ndarray:
+    """Eq. 3: per-token cross entropy, n_r = log(sum_v exp(z_rv)) - z_{r, label_r}, as fp32 [rows].
+
+    logits [rows, V] in storage form (fp32 or bf16 bits); labels [rows] integer.  A label outside
+    [0, V) marks a token without a prediction: its novelty is -inf, so it never takes a NuC slot.
+    """
+    z = to_f64(logits)
+    labels = np.asarray(labels).astype(np.int64)
+    rows, V = z.shape
+    out = np.full(rows, -np.inf, dtype=np.float64)
+    for r in range(rows):
+        if 0 <= labels[r] < V:
+            m = z[r].max()
+            out[r] = m + math.log(np.exp(z[r] - m).sum()) - z[r, labels[r]]
+    return out.astype(np.float32)
 
 
 def rope_tables(n_pos: int, d: int, base: float = 10000.0):
