@@ -103,6 +103,16 @@ CCD_API int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, v
                  float* scores_opt, int32_t* keep_idx, void* workspace, size_t workspace_bytes,
                  void* hip_stream);
 
+/* NuC score from the model's logits (Sec. 3.3.2, Eq. 3; App. B "Calculate NuC Score"): the novelty of a token is its
+ * cross entropy under the model, novelty[r] = log(sum_v exp(logits[r][v])) - logits[r][labels[r]], r < rows.
+ * logits: device, [rows, V] of `dtype` (CCD_FP32 or CCD_BF16), rows `row_stride` elements apart (row_stride >= V, a
+ * multiple of 16 bytes; base 16-byte aligned); row r must be the prediction FOR labels[r] (the caller shifts).
+ * labels: device int32 [rows]; a label outside [0, V) marks a token without a prediction and gives -inf, which never
+ * takes a NuC slot.  novelty: device fp32 [rows], the `novelty` input of ccd_score / ccd_compress.  fp32 arithmetic;
+ * rows holding +inf or NaN logits give NaN.  rows == 0 returns CCD_OK and launches nothing. */
+CCD_API int ccd_nuc_from_logits(const void* logits, const int32_t* labels, float* novelty, int64_t rows, int32_t V,
+                        int64_t row_stride, int32_t dtype, void* hip_stream);
+
 /* CR-RoPE (Sec. 3.5).  The pot stores keys BEFORE the rotary position embedding; after a distillation the kept
  * keys are embedded at their NEW positions 0 .. |C|-1.  ccd_cr_rope writes, for every unit, K_rot[j] = the rotary
  * embedding at position j of row j of K, for j < count (0 <= count <= n_cap); rows >= count of K_rot are left as they

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libinfinipot.so")
-SOURCES = ["infinipot_api.hip", "ccd_score_valu.hip", "ccd_score_mfma.hip", "ccd_select.hip", "ccd_compact.hip"]
+SOURCES = ["infinipot_api.hip", "ccd_score_valu.hip", "ccd_score_mfma.hip", "ccd_select.hip", "ccd_compact.hip", "ccd_nuc.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
 

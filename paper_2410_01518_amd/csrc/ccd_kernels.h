@@ -63,6 +63,9 @@ void launch_select_compact(const Dims& D, const float* u, const uint8_t* mask, f
 // CR-RoPE of the first `count` rows of every unit (Sec. 3.5): Krot[j] = rotary embedding at position j of K[j]
 void launch_rope_rows(const Dims& D, const void* K, const float* rope_cos, const float* rope_sin, int count, void* Krot,
                       hipStream_t s);
+// NuC score from logits (Eq. 3): novelty[r] = logsumexp(logits[r, :]) - logits[r, labels[r]]
+void launch_nuc_from_logits(const void* logits, const int32_t* labels, float* novelty, int64_t rows, int V,
+                            int64_t row_stride_elems, int dtype, hipStream_t s);
 int select_max_tokens();   // largest n the selection kernel handles
 
 void launch_compact(const Dims& D, const void* Ksrc, const void* Vsrc, const int32_t* keep_idx,

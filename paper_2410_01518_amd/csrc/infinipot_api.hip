@@ -342,6 +342,17 @@ int ccd_cr_rope(const ccd_shape_t* shape, const void* K, const float* rope_cos, 
   return launch_status();
 }
 
+int ccd_nuc_from_logits(const void* logits, const int32_t* labels, float* novelty, int64_t rows, int32_t V,
+                        int64_t row_stride, int32_t dtype, void* hip_stream) {
+  if (logits == nullptr || labels == nullptr || novelty == nullptr) return CCD_EINVAL;
+  if (rows < 0 || rows > 0x7FFFFFFF || V < 1 || row_stride < V) return CCD_EINVAL;
+  if (dtype != CCD_FP32 && dtype != CCD_BF16) return CCD_EUNSUPPORTED;
+  if (!aligned16(logits) || (row_stride * (dtype == CCD_FP32 ? 4 : 2)) % 16) return CCD_EALIGN;
+  if (rows == 0) return CCD_OK;
+  launch_nuc_from_logits(logits, labels, novelty, rows, V, row_stride, dtype, static_cast<hipStream_t>(hip_stream));
+  return launch_status();
+}
+
 int ccd_set_score_path(int path) {
   if (path < 0 || path > 1) return CCD_EINVAL;
   g_score_path = path;

@@ -10,6 +10,7 @@ from __future__ import annotations
 import ctypes
 import os
 
+import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -21,7 +22,7 @@ CCD_FP32, CCD_BF16 = 0, 1
 CCD_POOL_NONE, CCD_POOL_MAX, CCD_POOL_AVG = 0, 1, 2
 
 EXPORTS = ("ccd_workspace_bytes", "ccd_score", "ccd_select", "ccd_compact", "ccd_compress", "ccd_cr_rope",
-           "ccd_compress_rope", "ccd_set_score_path", "ccd_profile_enable", "ccd_profile_stages", "ccd_profile_stage_name",
+           "ccd_compress_rope", "ccd_nuc_from_logits", "ccd_set_score_path", "ccd_profile_enable", "ccd_profile_stages", "ccd_profile_stage_name",
            "ccd_profile_collect", "ccd_strerror")
 
 
@@ -67,6 +68,8 @@ def lib() -> ctypes.CDLL:
         L.ccd_cr_rope.argtypes = [sp, vp, vp, vp, ctypes.c_int32, vp, vp]
         L.ccd_compress_rope.restype = ctypes.c_int
         L.ccd_compress_rope.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ccd_nuc_from_logits.restype = ctypes.c_int
+        L.ccd_nuc_from_logits.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp]
         L.ccd_set_score_path.restype = ctypes.c_int
         L.ccd_set_score_path.argtypes = [ctypes.c_int]
         L.ccd_profile_enable.restype = ctypes.c_int
@@ -166,6 +169,22 @@ def ccd_compress(shape, Q_cat, K, V, novelty, keep_idx, workspace, scores=None, 
     return _check(lib().ccd_compress(ctypes.byref(shape), _ptr(Q_cat), _ptr(K), _ptr(V), _ptr(novelty), _ptr(scores),
                                      _ptr(keep_idx), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                      _stream(stream)))
+
+
+def ccd_nuc_from_logits(logits, labels, novelty, stream=None) -> int:
+    """novelty[r] = cross entropy of labels[r] under logits[r, :]; logits [..., V] with a dense last axis and equally
+    spaced rows, labels and novelty with the same leading shape (flattened row-major)."""
+    V = logits.shape[-1]
+    assert logits.stride(-1) == 1 and labels.dtype == torch.int32 and novelty.dtype == torch.float32
+    assert labels.is_contiguous() and novelty.is_contiguous() and labels.numel() == novelty.numel()
+    lead = logits.shape[:-1]
+    rows = int(np.prod(lead)) if len(lead) else 1
+    flat = logits.reshape(rows, V) if rows else logits
+    assert rows == 0 or flat.data_ptr() == logits.data_ptr(), "rows must be equally spaced"
+    esz = logits.element_size()
+    stride = flat.stride(0) if rows > 1 else (V * esz + 15) // 16 * 16 // esz   # a single row: any legal stride
+    return _check(lib().ccd_nuc_from_logits(_ptr(logits), _ptr(labels), _ptr(novelty), rows, V, stride,
+                                            _dtype_code(logits), _stream(stream)))
 
 
 def ccd_cr_rope(shape, K, rope_cos, rope_sin, count, K_rot, stream=None) -> int:

@@ -153,3 +153,16 @@ def test_strerror():
         assert len(ip.ccd_strerror(code)) > 0
     with pytest.raises(ip.CCDError):
         ip._check(ip.CCD_EALIGN)
+
+
+def test_nuc_from_logits_argument_errors_are_decided_on_the_host():
+    L = ip.lib()
+
+    def nuc(logits=P, labels=P, nov=P, rows=4, V=1000, stride=1000, dtype=ip.CCD_BF16):
+        return L.ccd_nuc_from_logits(logits, labels, nov, rows, V, stride, dtype, None)
+
+    assert nuc(logits=None) == ip.CCD_EINVAL and nuc(labels=None) == ip.CCD_EINVAL and nuc(nov=None) == ip.CCD_EINVAL
+    assert nuc(rows=-1) == ip.CCD_EINVAL and nuc(V=0) == ip.CCD_EINVAL and nuc(stride=999) == ip.CCD_EINVAL
+    assert nuc(dtype=5) == ip.CCD_EUNSUPPORTED
+    assert nuc(logits=P + 2) == ip.CCD_EALIGN and nuc(V=1001, stride=1001) == ip.CCD_EALIGN     # rows 2002 bytes apart
+    assert nuc(rows=0) == ip.CCD_OK                                                             # nothing launched
