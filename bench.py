@@ -53,6 +53,48 @@ def algorithmic_flops(cfg) -> float:
     return 2.0 * cfg.units * cfg.G * cfg.P * cfg.N * cfg.d
 
 
+def aux_bench(args, cfg, dev, torch, ip, synth) -> int:
+    """Stand-alone companion kernels (HBM-bound): HIP-event time over `steps` calls on rotating cold buffers."""
+    g = torch.Generator(device=dev).manual_seed(77)
+    steps, warmup = min(args.steps, 80), min(args.warmup, 8)
+    if args.aux == "nuc":
+        rows, V = 4096, 128256
+        bufs = [torch.empty((rows, V), dtype=torch.bfloat16, device=dev).normal_(generator=g) for _ in range(4)]
+        labels = torch.randint(0, V, (rows,), generator=g, device=dev, dtype=torch.int32)
+        nov = torch.empty(rows, dtype=torch.float32, device=dev)
+        call = lambda i: ip.ccd_nuc_from_logits(bufs[i % 4], labels, nov)
+        nbytes, work = rows * V * 2 + rows * 8, f"{rows} x {V} bf16 logits"
+        metric = "ccd_nuc_from_logits calls/s (per-token cross entropy, Eq. 3)"
+    else:
+        Ks = [torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N, cfg.d), dtype=torch.bfloat16, device=dev).normal_(generator=g)
+              for _ in range(8)]
+        Q = torch.empty((cfg.B, cfg.L, cfg.Hq, cfg.P, cfg.d), dtype=torch.bfloat16, device=dev)
+        k_rot = torch.empty_like(Ks[0])
+        c, s = synth.rope_tables(cfg.k, cfg.d)
+        c, s = torch.from_numpy(c).to(dev), torch.from_numpy(s).to(dev)
+        shape = ip.make_shape(Q, Ks[0], None, k=cfg.k)
+        call = lambda i: ip.ccd_cr_rope(shape, Ks[i % 8], c, s, cfg.k, k_rot)
+        nbytes, work = 2 * cfg.units * cfg.k * cfg.d * 2, f"{cfg.name}: first {cfg.k} rows of {cfg.units} units, bf16 d{cfg.d}"
+        metric = "ccd_cr_rope calls/s (CR-RoPE of the kept keys, Sec. 3.5)"
+    for i in range(warmup):
+        call(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        call(i)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    gbps = nbytes / (ms * 1e-3) / 1e9
+    print(json.dumps({"metric": metric, "value": 1e3 / ms, "unit": "calls/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+                      "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+                      "data": "synthetic", "config": {"workload": work},
+                      "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                   "frac": gbps / HBM_PEAK_GBPS, "traffic": None}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -64,6 +106,9 @@ def main() -> int:
     ap.add_argument("--score-path", type=int, default=0, help="0 auto (matrix cores for bf16), 1 vector ALUs")
     ap.add_argument("--rope", action="store_true",
                     help="time ccd_compress_rope (CR-RoPE of the kept keys written on the side) instead of ccd_compress")
+    ap.add_argument("--aux", choices=["nuc", "cr_rope"], default=None,
+                    help="time a stand-alone companion kernel instead of the headline call: nuc = ccd_nuc_from_logits on "
+                         "4096 x 128256 bf16 logits, cr_rope = ccd_cr_rope on the kept half of a headline pot")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for scaling rocprofv3's "
@@ -83,6 +128,8 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     ip.lib()
+    if args.aux is not None:
+        return aux_bench(args, cfg, dev, torch, ip, synth)
     ip.ccd_set_score_path(args.score_path)
 
     def upload(a):
