@@ -87,7 +87,25 @@ def aux_bench(args, cfg, dev, torch, ip, synth) -> int:
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / steps
     gbps = nbytes / (ms * 1e-3) / 1e9
-    print(json.dumps({"metric": metric, "value": 1e3 / ms, "unit": "calls/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ccd_oracle as O   # CPU baseline leg only
+        c0 = time.perf_counter()
+        if args.aux == "nuc":
+            n_s = 256
+            O.nuc_from_logits(bufs[0][:n_s].view(torch.int16).cpu().numpy().view(np.uint16), labels[:n_s].cpu().numpy())
+            frac, sample = n_s / rows, f"{n_s} of {rows} rows"
+        else:
+            n_s = 16
+            Kh = Ks[0].view(torch.int16).cpu().numpy().view(np.uint16).reshape(cfg.units, cfg.N, cfg.d)
+            ch, sh_ = synth.rope_tables(cfg.k, cfg.d)
+            for u in range(n_s):
+                O.cr_rope(Kh[u, :cfg.k], ch, sh_)
+            frac, sample = n_s / cfg.units, f"{n_s} of {cfg.units} units"
+        dt = time.perf_counter() - c0
+        cpu = {"value": frac / dt, "unit": "calls/s", "cores": 1, "kind": "oracle",
+               "sample": f"{sample} in {dt:.2f} s, scaled to a whole call"}
+    print(json.dumps({"cpu_baseline": cpu, "metric": metric, "value": 1e3 / ms, "unit": "calls/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
                       "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
                       "data": "synthetic", "config": {"workload": work},
                       "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
