@@ -3,8 +3,8 @@
 // Same two-pass scheme as the vector-ALU kernels (the normaliser of every CaP query over ALL cached tokens is
 // needed before probabilities can be summed over queries); the logits are recomputed in pass 2 rather than kept.
 // A workgroup of 4 waves owns one token slice of one unit.  Each wave keeps the fragments of 64 query rows in
-// registers for the whole slice; K streams HBM -> LDS by DMA in 32-token tiles (two batches of three tiles,
-// XOR-swizzled so that fragment reads are bank-conflict free) and every wave reads each tile.
+// registers for the whole slice; K streams HBM -> LDS by DMA in 32-token tiles (a ring of two batches of three or
+// two tiles, XOR-swizzled so that fragment reads are bank-conflict free) and every wave reads each tile.
 //
 // The 32x32 accumulator tile puts its column index on the lane (lane % 32) and its row index on the register, so
 // the operand order is chosen per pass to make the reduction run along registers, never across lanes:
@@ -15,9 +15,10 @@
 // The fragment a lane holds is the same in both roles: the vector with index lane % 32, elements
 // 8*(lane/32) .. +7 of each 16-element step of the head dimension.
 //
-// The path is bound by the vector ALU (fma + exp2 + add per logit), not by the matrix cores, so the loop is
-// software pipelined inside each wave: the MFMAs of tile s+1 are issued between the ALU instructions that
-// consume tile s, and the scheduler is told to keep that interleave.
+// On this chip the matrix-core time and the vector-ALU time (fma + exp2 + add per logit) of a SIMD add up rather
+// than overlap, so a pass costs their sum.  The loop is still software pipelined inside each wave (the MFMAs of tile
+// s+1 are issued between the ALU instructions that consume tile s): it hides the LDS reads and the little ALU work
+// that does fit under an MFMA.
 #include "ccd_score_mfma.h"
 #include "ccd_topk.h"
 
