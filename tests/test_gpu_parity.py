@@ -268,3 +268,55 @@ def test_non_finite_keys_keep_indices_valid():
     rc, dev, scores, keep = _run_fused(cfg, inp)
     assert rc == ip.CCD_OK
     gu.check_keep_valid(gu.to_host(keep), cfg.N, cfg.k)
+
+
+# ------------------------------------------------------------------ run-to-run behaviour
+
+def test_repeated_calls_give_identical_bits():
+    """Nothing in the path depends on scheduling order (no float atomics, fixed reduction trees): two calls on the same
+    inputs give the same bits in scores, keep_idx, K' and V'."""
+    cfg = _cfg(L=4, N=1500, k=700, T=200)
+    inp = synth.make_inputs(cfg)
+    outs = []
+    for rep in range(3):
+        rc, dev, scores, keep = _run_fused(cfg, inp)
+        assert rc == ip.CCD_OK
+        outs.append((gu.to_host(scores).view(np.uint32), gu.to_host(keep), gu.to_host(dev["K"]), gu.to_host(dev["V"])))
+    for o in outs[1:]:
+        for a, b in zip(outs[0], o):
+            np.testing.assert_array_equal(a, b)
+
+
+def test_compress_in_a_captured_graph_replays_exactly():
+    """The call launches kernels only (no allocation, no memset, no host sync): it can be captured into a HIP graph.
+    Every replay, with eager work and synchronisations in between, must reproduce the eager result."""
+    cfg = _cfg(L=2, N=1100, k=500, T=100)
+    inp = synth.make_inputs(cfg)
+    rc, dev_e, scores_e, keep_e = _run_fused(cfg, inp)
+    assert rc == ip.CCD_OK
+    want = (gu.to_host(scores_e).view(np.uint32), gu.to_host(keep_e), gu.to_host(dev_e["K"]), gu.to_host(dev_e["V"]))
+    dev = _upload(inp)
+    pristine = {k: v.clone() for k, v in dev.items()}
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=O.POOL_MAX)
+    ws = ip.alloc_workspace(shape)
+    scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
+    keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            assert ip.ccd_compress(shape, dev["Q_cat"], dev["K"], dev["V"], dev["novelty"], keep, ws, scores=scores,
+                                   stream=side) == ip.CCD_OK
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for k_, v in pristine.items():                      # eager work between the replays: restore the pot
+            dev[k_].copy_(v)
+        scores.zero_()
+        keep.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (gu.to_host(scores).view(np.uint32), gu.to_host(keep), gu.to_host(dev["K"]), gu.to_host(dev["V"]))
+        for a, b in zip(want, got):
+            np.testing.assert_array_equal(a, b)
