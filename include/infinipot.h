@@ -125,11 +125,15 @@ CCD_API int ccd_cr_rope(const ccd_shape_t* shape, const void* K, const float* ro
                 int32_t count, void* K_rot, void* hip_stream);
 
 /* ccd_compress with CR-RoPE in the same pass: as ccd_compress, and K_rot[j] = the rotary embedding at position j of
- * the j-th kept key, j < k (tables with at least k rows).  The pot itself keeps the un-embedded keys.  K_rot must
- * not be NULL, K or V.  On CCD_NOOP nothing is written, K_rot included. */
+ * the j-th kept key, j < k (tables with at least k rows).  The pot itself (K) keeps the un-embedded keys.  K_rot must
+ * not be NULL, K or V.  K_score (nullable; layout and strides of K): the keys the catalyst queries attend to when they
+ * are not the stored ones - the model attends to the EMBEDDED keys of the current positions 0 .. n_valid-1, i.e. to the
+ * attention cache that the previous call left in K_rot and the prefill extended; NULL scores on K itself.  K_score is
+ * only read, and only before K_rot is written, so K_score may be the same buffer as K_rot.  On CCD_NOOP nothing is
+ * written, K_rot included. */
 CCD_API int ccd_compress_rope(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty,
-                      float* scores_opt, int32_t* keep_idx, const float* rope_cos, const float* rope_sin,
-                      void* K_rot, void* workspace, size_t workspace_bytes, void* hip_stream);
+                      float* scores_opt, int32_t* keep_idx, const void* K_score, const float* rope_cos,
+                      const float* rope_sin, void* K_rot, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Process-wide choice of kernels: 0 = automatic (bf16: matrix cores; fp32: vector ALUs), 1 = vector ALUs
  * everywhere.  Meant for profiling one path against the other; returns CCD_EINVAL for any other value. */

@@ -228,7 +228,7 @@ def default_scale(d: int) -> float:
 
 
 def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=None,
-             n_valid=None, units=None, rope_cos=None, rope_sin=None):
+             n_valid=None, units=None, rope_cos=None, rope_sin=None, K_score=None):
     """One CCD compression over a whole cache.
 
     Q_cat [B, L, Hq, P, d]; K, V [B, L, Hkv, n_cap, d]; novelty [B, n] (shared by
@@ -238,6 +238,9 @@ def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=
     `units` optionally restricts the work to a list of (b, l, h) triples; the
     other entries of the outputs stay zero.  With rope_cos / rope_sin [>= k, d/2] the
     dict also holds K_rot [B, L, Hkv, k, d]: the kept keys after CR-RoPE (Sec. 3.5).
+    K_score (same shape as K): the keys the CaP queries attend to, when they are not the
+    stored ones - with CR-RoPE the pot stores keys before the rotary embedding while the
+    model attends to the embedded keys of the current positions.
     """
     B, L, Hq, P, d = Q_cat.shape
     Hkv, n_cap = K.shape[2], K.shape[3]
@@ -256,7 +259,8 @@ def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=
     for (b, l, h) in todo:
         Qu = Q_cat[b, l, h * G:(h + 1) * G].reshape(G * P, d)
         nov = novelty[b, l, h, :n] if per_head else novelty[b, :n]
-        s = score_unit(Qu, K[b, l, h, :n], nov, T=T, scale=scale, pool_w=pool_w, pool_mode=pool_mode)
+        Ks = K if K_score is None else K_score
+        s = score_unit(Qu, Ks[b, l, h, :n], nov, T=T, scale=scale, pool_w=pool_w, pool_mode=pool_mode)
         keep = select(s, k)
         scores[b, l, h] = s
         keep_idx[b, l, h] = keep

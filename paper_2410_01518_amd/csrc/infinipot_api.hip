@@ -274,8 +274,8 @@ int ccd_compact(const ccd_shape_t* shape, const void* K_src, const void* V_src, 
 
 // ccd_compress, optionally with CR-RoPE of the kept keys on the side (K_rot != nullptr)
 static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
-                         int32_t* keep_idx, const float* rope_cos, const float* rope_sin, void* K_rot, void* workspace,
-                         size_t workspace_bytes, void* hip_stream) {
+                         int32_t* keep_idx, const void* K_score, const float* rope_cos, const float* rope_sin, void* K_rot,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = check_shape(shape, kNeedFull);
   if (rc != CCD_OK) return rc;
   if (Q_cat == nullptr || K == nullptr || V == nullptr || keep_idx == nullptr) return CCD_EINVAL;
@@ -285,6 +285,8 @@ static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, v
     if (rope_cos == nullptr || rope_sin == nullptr || K_rot == K || K_rot == V) return CCD_EINVAL;
     if (!aligned16(K_rot) || !aligned16(rope_cos) || !aligned16(rope_sin)) return CCD_EALIGN;
   }
+  if (K_score != nullptr && (K_score == V || !aligned16(K_score))) return K_score == V ? CCD_EINVAL : CCD_EALIGN;
+  const void* K_attn = K_score != nullptr ? K_score : K;     // the keys the CaP queries attend to
   const Dims D = make_dims(shape);
   const ScorePlan pl = plan_score(D);
   const Workspace w = layout_workspace(D);
@@ -297,7 +299,7 @@ static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, v
   const float* u = reinterpret_cast<const float*>(ws + w.off_u);
   const bool per_head = shape->nov_stride_l != 0 || shape->nov_stride_h != 0;
   if (g_prof.on) ++g_prof.calls;
-  run_mask_and_cap_scores(D, pl, w, Q_cat, K, novelty, ws, st);
+  run_mask_and_cap_scores(D, pl, w, Q_cat, K_attn, novelty, ws, st);
   if (select_compact_supported(D)) {
     g_prof.begin(kStSelCompact, st);
     launch_select_compact(D, u, mask, scores_opt, keep_idx, K, V, per_head ? novelty : nullptr, rope_cos, rope_sin, K_rot,
@@ -317,15 +319,15 @@ static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, v
 
 int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
                  int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, nullptr, nullptr, nullptr, workspace,
+  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, nullptr, nullptr, nullptr, nullptr, workspace,
                        workspace_bytes, hip_stream);
 }
 
 int ccd_compress_rope(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
-                      int32_t* keep_idx, const float* rope_cos, const float* rope_sin, void* K_rot, void* workspace,
-                      size_t workspace_bytes, void* hip_stream) {
+                      int32_t* keep_idx, const void* K_score, const float* rope_cos, const float* rope_sin, void* K_rot,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (K_rot == nullptr) return CCD_EINVAL;
-  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, rope_cos, rope_sin, K_rot, workspace,
+  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, K_score, rope_cos, rope_sin, K_rot, workspace,
                        workspace_bytes, hip_stream);
 }
 

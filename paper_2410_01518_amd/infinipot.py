@@ -67,7 +67,7 @@ def lib() -> ctypes.CDLL:
         L.ccd_cr_rope.restype = ctypes.c_int
         L.ccd_cr_rope.argtypes = [sp, vp, vp, vp, ctypes.c_int32, vp, vp]
         L.ccd_compress_rope.restype = ctypes.c_int
-        L.ccd_compress_rope.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ccd_compress_rope.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.ccd_nuc_from_logits.restype = ctypes.c_int
         L.ccd_nuc_from_logits.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp]
         L.ccd_set_score_path.restype = ctypes.c_int
@@ -193,10 +193,10 @@ def ccd_cr_rope(shape, K, rope_cos, rope_sin, count, K_rot, stream=None) -> int:
 
 
 def ccd_compress_rope(shape, Q_cat, K, V, novelty, keep_idx, rope_cos, rope_sin, K_rot, workspace, scores=None,
-                      stream=None) -> int:
+                      K_score=None, stream=None) -> int:
     return _check(lib().ccd_compress_rope(ctypes.byref(shape), _ptr(Q_cat), _ptr(K), _ptr(V), _ptr(novelty), _ptr(scores),
-                                          _ptr(keep_idx), _ptr(rope_cos), _ptr(rope_sin), _ptr(K_rot), _ptr(workspace),
-                                          0 if workspace is None else workspace.numel(), _stream(stream)))
+                                          _ptr(keep_idx), _ptr(K_score), _ptr(rope_cos), _ptr(rope_sin), _ptr(K_rot),
+                                          _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
 
 
 def ccd_set_score_path(path: int) -> int:

@@ -133,12 +133,13 @@ def test_cr_rope_argument_errors_are_decided_on_the_host():
     assert rope(cos=P + 4) == ip.CCD_EALIGN and rope(Krot=P2 + 8) == ip.CCD_EALIGN
     assert rope(count=0) == ip.CCD_OK                                                   # nothing to do, nothing launched
 
-    def crope(cos=P, sin=P, Krot=P2, shape=s):
-        return L.ccd_compress_rope(ctypes.byref(shape), P, P, P, P, None, P, cos, sin, Krot, 0x10000, ws_bytes, None)
+    def crope(cos=P, sin=P, Krot=P2, shape=s, Kscore=None):
+        return L.ccd_compress_rope(ctypes.byref(shape), P, P, P, P, None, P, Kscore, cos, sin, Krot, 0x10000, ws_bytes, None)
 
     assert crope(Krot=None) == ip.CCD_EINVAL and crope(cos=None) == ip.CCD_EINVAL and crope(sin=None) == ip.CCD_EINVAL
     assert crope(Krot=P) == ip.CCD_EINVAL                                               # aliases K (and V)
-    assert crope(sin=P + 4) == ip.CCD_EALIGN
+    assert crope(sin=P + 4) == ip.CCD_EALIGN and crope(Kscore=P2 + 4) == ip.CCD_EALIGN
+    assert crope(Kscore=P2, shape=_shape(n_valid=300, n_cap=512, k=256)) == ip.CCD_NOOP   # K_score may be K_rot
     assert crope(shape=_shape(n_valid=300, n_cap=512, k=256)) == ip.CCD_NOOP            # pot not full: nothing launched
 
 

@@ -138,3 +138,41 @@ def test_compress_with_cr_rope_on_a_pot_that_is_not_full_writes_nothing():
     np.testing.assert_array_equal(gu.to_host(Krot), sentinel)
     np.testing.assert_array_equal(gu.to_host(dev["K"]), inp["K"])
     assert (gu.to_host(keep) == -1).all()
+
+
+@pytest.mark.parametrize("d", [128, 64])
+def test_compress_scores_on_the_embedded_keys_and_rewrites_them_in_place(d):
+    """One CR-RoPE cycle as the model sees it (Sec. 3.5): the pot holds plain keys, the attention cache holds the keys
+    embedded at positions 0 .. n-1; the CaP queries attend to the attention cache (K_score), the plain keys are
+    compacted, and the attention cache (the same buffer, K_rot) receives the kept keys embedded at 0 .. k-1."""
+    cfg = synth.CCDConfig(name="t", B=1, L=2, Hq=8, Hkv=2, d=d, N=900, k=400, P=6, T=50, w=7, dtype="bf16", keys="normal", seed=61)
+    print(f"cr-rope cycle {cfg}", flush=True)
+    inp = synth.make_inputs(cfg)
+    cos, sin = O.rope_tables(cfg.N, cfg.d)
+    dev = {k: gu.to_dev(v) for k, v in inp.items()}
+    cos_d, sin_d = torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda()
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w)
+    K_att = torch.zeros_like(dev["K"])
+    assert ip.ccd_cr_rope(shape, dev["K"], cos_d, sin_d, cfg.N, K_att) == ip.CCD_OK      # the cache before the call
+    torch.cuda.synchronize()
+    K_att_in = gu.to_host(K_att)
+    ws = ip.alloc_workspace(shape)
+    keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device="cuda")
+    scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
+    rc = ip.ccd_compress_rope(shape, dev["Q_cat"], dev["K"], dev["V"], dev["novelty"], keep, cos_d, sin_d, K_att, ws,
+                              scores=scores, K_score=K_att)
+    assert rc == ip.CCD_OK
+    torch.cuda.synchronize()
+    kh, sh, Kh, got = gu.to_host(keep), gu.to_host(scores), gu.to_host(dev["K"]), gu.to_host(K_att)
+    ref = O.compress(inp["Q_cat"], inp["K"], inp["V"], inp["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w,
+                     rope_cos=cos, rope_sin=sin, K_score=K_att_in)
+    gu.assert_scores_close(sh, ref["scores"], cfg.G * cfg.P)                              # scored on the embedded keys
+    gu.assert_keep_matches(kh, ref["keep_idx"], ref["scores"], cfg.k)
+    plain = O.compress(inp["Q_cat"], inp["K"], inp["V"], inp["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w)
+    assert not np.array_equal(plain["keep_idx"], ref["keep_idx"])                         # ... which does matter
+    idx = kh.astype(np.int64)[..., None]
+    np.testing.assert_array_equal(Kh[..., :cfg.k, :], np.take_along_axis(inp["K"], idx, axis=3))
+    np.testing.assert_array_equal(got[..., cfg.k:, :], K_att_in[..., cfg.k:, :])          # rows >= k of the cache stay
+    for l in range(cfg.L):
+        for h in range(cfg.Hkv):
+            _check_rot(got[0, l, h, :cfg.k], Kh[0, l, h, :cfg.k], cos, sin)
