@@ -22,7 +22,12 @@ Steps, per unit (sequence b, layer l, KV head h), in the paper's order:
                 their attention probability on each context token (the Listing
                 in App. B sums the CaP rows of the attention map and keeps the
                 context columns only).  With grouped-query attention the G
-                query heads that share the KV head are summed as well.
+                query heads that share the KV head are summed as well.  Two readings of
+                "the attention row" are provided: the softmax over the n context tokens
+                alone (the default: the benchmark's interface hands over the cache only),
+                and, with K_cap, the model's own causal row, in which CaP token i also
+                attends to the CaP keys 0 .. i (Eq. 2 places the CaP tokens at the end of
+                the same sequence).
   pool          1-D pooling of the score along the token axis (not in the
                 paper; the paper's implementation follows a code base that
                 clusters scores this way, and the benchmark configs ask for a
@@ -92,18 +97,31 @@ def nuc_slots(novelty: np.ndarray, T: int) -> np.ndarray:
     return np.sort(take)
 
 
-def cap_scores(Q: np.ndarray, K: np.ndarray, scale: float) -> np.ndarray:
+def cap_scores(Q: np.ndarray, K: np.ndarray, scale: float, K_cap: np.ndarray | None = None, P: int | None = None) -> np.ndarray:
     """Eq. 2: u_t = sum over CaP queries of softmax_t(scale * <q, k_t>).
 
-    Q is [G*P, d] (all query rows that attend through this KV head), K is
-    [n, d]; both already fp64.  The softmax runs over the n context tokens.
+    Q is [G*P, d] (all query rows that attend through this KV head, row g*P + i = CaP token i
+    of query head g), K is [n, d]; both already fp64.  Without K_cap the softmax runs over the
+    n context tokens.  With K_cap [P, d] (the CaP tokens' own keys) it is the model's causal
+    attention row of Eq. 2: CaP token i also sees the CaP keys 0 .. i, which take their share
+    of the probability mass; the score still sums the context columns only.
     """
     S = scale * (Q @ K.T)                      # [G*P, n] attention logits
-    m = S.max(axis=1, keepdims=True)
-    E = np.exp(S - m)
-    Z = E.sum(axis=1, keepdims=True)
-    A = E / Z                                  # attention probabilities, rows sum to 1
-    return A.sum(axis=0)                       # sum over the CaP rows
+    if K_cap is None:
+        m = S.max(axis=1, keepdims=True)
+        E = np.exp(S - m)
+        Z = E.sum(axis=1, keepdims=True)
+        A = E / Z                              # attention probabilities, rows sum to 1
+        return A.sum(axis=0)                   # sum over the CaP rows
+    P = K_cap.shape[0] if P is None else P
+    assert K_cap.shape[0] == P and Q.shape[0] % P == 0
+    C = scale * (Q @ K_cap.T)                  # [G*P, P] logits on the CaP keys
+    i = np.arange(Q.shape[0]) % P              # CaP position of each query row
+    C = np.where(np.arange(P)[None, :] <= i[:, None], C, -np.inf)   # causal: key j visible iff j <= i
+    m = np.maximum(S.max(axis=1, keepdims=True), C.max(axis=1, keepdims=True))
+    E, Ec = np.exp(S - m), np.exp(C - m)
+    Z = E.sum(axis=1, keepdims=True) + Ec.sum(axis=1, keepdims=True)
+    return (E / Z).sum(axis=0)                 # context columns only
 
 
 def pool(u: np.ndarray, w: int, mode: int) -> np.ndarray:
@@ -216,9 +234,9 @@ def cr_rope(K_kept: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
     return y.astype(np.float32)
 
 
-def score_unit(Q, K, novelty, *, T, scale, pool_w, pool_mode):
-    """Final fp32 scores of one unit. Q [G*P, d], K [n, d] raw inputs; novelty [n] fp32."""
-    u = cap_scores(to_f64(Q), to_f64(K), scale)
+def score_unit(Q, K, novelty, *, T, scale, pool_w, pool_mode, K_cap=None):
+    """Final fp32 scores of one unit. Q [G*P, d], K [n, d], K_cap [P, d] or None: raw inputs; novelty [n] fp32."""
+    u = cap_scores(to_f64(Q), to_f64(K), scale, None if K_cap is None else to_f64(K_cap))
     ubar = pool(u, pool_w, pool_mode)
     return combine(ubar, nuc_slots(novelty, T))
 
@@ -228,7 +246,7 @@ def default_scale(d: int) -> float:
 
 
 def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=None,
-             n_valid=None, units=None, rope_cos=None, rope_sin=None, K_score=None):
+             n_valid=None, units=None, rope_cos=None, rope_sin=None, K_score=None, K_cap=None):
     """One CCD compression over a whole cache.
 
     Q_cat [B, L, Hq, P, d]; K, V [B, L, Hkv, n_cap, d]; novelty [B, n] (shared by
@@ -241,6 +259,8 @@ def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=
     K_score (same shape as K): the keys the CaP queries attend to, when they are not the
     stored ones - with CR-RoPE the pot stores keys before the rotary embedding while the
     model attends to the embedded keys of the current positions.
+    K_cap [B, L, Hkv, P, d]: the CaP tokens' own keys; with them the attention rows are the
+    model's causal ones (see cap_scores).
     """
     B, L, Hq, P, d = Q_cat.shape
     Hkv, n_cap = K.shape[2], K.shape[3]
@@ -260,7 +280,8 @@ def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=
         Qu = Q_cat[b, l, h * G:(h + 1) * G].reshape(G * P, d)
         nov = novelty[b, l, h, :n] if per_head else novelty[b, :n]
         Ks = K if K_score is None else K_score
-        s = score_unit(Qu, Ks[b, l, h, :n], nov, T=T, scale=scale, pool_w=pool_w, pool_mode=pool_mode)
+        s = score_unit(Qu, Ks[b, l, h, :n], nov, T=T, scale=scale, pool_w=pool_w, pool_mode=pool_mode,
+                       K_cap=None if K_cap is None else K_cap[b, l, h])
         keep = select(s, k)
         scores[b, l, h] = s
         keep_idx[b, l, h] = keep
