@@ -44,6 +44,8 @@ def algorithmic_bytes(cfg) -> dict:
         "compact": 4 * rows + u * k * 4,
         # selection and compaction in one kernel: keep_idx is written once and never read back
         "select_compact": u * N * 4 + cfg.B * N * 4 + u * k * 4 + 4 * rows,
+        # causal variant (--kcat): Q_cat and the CaP keys read, one (max, sum) pair per query written
+        "cap_block": qbytes + u * cfg.P * d * e + u * GP * 8,
         # whole call: K read once, Q_cat once, kept V rows read once, K' and V' written once, keep_idx, novelty
         "call": kbytes + qbytes + rows + 2 * rows + u * k * 4 + cfg.B * N * 4,
     }
@@ -124,6 +126,9 @@ def main() -> int:
     ap.add_argument("--score-path", type=int, default=0, help="0 auto (matrix cores for bf16), 1 vector ALUs")
     ap.add_argument("--rope", action="store_true",
                     help="time ccd_compress_rope (CR-RoPE of the kept keys written on the side) instead of ccd_compress")
+    ap.add_argument("--kcat", action="store_true",
+                    help="the causal variant of Eq. 2: the CaP tokens' own keys join the softmax (ccd_compress_kcat, or "
+                         "ccd_compress_rope with K_cap when combined with --rope)")
     ap.add_argument("--aux", choices=["nuc", "cr_rope"], default=None,
                     help="time a stand-alone companion kernel instead of the headline call: nuc = ccd_nuc_from_logits on "
                          "4096 x 128256 bf16 logits, cr_rope = ccd_cr_rope on the kept half of a headline pot")
@@ -200,11 +205,16 @@ def main() -> int:
         rope_cos, rope_sin = torch.from_numpy(cos_h).to(dev), torch.from_numpy(sin_h).to(dev)
         k_rot = torch.empty_like(dev0["K"])
 
+    k_cap_h = synth.cap_keys(cfg) if args.kcat else None
+    k_cap = upload(k_cap_h) if args.kcat else None
+
     def step(i):
         K, V = pots[i % len(pots)]
         if args.rope:
             rc = ip.ccd_compress_rope(shape, qsets[i % len(qsets)], K, V, novs[i % len(novs)], keep, rope_cos, rope_sin,
-                                      k_rot, ws, stream=stream)
+                                      k_rot, ws, K_cap=k_cap, stream=stream)
+        elif args.kcat:
+            rc = ip.ccd_compress_kcat(shape, qsets[i % len(qsets)], K, V, k_cap, novs[i % len(novs)], keep, ws, stream=stream)
         else:
             rc = ip.ccd_compress(shape, qsets[i % len(qsets)], K, V, novs[i % len(novs)], keep, ws, stream=stream)
         assert rc == ip.CCD_OK, rc
@@ -242,6 +252,8 @@ def main() -> int:
     ab["call"] -= int((1.0 - moved) * 0.75 * row_bytes)                          # only moved rows travel
     ab["compact"] -= int((1.0 - moved) * row_bytes)
     ab["select_compact"] -= int((1.0 - moved) * row_bytes)
+    if args.kcat:
+        ab["call"] += cfg.units * cfg.P * cfg.d * (4 if cfg.dtype == "fp32" else 2)
     if args.rope:                                # every kept K row is read (moved or not) and K_rot is written
         extra = int((1.0 - moved) * row_bytes / 4) + row_bytes // 4
         ab["select_compact"] += extra
@@ -257,7 +269,7 @@ def main() -> int:
         else:
             r = {"kernel": stage, "bound": "hbm", "achieved": ab[stage] / t / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
         r["frac"] = r["achieved"] / r["peak"]
-        r["traffic"] = MEASURED_TRAFFIC_C3.get(stage) if cfg.name == "c3" and args.score_path == 0 and not args.rope else None
+        r["traffic"] = MEASURED_TRAFFIC_C3.get(stage) if cfg.name == "c3" and args.score_path == 0 and not args.rope and not args.kcat else None
         r["traffic_source"] = "profiles/ccd_compress_c3_hbm_traffic.md" if r["traffic"] else None
         r["avg_us"] = stage_avg_us[stage]
         return r
@@ -270,12 +282,15 @@ def main() -> int:
     out = {
         "metric": ("ccd_compress_rope calls/s (fused score+select+compact+CR-RoPE, 32L x 8KV x 128d pot 4096->2048)"
                    if args.rope else
+                   "ccd_compress_kcat calls/s (causal Eq. 2: CaP keys in the softmax; 32L x 8KV x 128d pot 4096->2048)"
+                   if args.kcat else
                    "ccd_compress calls/s (fused score+select+compact, 32L x 8KV x 128d pot 4096->2048)"),
         "value": 1e3 / ms_per_step, "unit": "calls/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B{cfg.B} L{cfg.L} Hq{cfg.Hq} Hkv{cfg.Hkv} d{cfg.d} N{cfg.N}->k{cfg.k} "
-                               f"P{cfg.P} T{cfg.T} pool{cfg.w}", "ring": [len(pots), len(qsets), len(novs)], "score_path": args.score_path},
+                               f"P{cfg.P} T{cfg.T} pool{cfg.w}", "ring": [len(pots), len(qsets), len(novs)], "score_path": args.score_path,
+                   "cap_keys_in_softmax": bool(args.kcat)},
         "call_hbm": {"algorithmic_bytes": ab["call"], "achieved_GBps": call_gbps, "frac_of_peak": call_gbps / HBM_PEAK_GBPS},
         "stage_avg_us": stage_avg_us, "moved_row_fraction": moved,
         "roofline": roof, "roofline_other_kernels": by_kernel,
@@ -293,6 +308,8 @@ def main() -> int:
                   for u in np.linspace(0, cfg.units - 1, n_units).astype(int)]
         c0 = time.perf_counter()
         rope_kw = dict(rope_cos=cos_h, rope_sin=sin_h) if args.rope else {}
+        if args.kcat:
+            rope_kw["K_cap"] = k_cap_h
         O.compress(host0["Q_cat"], host0["K"], host0["V"], host0["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w,
                    pool_mode=O.POOL_MAX, units=sample, **rope_kw)
         c1 = time.perf_counter()

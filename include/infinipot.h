@@ -129,11 +129,24 @@ CCD_API int ccd_cr_rope(const ccd_shape_t* shape, const void* K, const float* ro
  * not be NULL, K or V.  K_score (nullable; layout and strides of K): the keys the catalyst queries attend to when they
  * are not the stored ones - the model attends to the EMBEDDED keys of the current positions 0 .. n_valid-1, i.e. to the
  * attention cache that the previous call left in K_rot and the prefill extended; NULL scores on K itself.  K_score is
- * only read, and only before K_rot is written, so K_score may be the same buffer as K_rot.  On CCD_NOOP nothing is
- * written, K_rot included. */
+ * only read, and only before K_rot is written, so K_score may be the same buffer as K_rot.  K_cap (nullable): the CaP
+ * tokens' own keys as in ccd_score_kcat below, embedded like K_score.  On CCD_NOOP nothing is written, K_rot included. */
 CCD_API int ccd_compress_rope(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty,
-                      float* scores_opt, int32_t* keep_idx, const void* K_score, const float* rope_cos,
-                      const float* rope_sin, void* K_rot, void* workspace, size_t workspace_bytes, void* hip_stream);
+                      float* scores_opt, int32_t* keep_idx, const void* K_score, const void* K_cap,
+                      const float* rope_cos, const float* rope_sin, void* K_rot, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
+
+/* Eq. 2 read as the model's own (causal) attention row: the CaP tokens stand at the end of the sequence, so CaP token
+ * i attends to the cached tokens AND to the CaP keys 0 .. i, which take their share of the probability mass; the
+ * representative score still sums the cached tokens' columns only (App. B slices the CaP columns off).  ccd_score and
+ * ccd_compress normalise over the cached tokens alone; these two take the CaP keys as well.
+ * K_cap: device, [B, L, Hkv, P, d] dense (no strides), of the cache's dtype, 16-byte aligned, only read; must not be
+ * NULL (CCD_EINVAL) nor alias K, V.  Everything else as in ccd_score / ccd_compress; same workspace. */
+CCD_API int ccd_score_kcat(const ccd_shape_t* shape, const void* Q_cat, const void* K, const void* K_cap,
+                   const float* novelty, float* scores, void* workspace, size_t workspace_bytes, void* hip_stream);
+CCD_API int ccd_compress_kcat(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, const void* K_cap,
+                      float* novelty, float* scores_opt, int32_t* keep_idx, void* workspace, size_t workspace_bytes,
+                      void* hip_stream);
 
 /* Process-wide choice of kernels: 0 = automatic (bf16: matrix cores; fp32: vector ALUs), 1 = vector ALUs
  * everywhere.  Meant for profiling one path against the other; returns CCD_EINVAL for any other value. */

@@ -28,6 +28,7 @@ struct ScorePlan {
   int n_slices1;
   int slice2;     // tokens per workgroup in the probability pass
   int n_slices2;
+  int cap_block;  // 1: `part` also holds the statistics of the CaP keys' block (causal variant of Eq. 2)
 };
 
 ScorePlan plan_score(const Dims& D);
@@ -46,8 +47,16 @@ bool stats_hosts_nuc(const Dims& D, const ScorePlan& pl);   // may pass 1 also w
 void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part,
                        const float* novelty, uint8_t* nuc_mask, hipStream_t s);
 // (pass 2 merges the per-slice statistics itself: no merge launch on this path)
-void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float2* part, float* u,
-                      hipStream_t s);
+// K_cap (nullable; [units, P, d], contiguous): the CaP tokens' own keys join the softmax (Eq. 2 read as the model's
+// causal attention row: query row g * P + i also sees the CaP keys 0 .. i); their statistics are computed in the
+// prologue of pass 2 and merged like one more token slice
+void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const void* K_cap,
+                      const float2* part, float* u, hipStream_t s);
+
+// The same on the vector-ALU path: statistics of CaP key j under CaP query i for j <= i, written to `part` behind
+// the slices of all units (pl.cap_block must be 1; launch_merge then takes them in).  K_cap as above.
+void launch_cap_block_stats_valu(const Dims& D, const ScorePlan& pl, const void* Q, const void* K_cap, float2* part,
+                                 hipStream_t s);
 
 // NuC slots: mask[row][t] = 1 for the T tokens of largest novelty (row = sequence when novelty is shared, else unit)
 void launch_nuc_mask(const Dims& D, const float* novelty, uint8_t* mask, hipStream_t s);

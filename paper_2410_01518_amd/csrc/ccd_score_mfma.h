@@ -196,6 +196,54 @@ __device__ __forceinline__ float fold_prob(const floatx16 (&acc)[kQB], const flo
   return s0 + s1;
 }
 
+// The CaP tokens' own keys in the softmax (Eq. 2 read as the model's causal attention row): query row q = g * P + i
+// also sees the CaP keys 0 .. i.  Computes, for the wave's 2 x 32 query rows whose fragments are in bq, the
+// (max2, sum) statistics over the visible CaP keys and returns the pair of the lane's OWN query row
+// qbase + lane (block lane / 32, column lane % 32).  Same operand roles as pass 1 (D[key][query]: a lane owns a
+// query and folds key rows); the P key rows of the unit (Kc, [P, HD]) are too few to stage, so their fragments
+// come straight from global memory like the queries'.
+template <int HD>
+__device__ __forceinline__ float2 cap_block_stats(const Dims& D, const uint16_t* __restrict__ Kc,
+                                                  const bf16x8 (&bq)[kQB][HD / 16], int qbase, int col, int half, float c) {
+  constexpr int KS = HD / 16;
+  int cap_pos[kQB];                               // CaP position i of the lane's query in each block
+  float m_raw[kQB], Z[kQB];
+#pragma unroll
+  for (int qb = 0; qb < kQB; ++qb) {
+    cap_pos[qb] = (qbase + qb * 32 + col) % D.P;
+    m_raw[qb] = kNegHuge;
+    Z[qb] = 0.f;
+  }
+  for (int j0 = 0; j0 < D.P; j0 += kStep) {
+    bf16x8 a[KS];
+    const int j = j0 + col;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      a[ks] = j < D.P ? *reinterpret_cast<const bf16x8*>(Kc + (int64_t)j * HD + half * 8 + ks * 16)
+                      : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    floatx16 acc[kQB];
+    logits<HD, 1>(acc, a, bq);
+    // key row j0 + row is visible to CaP position i iff it is not after it (rows past P are after every i)
+#pragma unroll
+    for (int qb = 0; qb < kQB; ++qb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (j0 + acc_row(r, half) > cap_pos[qb]) acc[qb][r] = -INFINITY;
+    fold_stats<false>(acc, m_raw, Z, c, half, kStep);
+  }
+  float2 own = make_float2(kNegHuge, 0.f);
+#pragma unroll
+  for (int qb = 0; qb < kQB; ++qb) {
+    // the two lane halves hold different key rows of the same query: merge (key 0 is visible to every query and
+    // lies in half 0, so the merged maximum is finite)
+    const float m_o = __shfl_xor(m_raw[qb], 32), z_o = __shfl_xor(Z[qb], 32);
+    const float M = fmaxf(m_raw[qb], m_o);
+    const float z = Z[qb] * fast_exp2((m_raw[qb] - M) * c) + z_o * fast_exp2((m_o - M) * c);
+    if (qb == half) own = make_float2(M * c, z);
+  }
+  return own;
+}
+
 // scheduling shape of one pipelined step: the LDS fragment reads first, a run of ALU work on the current tile
 // to cover their latency, then one MFMA of the next tile per group of ALU instructions
 template <int KS, int VALU_LEAD, int VALU_PER_MFMA>
@@ -209,7 +257,8 @@ __device__ __forceinline__ void interleave_hint() {
   }
 }
 
-// PASS 1 writes part[unit][slice][q] = (max2, sum); PASS 2 reads part (all slices), writes u[unit][t].
+// PASS 1 writes part[unit][slice][q] = (max2, sum); PASS 2 reads part (all slices of the unit), adds the block of
+// the CaP keys in the causal variant (Kcap != nullptr), writes u[unit][t].
 // LDS of one score pass.  The K ring must stay first (DMA destinations are addressed relative to it).
 template <int HD, int PASS>
 struct ScoreLds {
@@ -225,7 +274,7 @@ template <int HD, int PASS>
 __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& pl, int unit, int slice,
                                                 const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
                                                 float2* __restrict__ part, float* __restrict__ u,
-                                                ScoreLds<HD, PASS>& sm) {
+                                                const uint16_t* __restrict__ Kcap, ScoreLds<HD, PASS>& sm) {
   constexpr int KS = HD / 16;
   constexpr int SLOTB = Tiles<HD>::kSlotBytes;
   constexpr int kBatch = Ring<PASS>::kBatch, kDepth = Ring<PASS>::kDepth;
@@ -265,14 +314,18 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
 #pragma unroll
       for (int qb = 0; qb < kQB; ++qb) { m_raw[qb] = kNegHuge; Z[qb] = 0.f; }
     } else {
-      // merge the per-slice statistics of pass 1 into log2-sum-exp per query (thread = query of this sweep)
+      // merge the per-slice statistics of pass 1 into log2-sum-exp per query (thread = query of this sweep: the
+      // thread's own query row is one of its wave's 2 x 32)
       const int q = qc + threadIdx.x;
       float lse = INFINITY;
+      float2 cap = make_float2(kNegHuge, 0.f);         // the block of the CaP keys (causal variant), else nothing
+      if (Kcap != nullptr)
+        cap = cap_block_stats<HD>(D, Kcap + (int64_t)unit * D.P * HD, bq, qc + wave * (kQB * 32), col, half, c);
       if (q < D.GP) {
         const float2* p = part + (int64_t)unit * pl.n_slices1 * D.GP + q;
-        float M = kNegHuge;
+        float M = cap.x;
         for (int j = 0; j < pl.n_slices1; ++j) M = fmaxf(M, p[(int64_t)j * D.GP].x);
-        float z = 0.f;
+        float z = cap.y * fast_exp2(cap.x - M);
         for (int j = 0; j < pl.n_slices1; ++j) {
           const float2 v = p[(int64_t)j * D.GP];
           z += v.y * fast_exp2(v.x - M);

@@ -64,7 +64,8 @@ template <int HD, int PASS>
 __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl, const uint16_t* __restrict__ Q,
                                                             const uint16_t* __restrict__ K, float2* __restrict__ part,
                                                             float* __restrict__ u, const float* __restrict__ novelty,
-                                                            uint8_t* __restrict__ nuc_mask) {
+                                                            uint8_t* __restrict__ nuc_mask,
+                                                            const uint16_t* __restrict__ Kcap) {
   __shared__ ScoreLds<HD, PASS> sm;
   if (PASS == 1 && novelty != nullptr)
     nuc_rank_share(novelty, nuc_mask, D.B, D.n, D.nov_sb, D.T, blockIdx.x, gridDim.x);
@@ -74,7 +75,7 @@ __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl
   // memory-side cache
   if (PASS == 2) unit = D.units_run - 1 - unit;
   unit += D.unit0;
-  score_pass_body<HD, PASS>(D, pl, unit, slice, Q, K, part, u, sm);
+  score_pass_body<HD, PASS>(D, pl, unit, slice, Q, K, part, u, Kcap, sm);
 }
 
 constexpr int kRankMaxSteps = 256;   // rank-counting steps (of 64 rivals) a wave may be asked to do
@@ -100,21 +101,22 @@ void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const 
   dim3 grid(stats_grid(D, pl)), block(kMT);
   if (D.d == 64)
     hipLaunchKernelGGL((score_pass_kernel<64, 1>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
-                       (float*)nullptr, novelty, nuc_mask);
+                       (float*)nullptr, novelty, nuc_mask, (const uint16_t*)nullptr);
   else
     hipLaunchKernelGGL((score_pass_kernel<128, 1>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
-                       (float*)nullptr, novelty, nuc_mask);
+                       (float*)nullptr, novelty, nuc_mask, (const uint16_t*)nullptr);
 }
 
-void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float2* part, float* u,
-                      hipStream_t s) {
+// K_cap (nullable; [units, P, d] bf16): the CaP tokens' own keys join the softmax, causally
+void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const void* K_cap,
+                      const float2* part, float* u, hipStream_t s) {
   dim3 grid((unsigned)((D.units_run + 7) / 8 * 8) * pl.n_slices2), block(kMT);
   if (D.d == 64)
     hipLaunchKernelGGL((score_pass_kernel<64, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
-                       const_cast<float2*>(part), u, (const float*)nullptr, (uint8_t*)nullptr);
+                       const_cast<float2*>(part), u, (const float*)nullptr, (uint8_t*)nullptr, (const uint16_t*)K_cap);
   else
     hipLaunchKernelGGL((score_pass_kernel<128, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
-                       const_cast<float2*>(part), u, (const float*)nullptr, (uint8_t*)nullptr);
+                       const_cast<float2*>(part), u, (const float*)nullptr, (uint8_t*)nullptr, (const uint16_t*)K_cap);
 }
 
 }  // namespace ccd

@@ -73,6 +73,61 @@ __global__ __launch_bounds__(kThreads) void stats_valu_kernel(Dims D, ScorePlan 
   }
 }
 
+// Statistics of the CaP keys' block (causal variant of Eq. 2): query row q = g * P + i sees the CaP keys 0 .. i.
+// One workgroup per unit; the result goes behind the slices' statistics in `part`.
+template <typename T, int HD>
+__global__ __launch_bounds__(kThreads) void cap_block_stats_valu_kernel(Dims D, ScorePlan pl, const T* __restrict__ Q,
+                                                                        const T* __restrict__ Kcap,
+                                                                        float2* __restrict__ part) {
+  __shared__ float4 Ks[kTokTile][HD / 4];
+  const int unit = D.unit0 + blockIdx.x, tid = threadIdx.x;
+  const UnitIdx ui = decode_unit(D, unit);
+  const T* Kc = Kcap + (int64_t)unit * D.P * HD;
+  for (int q0 = 0; q0 < D.GP; q0 += kThreads) {
+    const int q = q0 + tid;
+    const bool active = q < D.GP;
+    const int i = q % D.P;                       // CaP position of the query
+    float4 qr[HD / 4];
+    if (active) {
+      const T* qp = Q + q_offset(D, ui, q);
+#pragma unroll
+      for (int c = 0; c < HD / 4; ++c) qr[c] = load4(qp + 4 * c);
+    } else {
+#pragma unroll
+      for (int c = 0; c < HD / 4; ++c) qr[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    float m = -INFINITY, Z = 0.f;
+    for (int jj = 0; jj < D.P; jj += kTokTile) {
+      __syncthreads();
+      for (int e = tid; e < kTokTile * (HD / 4); e += kThreads) {
+        const int t = e / (HD / 4), c = e - t * (HD / 4);
+        Ks[t][c] = jj + t < D.P ? load4(Kc + (int64_t)(jj + t) * HD + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+      __syncthreads();
+      const int nt = active ? min(kTokTile, i + 1 - jj) : 0;      // keys jj .. jj + nt - 1 are visible
+      for (int t = 0; t < nt; ++t) {
+        float acc = 0.f;
+#pragma unroll
+        for (int c = 0; c < HD / 4; ++c) {
+          const float4 kk = Ks[t][c];
+          acc = fmaf(qr[c].x, kk.x, acc);
+          acc = fmaf(qr[c].y, kk.y, acc);
+          acc = fmaf(qr[c].z, kk.z, acc);
+          acc = fmaf(qr[c].w, kk.w, acc);
+        }
+        const float x = acc * D.scale_log2;
+        if (x > m) {
+          Z = Z * fast_exp2(m - x) + 1.f;
+          m = x;
+        } else {
+          Z += fast_exp2(x - m);
+        }
+      }
+    }
+    if (active) part[cap_block_index(D, pl, unit, q)] = make_float2(m, Z);
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void merge_kernel(Dims D, ScorePlan pl, const float2* __restrict__ part,
                                                          float* __restrict__ lse2) {
   const int qblocks = (D.GP + kThreads - 1) / kThreads;
@@ -80,9 +135,13 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Dims D, ScorePlan pl, c
   const int q = (blockIdx.x % qblocks) * kThreads + threadIdx.x;
   if (q >= D.GP) return;
   const float2* p = part + (int64_t)unit * pl.n_slices1 * D.GP + q;
-  float M = -INFINITY;
+  float M = -INFINITY, Z = 0.f;
+  if (pl.cap_block) M = part[cap_block_index(D, pl, unit, q)].x;
   for (int j = 0; j < pl.n_slices1; ++j) M = fmaxf(M, p[(int64_t)j * D.GP].x);
-  float Z = 0.f;
+  if (pl.cap_block) {
+    const float2 v = part[cap_block_index(D, pl, unit, q)];
+    Z = v.y * fast_exp2(v.x - M);
+  }
   for (int j = 0; j < pl.n_slices1; ++j) {
     const float2 v = p[(int64_t)j * D.GP];
     Z += v.y * fast_exp2(v.x - M);
@@ -142,6 +201,16 @@ void launch_stats_valu(const Dims& D, const ScorePlan& pl, const void* Q, const 
   dim3 grid((unsigned)pl.n_slices1 * D.units_run), block(kThreads);
 #define CCD_LAUNCH(T, HD) \
   hipLaunchKernelGGL((stats_valu_kernel<T, HD>), grid, block, 0, s, D, pl, (const T*)Q, (const T*)K, part)
+  if (D.dtype == 0) { if (D.d == 64) CCD_LAUNCH(float, 64); else CCD_LAUNCH(float, 128); }
+  else              { if (D.d == 64) CCD_LAUNCH(uint16_t, 64); else CCD_LAUNCH(uint16_t, 128); }
+#undef CCD_LAUNCH
+}
+
+void launch_cap_block_stats_valu(const Dims& D, const ScorePlan& pl, const void* Q, const void* K_cap, float2* part,
+                                 hipStream_t s) {
+  dim3 grid((unsigned)D.units_run), block(kThreads);
+#define CCD_LAUNCH(T, HD) \
+  hipLaunchKernelGGL((cap_block_stats_valu_kernel<T, HD>), grid, block, 0, s, D, pl, (const T*)Q, (const T*)K_cap, part)
   if (D.dtype == 0) { if (D.d == 64) CCD_LAUNCH(float, 64); else CCD_LAUNCH(float, 128); }
   else              { if (D.d == 64) CCD_LAUNCH(uint16_t, 64); else CCD_LAUNCH(uint16_t, 128); }
 #undef CCD_LAUNCH

@@ -106,6 +106,7 @@ static ScorePlan plan_mfma(const Dims& D) {
   pl.slice1 = pl.slice2 = pick_slice(D);   // multiples of 32, at most mfma_max_slice()
   pl.n_slices1 = (D.n + pl.slice1 - 1) / pl.slice1;
   pl.n_slices2 = (D.n + pl.slice2 - 1) / pl.slice2;
+  pl.cap_block = 0;
   return pl;
 }
 
@@ -120,6 +121,7 @@ ScorePlan plan_score(const Dims& D) {
   }
   pl.n_slices1 = (D.n + pl.slice1 - 1) / pl.slice1;
   pl.n_slices2 = (D.n + pl.slice2 - 1) / pl.slice2;
+  pl.cap_block = 0;
   return pl;
 }
 
@@ -131,7 +133,7 @@ struct Workspace {
 static Workspace layout_workspace(const Dims& D) {
   Workspace w{};
   size_t off = 0;
-  const size_t max_slices = (D.n + kMinSlice - 1) / kMinSlice;
+  const size_t max_slices = (D.n + kMinSlice - 1) / kMinSlice + 1;   // + the block of the CaP keys (causal variant)
   w.off_part = off;   off = align_up(off + (size_t)D.units * max_slices * D.GP * sizeof(float2), 256);
   w.off_lse = off;    off = align_up(off + (size_t)D.units * D.GP * sizeof(float), 256);
   w.off_u = off;      off = align_up(off + (size_t)D.units * D.n * sizeof(float), 256);
@@ -147,9 +149,9 @@ static int check_workspace(const Workspace& w, const void* ws, size_t ws_bytes) 
 }
 
 // ---- optional per-kernel timing of ccd_compress -------------------------------------------------------
-enum Stage { kStNuc = 0, kStStats, kStMerge, kStProb, kStSelect, kStCompact, kStSelCompact, kNumStages };
-static const char* const kStageNames[kNumStages] = {"nuc_mask", "score_stats", "score_merge", "score_prob", "select",
-                                                    "compact",  "select_compact"};
+enum Stage { kStNuc = 0, kStStats, kStMerge, kStProb, kStSelect, kStCompact, kStSelCompact, kStCapBlock, kNumStages };
+static const char* const kStageNames[kNumStages] = {"nuc_mask", "score_stats",    "score_merge", "score_prob", "select",
+                                                    "compact",  "select_compact", "cap_block"};
 
 // Every profiled launch is bracketed by two events on the stream it runs on.
 struct Profiler {
@@ -183,9 +185,10 @@ static Profiler g_prof;
 static int launch_status() { return hipGetLastError() == hipSuccess ? CCD_OK : CCD_ELAUNCH; }
 
 // NuC mask (step a1, when T > 0) and raw CaP score u[unit, t] (steps a2-a3).  On the matrix-core path the first
-// score pass marks the NuC slots on the side when it can; otherwise they take a kernel of their own.
-static void run_mask_and_cap_scores(const Dims& D, const ScorePlan& pl, const Workspace& w, const void* Q, const void* K,
-                                    const float* novelty, char* ws, hipStream_t st) {
+// score pass marks the NuC slots on the side when it can; otherwise they take a kernel of their own.  With K_cap the
+// CaP tokens' own keys join the softmax (causally): their statistics become one more entry per unit of `part`.
+static void run_mask_and_cap_scores(const Dims& D, ScorePlan pl, const Workspace& w, const void* Q, const void* K,
+                                    const void* K_cap, const float* novelty, char* ws, hipStream_t st) {
   float2* part = reinterpret_cast<float2*>(ws + w.off_part);
   float* lse2 = reinterpret_cast<float*>(ws + w.off_lse);
   float* u = reinterpret_cast<float*>(ws + w.off_u);
@@ -196,12 +199,18 @@ static void run_mask_and_cap_scores(const Dims& D, const ScorePlan& pl, const Wo
     launch_nuc_mask(D, novelty, mask, st);
     g_prof.end(st);
   }
+  if (K_cap != nullptr && !pl.use_mfma) {    // (the matrix-core pass 2 takes the CaP keys in its prologue)
+    pl.cap_block = 1;
+    g_prof.begin(kStCapBlock, st);
+    launch_cap_block_stats_valu(D, pl, Q, K_cap, part, st);
+    g_prof.end(st);
+  }
   if (pl.use_mfma) {
     g_prof.begin(kStStats, st);
     launch_stats_mfma(D, pl, Q, K, part, nuc_in_stats ? novelty : nullptr, mask, st);
     g_prof.end(st);
     g_prof.begin(kStProb, st);
-    launch_prob_mfma(D, pl, Q, K, part, u, st);
+    launch_prob_mfma(D, pl, Q, K, K_cap, part, u, st);
     g_prof.end(st);
   } else {
     g_prof.begin(kStStats, st);
@@ -228,13 +237,13 @@ size_t ccd_workspace_bytes(const ccd_shape_t* shape) {
   return layout_workspace(D).total;
 }
 
-int ccd_score(const ccd_shape_t* shape, const void* Q_cat, const void* K, const float* novelty, float* scores,
-              void* workspace, size_t workspace_bytes, void* hip_stream) {
+static int score_impl(const ccd_shape_t* shape, const void* Q_cat, const void* K, const void* K_cap, const float* novelty,
+                      float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = check_shape(shape, kNeedFull);
   if (rc != CCD_OK) return rc;
   if (Q_cat == nullptr || K == nullptr || scores == nullptr) return CCD_EINVAL;
   if (novelty == nullptr && shape->T > 0) return CCD_EINVAL;
-  if (!aligned16(Q_cat) || !aligned16(K)) return CCD_EALIGN;
+  if (!aligned16(Q_cat) || !aligned16(K) || !aligned16(K_cap)) return CCD_EALIGN;
   const Dims D = make_dims(shape);
   const ScorePlan pl = plan_score(D);
   const Workspace w = layout_workspace(D);
@@ -243,9 +252,20 @@ int ccd_score(const ccd_shape_t* shape, const void* Q_cat, const void* K, const 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
   uint8_t* mask = reinterpret_cast<uint8_t*>(ws + w.off_mask);
-  run_mask_and_cap_scores(D, pl, w, Q_cat, K, novelty, ws, st);
+  run_mask_and_cap_scores(D, pl, w, Q_cat, K, K_cap, novelty, ws, st);
   launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), mask, scores, nullptr, st);
   return launch_status();
+}
+
+int ccd_score(const ccd_shape_t* shape, const void* Q_cat, const void* K, const float* novelty, float* scores,
+              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return score_impl(shape, Q_cat, K, nullptr, novelty, scores, workspace, workspace_bytes, hip_stream);
+}
+
+int ccd_score_kcat(const ccd_shape_t* shape, const void* Q_cat, const void* K, const void* K_cap, const float* novelty,
+                   float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (K_cap == nullptr) return CCD_EINVAL;
+  return score_impl(shape, Q_cat, K, K_cap, novelty, scores, workspace, workspace_bytes, hip_stream);
 }
 
 int ccd_select(const ccd_shape_t* shape, const float* scores, int32_t* keep_idx, void* hip_stream) {
@@ -272,10 +292,11 @@ int ccd_compact(const ccd_shape_t* shape, const void* K_src, const void* V_src, 
   return launch_status();
 }
 
-// ccd_compress, optionally with CR-RoPE of the kept keys on the side (K_rot != nullptr)
+// ccd_compress, optionally with CR-RoPE of the kept keys on the side (K_rot != nullptr), other keys to attend to
+// (K_score != nullptr) and the CaP tokens' own keys in the softmax (K_cap != nullptr)
 static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
-                         int32_t* keep_idx, const void* K_score, const float* rope_cos, const float* rope_sin, void* K_rot,
-                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+                         int32_t* keep_idx, const void* K_score, const void* K_cap, const float* rope_cos,
+                         const float* rope_sin, void* K_rot, void* workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = check_shape(shape, kNeedFull);
   if (rc != CCD_OK) return rc;
   if (Q_cat == nullptr || K == nullptr || V == nullptr || keep_idx == nullptr) return CCD_EINVAL;
@@ -286,6 +307,8 @@ static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, v
     if (!aligned16(K_rot) || !aligned16(rope_cos) || !aligned16(rope_sin)) return CCD_EALIGN;
   }
   if (K_score != nullptr && (K_score == V || !aligned16(K_score))) return K_score == V ? CCD_EINVAL : CCD_EALIGN;
+  if (K_cap != nullptr && (K_cap == K || K_cap == V || K_cap == K_rot)) return CCD_EINVAL;
+  if (!aligned16(K_cap)) return CCD_EALIGN;
   const void* K_attn = K_score != nullptr ? K_score : K;     // the keys the CaP queries attend to
   const Dims D = make_dims(shape);
   const ScorePlan pl = plan_score(D);
@@ -299,7 +322,7 @@ static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, v
   const float* u = reinterpret_cast<const float*>(ws + w.off_u);
   const bool per_head = shape->nov_stride_l != 0 || shape->nov_stride_h != 0;
   if (g_prof.on) ++g_prof.calls;
-  run_mask_and_cap_scores(D, pl, w, Q_cat, K_attn, novelty, ws, st);
+  run_mask_and_cap_scores(D, pl, w, Q_cat, K_attn, K_cap, novelty, ws, st);
   if (select_compact_supported(D)) {
     g_prof.begin(kStSelCompact, st);
     launch_select_compact(D, u, mask, scores_opt, keep_idx, K, V, per_head ? novelty : nullptr, rope_cos, rope_sin, K_rot,
@@ -319,16 +342,23 @@ static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, v
 
 int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
                  int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, nullptr, nullptr, nullptr, nullptr, workspace,
-                       workspace_bytes, hip_stream);
+  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, nullptr, nullptr, nullptr, nullptr, nullptr,
+                       workspace, workspace_bytes, hip_stream);
+}
+
+int ccd_compress_kcat(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, const void* K_cap, float* novelty,
+                      float* scores_opt, int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (K_cap == nullptr) return CCD_EINVAL;
+  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, nullptr, K_cap, nullptr, nullptr, nullptr,
+                       workspace, workspace_bytes, hip_stream);
 }
 
 int ccd_compress_rope(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
-                      int32_t* keep_idx, const void* K_score, const float* rope_cos, const float* rope_sin, void* K_rot,
-                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+                      int32_t* keep_idx, const void* K_score, const void* K_cap, const float* rope_cos,
+                      const float* rope_sin, void* K_rot, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (K_rot == nullptr) return CCD_EINVAL;
-  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, K_score, rope_cos, rope_sin, K_rot, workspace,
-                       workspace_bytes, hip_stream);
+  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, K_score, K_cap, rope_cos, rope_sin, K_rot,
+                       workspace, workspace_bytes, hip_stream);
 }
 
 int ccd_cr_rope(const ccd_shape_t* shape, const void* K, const float* rope_cos, const float* rope_sin, int32_t count,

@@ -89,6 +89,14 @@ def make_inputs(cfg: CCDConfig, *, per_head_novelty: bool = False, seed: int | N
             "novelty": novelty}
 
 
+def cap_keys(cfg: CCDConfig, *, seed: int | None = None, gain: float = 1.0) -> np.ndarray:
+    """K_cap [B,L,Hkv,P,d]: the CaP tokens' own keys (standard normal like the cached keys, times `gain`), in the
+    cache's storage type.  A stream of its own, so that make_inputs stays as it is."""
+    rng = np.random.Generator(np.random.Philox((cfg.seed if seed is None else seed) + 7919))
+    Kc = rng.standard_normal((cfg.B, cfg.L, cfg.Hkv, cfg.P, cfg.d), dtype=np.float32) * np.float32(gain)
+    return _store(Kc, cfg.dtype)
+
+
 def scaled(cfg: CCDConfig, **kw) -> CCDConfig:
     """A copy of a configuration with some fields replaced (test-sized variants)."""
     return replace(cfg, **kw)

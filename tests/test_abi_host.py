@@ -133,14 +133,37 @@ def test_cr_rope_argument_errors_are_decided_on_the_host():
     assert rope(cos=P + 4) == ip.CCD_EALIGN and rope(Krot=P2 + 8) == ip.CCD_EALIGN
     assert rope(count=0) == ip.CCD_OK                                                   # nothing to do, nothing launched
 
-    def crope(cos=P, sin=P, Krot=P2, shape=s, Kscore=None):
-        return L.ccd_compress_rope(ctypes.byref(shape), P, P, P, P, None, P, Kscore, cos, sin, Krot, 0x10000, ws_bytes, None)
+    def crope(cos=P, sin=P, Krot=P2, shape=s, Kscore=None, Kcap=None):
+        return L.ccd_compress_rope(ctypes.byref(shape), P, P, P, P, None, P, Kscore, Kcap, cos, sin, Krot, 0x10000, ws_bytes,
+                                   None)
 
     assert crope(Krot=None) == ip.CCD_EINVAL and crope(cos=None) == ip.CCD_EINVAL and crope(sin=None) == ip.CCD_EINVAL
     assert crope(Krot=P) == ip.CCD_EINVAL                                               # aliases K (and V)
     assert crope(sin=P + 4) == ip.CCD_EALIGN and crope(Kscore=P2 + 4) == ip.CCD_EALIGN
     assert crope(Kscore=P2, shape=_shape(n_valid=300, n_cap=512, k=256)) == ip.CCD_NOOP   # K_score may be K_rot
     assert crope(shape=_shape(n_valid=300, n_cap=512, k=256)) == ip.CCD_NOOP            # pot not full: nothing launched
+    assert crope(Kcap=P) == ip.CCD_EINVAL and crope(Kcap=P2) == ip.CCD_EINVAL           # aliases K / K_rot
+    assert crope(Kcap=P2 + 0x100004) == ip.CCD_EALIGN
+    assert crope(Kcap=P2 + 0x100000, shape=_shape(n_valid=300, n_cap=512, k=256)) == ip.CCD_NOOP
+
+
+def test_kcat_argument_errors_are_decided_on_the_host():
+    s = _shape()
+    L = ip.lib()
+    ws_bytes = ip.ccd_workspace_bytes(s)
+    P2 = P + 0x100000
+
+    def score(Kcap=P2, K=P, scores=P, ws=0x10000):
+        return L.ccd_score_kcat(ctypes.byref(s), P, K, Kcap, P, scores, ws, ws_bytes, None)
+
+    def compress(Kcap=P2, shape=s, K=P, V=P + 0x200000):
+        return L.ccd_compress_kcat(ctypes.byref(shape), P, K, V, Kcap, P, None, P, 0x10000, ws_bytes, None)
+
+    assert score(Kcap=None) == ip.CCD_EINVAL and compress(Kcap=None) == ip.CCD_EINVAL
+    assert score(Kcap=P2 + 2) == ip.CCD_EALIGN and compress(Kcap=P2 + 2) == ip.CCD_EALIGN
+    assert score(scores=None) == ip.CCD_EINVAL and score(ws=None) == ip.CCD_EWORKSPACE
+    assert compress(Kcap=P) == ip.CCD_EINVAL and compress(Kcap=P + 0x200000) == ip.CCD_EINVAL   # aliases K / V
+    assert compress(shape=_shape(n_valid=300, n_cap=512, k=256)) == ip.CCD_NOOP
 
 
 def test_pot_not_full_is_a_noop_decided_on_the_host():
