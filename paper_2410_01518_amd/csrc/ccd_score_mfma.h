@@ -183,6 +183,25 @@ __device__ __forceinline__ void fold_stats(floatx16 (&acc)[kQB], float (&m_raw)[
   }
 }
 
+// pass 1, the common case: add the 16 token rows a lane holds to its query's sum of 2^((x - m_ref) c) WITHOUT moving
+// the reference m_ref (no maximum, no rescaling: 5 instead of 5.5 ALU instructions per logit and no dependent
+// chain through the maximum).  The reference is the lane's maximum over the slice's first tile; a sum that leaves
+// the fp32 range (some later logit more than ~127 / c above the reference) is detected after the slice, and the
+// slice is then redone with fold_stats.
+__device__ __forceinline__ void fold_sum(const floatx16 (&acc)[kQB], const float (&m_ref)[kQB], float (&Z)[kQB], float c) {
+#pragma unroll
+  for (int qb = 0; qb < kQB; ++qb) {
+    const float negm = -m_ref[qb] * c;
+    float z0 = Z[qb], z1 = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+      z0 += fast_exp2(fmaf(acc[qb][r], c, negm));
+      z1 += fast_exp2(fmaf(acc[qb][r + 1], c, negm));
+    }
+    Z[qb] = z0 + z1;
+  }
+}
+
 // pass 2: probability of the lane's token under its 2 x 16 query rows, summed
 __device__ __forceinline__ float fold_prob(const floatx16 (&acc)[kQB], const float (&neg_lse)[kQB][16], float c) {
   float s0 = 0.f, s1 = 0.f;
@@ -257,6 +276,62 @@ __device__ __forceinline__ void interleave_hint() {
   }
 }
 
+// Pass 1 of one sweep the careful way (running maximum, rescaled sums), tile by tile without any overlap: the
+// fallback for sweeps whose fixed-reference sums overflowed.  Called by all threads of the workgroup; uses ring slot
+// 0 (`ring` points at it), which must be idle.  q_row0 / q_row1: the lane's query rows of block 0 and 1, or
+// null past the end.  Not inlined: it is rare, and as a function it leaves the registers of the main loop alone.
+struct MaxSum2 { float m[kQB], Z[kQB]; };
+template <int HD>
+__device__ __attribute__((noinline)) MaxSum2 stats_sweep_careful(const uint16_t* __restrict__ Ku, int t0, int t1,
+                                                                 const uint16_t* __restrict__ q_row0,
+                                                                 const uint16_t* __restrict__ q_row1,
+                                                                 __attribute__((address_space(3))) uint8_t* ring,
+                                                                 float c) {
+  constexpr int KS = HD / 16;
+  static_assert(kQB == 2, "two query rows per lane are passed in");
+  // arguments of a callable function arrive in vector registers; the DMA wants its base addresses in scalar ones
+  const uint64_t ku_bits = reinterpret_cast<uint64_t>(Ku);
+  Ku = reinterpret_cast<const uint16_t*>(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(ku_bits >> 32)) << 32) |
+                                         (uint32_t)__builtin_amdgcn_readfirstlane((int)ku_bits));
+  t0 = __builtin_amdgcn_readfirstlane(t0);
+  t1 = __builtin_amdgcn_readfirstlane(t1);
+  const uint32_t lds_addr = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)ring);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63, col = lane & 31, half = lane >> 5;
+  const uint8_t* lds = (const uint8_t*)ring;
+  int koff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) koff[ks] = col * Tiles<HD>::kRowBytes + (((2 * ks + half) ^ Tiles<HD>::swz(col)) << 4);
+  uint32_t voff_full[Tiles<HD>::kInstrPerWave];
+  tile_offsets<HD>(voff_full, wave, lane);
+  bf16x8 bq[kQB][KS];
+#pragma unroll
+  for (int qb = 0; qb < kQB; ++qb) {
+    const uint16_t* qp = qb == 0 ? q_row0 : q_row1;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      bq[qb][ks] = qp != nullptr ? *reinterpret_cast<const bf16x8*>(qp + half * 8 + ks * 16) : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+  }
+  MaxSum2 r;
+#pragma unroll
+  for (int qb = 0; qb < kQB; ++qb) { r.m[qb] = kNegHuge; r.Z[qb] = 0.f; }
+  const int S = (t1 - t0 + kStep - 1) / kStep;
+  for (int s = 0; s < S; ++s) {
+    issue_tile<HD>(Ku, t0, t1, s, lds_addr, wave, lane, voff_full);
+    wait_all_dma();
+    __syncthreads();
+    bf16x8 a[KS];
+    load_k_frags<HD, 0>(a, lds, koff);
+    floatx16 acc[kQB];
+    logits<HD, 1>(acc, a, bq);
+    const int nvalid = t1 - t0 - s * kStep;
+    if (nvalid < kStep) fold_stats<true>(acc, r.m, r.Z, c, half, nvalid);
+    else                fold_stats<false>(acc, r.m, r.Z, c, half, kStep);
+    __syncthreads();   // slot 0 is overwritten by the next tile
+  }
+  return r;
+}
+
 // PASS 1 writes part[unit][slice][q] = (max2, sum); PASS 2 reads part (all slices of the unit), adds the block of
 // the CaP keys in the causal variant (Kcap != nullptr), writes u[unit][t].
 // LDS of one score pass.  The K ring must stay first (DMA destinations are addressed relative to it).
@@ -266,6 +341,7 @@ struct ScoreLds {
   float up[PASS == 2 ? 4 : 1][PASS == 2 ? kMaxSlice : 1];   // per-wave partial sums (pass 2)
   float lse_s[PASS == 2 ? kQPerPass : 1];
   int parity;
+  int redo[2];     // pass 1: some sum of the sweep left the fp32 range
 };
 
 // One (unit, token slice) of one pass, executed by a workgroup of kMT threads.  Ends with every thread past a
@@ -300,6 +376,8 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
   if (threadIdx.x == 0) sm.parity = cu_parity();     // read after the first barrier below
   const int s_switch = (int)(kPrioSwitch * (float)S);
   for (int qc = 0; qc < D.GP; qc += kQPerPass) {
+    const int redo_slot = (qc / kQPerPass) & 1;     // alternating: the flag of the sweep before may still be read
+    if (PASS == 1 && threadIdx.x == 0) sm.redo[redo_slot] = 0;
     // start the K stream first: batch 0 is in flight while the query fragments are fetched
 #pragma unroll
     for (int i = 0; i < kBatch; ++i)
@@ -352,6 +430,16 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
     floatx16 accA[kQB], accB[kQB];
     load_k_frags<HD, 0>(a, lds, koff);
     logits<HD, PASS>(accA, a, bq);
+    if (PASS == 1 && S_full > 0) {
+      // reference of the sums of this sweep: the lane's maximum over tile 0 (see fold_sum)
+#pragma unroll
+      for (int qb = 0; qb < kQB; ++qb) {
+        float t = accA[qb][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) t = fmaxf(t, accA[qb][r]);
+        m_raw[qb] = t;
+      }
+    }
 
     // Step s (ring slot I = s mod kDepth) folds tile s on the ALU while the MFMAs of tile s+1 run.  Tiles arrive in
     // batches of b = kBatch: the batch that holds tile s+2 must have landed by the end of every step with
@@ -371,8 +459,8 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
       load_k_frags<HD, ((I) + 1) % kDepth>(a, lds, koff);                                         \
       logits<HD, PASS>(NXT, a, bq);                                                               \
       if (PASS == 1) {                                                                            \
-        fold_stats<false>(CUR, m_raw, Z, c, half, 32);                                            \
-        interleave_hint<KS, 20, 8>();                                                             \
+        fold_sum(CUR, m_raw, Z, c);                                                               \
+        interleave_hint<KS, 14, 6>();                                                             \
       } else {                                                                                    \
         float us = fold_prob(CUR, neg_lse, c);                                                    \
         interleave_hint<KS, 14, 5>();                                                             \
@@ -399,6 +487,24 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
     }
 #undef CCD_STEP
     static_assert(kDepth <= 6 && kDepth % 2 == 0, "the step sequence above is written out for up to six slots");
+    if (PASS == 1 && S_full > 0) {
+      // Did a sum leave the fp32 range (or meet a NaN)?  Then the whole workgroup redoes the sweep the careful way
+      // below.  Otherwise move each reference to where its sum is of order one (Z = mant * 2^e -> reference
+      // + e / c), so that the tail fold and the merges see the magnitudes of a (maximum, sum) pair.
+      bool bad = false;
+      const float inv_c = 1.0f / c;
+#pragma unroll
+      for (int qb = 0; qb < kQB; ++qb) {
+        bad |= !(Z[qb] < INFINITY);
+        // (2^-e by ldexp: exp2 would flush it to zero for e near 127; the residual factor makes the new sum
+        // consistent with the ROUNDED new reference)
+        const int e = __builtin_amdgcn_frexp_expf(Z[qb]);
+        const float m_new = m_raw[qb] + (float)e * inv_c;
+        Z[qb] = __builtin_amdgcn_ldexpf(Z[qb], -e) * fast_exp2(fmaf(m_raw[qb] - m_new, c, (float)e));
+        m_raw[qb] = m_new;
+      }
+      if (__any(bad) && lane == 0) sm.redo[redo_slot] = 1;
+    }
     // the logits of tile S_full - the partial tail tile, if there is one - are in accA or accB by parity
     if (S > S_full) {
       if (S_full & 1) {
@@ -419,6 +525,14 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
     __syncthreads();   // ring, lse_s and up are reused by the next sweep / read below
 
     if (PASS == 1) {
+      if (sm.redo[redo_slot]) {     // uniform over the workgroup
+        const int q0 = qc + wave * (kQB * 32) + col;
+        const MaxSum2 r = stats_sweep_careful<HD>(Ku, t0, t1, q0 < D.GP ? Q + q_offset(D, ui, q0) : nullptr,
+                                                  q0 + 32 < D.GP ? Q + q_offset(D, ui, q0 + 32) : nullptr,
+                                                  (__attribute__((address_space(3))) uint8_t*)lds, c);
+#pragma unroll
+        for (int qb = 0; qb < kQB; ++qb) { m_raw[qb] = r.m[qb]; Z[qb] = r.Z[qb]; }
+      }
       // the two lane halves hold different token rows of the same query: merge, lower half writes
 #pragma unroll
       for (int qb = 0; qb < kQB; ++qb) {

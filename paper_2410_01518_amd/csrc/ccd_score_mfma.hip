@@ -8,8 +8,9 @@
 //
 // The 32x32 accumulator tile puts its column index on the lane (lane % 32) and its row index on the register, so
 // the operand order is chosen per pass to make the reduction run along registers, never across lanes:
-//   pass 1  D[token][query] = Kfrag x Qfrag : each lane owns one query, folds its 16 token rows into a running
-//           (max, sum of 2^(x - max)) pair;
+//   pass 1  D[token][query] = Kfrag x Qfrag : each lane owns one query and adds 2^(x - reference) of its 16 token
+//           rows to a sum; the reference is fixed per slice (the lane's maximum over the first tile), and a slice
+//           whose sums leave the fp32 range is redone with a running maximum;
 //   pass 2  D[query][token] = Qfrag x Kfrag : each lane owns one token, adds 2^(x - lse2[query]) of its 16 query
 //           rows into partial sums.
 // The fragment a lane holds is the same in both roles: the vector with index lane % 32, elements

@@ -270,6 +270,41 @@ def test_non_finite_keys_keep_indices_valid():
     gu.check_keep_valid(gu.to_host(keep), cfg.N, cfg.k)
 
 
+@pytest.mark.parametrize("where", ["late_tokens", "second_slice", "second_sweep", "tail_tile"])
+def test_logits_far_above_those_of_the_first_tile(where):
+    """The matrix-core statistics pass sums 2^(x - reference) with the reference taken from the first tile of a slice
+    and redoes a slice whose sums leave the fp32 range.  Keys whose logits outgrow the first tile's by hundreds of
+    binary orders force that; the result must be the oracle's all the same."""
+    cfg = _cfg(B=1, L=1, Hq=16, Hkv=2, P=40, N=2500 if where == "second_slice" else 1000, k=300, T=50, w=3, seed=71)
+    print(f"far logits {where} {cfg}", flush=True)
+    inp = synth.make_inputs(cfg)
+    K = synth.bf16_bits_to_f32(inp["K"])
+    Q = synth.bf16_bits_to_f32(inp["Q_cat"])
+    K[..., :64, :] *= 0.01                                           # a quiet first tile
+    if where == "late_tokens":
+        K[..., 300:, :] *= 30.0
+        Q *= 3.0
+    elif where == "second_slice":                                    # 2500 tokens: slices of 2048 or shorter
+        K[..., 2100:, :] *= 30.0
+        Q *= 3.0
+    elif where == "second_sweep":                                    # G * P = 320: only query rows >= 256 grow
+        K[..., 300:, :] *= 30.0
+        Q[:, :, cfg.G - 1::cfg.G, 20:, :] *= 30.0                    # the last query head of each group, CaP rows 20..
+        Q[:, :, : cfg.G - 1, :, :] *= 0.01
+    else:                                                            # only the ragged last tile (1000 = 31 * 32 + 8)
+        K[..., 992:, :] *= 90.0
+        Q *= 3.0
+    inp["K"], inp["Q_cat"] = synth.f32_to_bf16_bits(K), synth.f32_to_bf16_bits(Q)
+    ref = _oracle(cfg, inp)
+    dev = _upload(inp)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w)
+    ws = ip.alloc_workspace(shape)
+    scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
+    assert ip.ccd_score(shape, dev["Q_cat"], dev["K"], dev["novelty"], scores, ws) == ip.CCD_OK
+    torch.cuda.synchronize()
+    gu.assert_scores_close(gu.to_host(scores), ref["scores"], cfg.G * cfg.P)
+
+
 # ------------------------------------------------------------------ run-to-run behaviour
 
 def test_repeated_calls_give_identical_bits():
