@@ -192,11 +192,21 @@ __device__ __forceinline__ void fold_sum(const floatx16 (&acc)[kQB], const float
 #pragma unroll
   for (int qb = 0; qb < kQB; ++qb) {
     const float negm = -m_ref[qb] * c;
-    float z0 = Z[qb], z1 = 0.f;
+    // four independent chains at a time: an exp2 result is never the operand of the very next instruction (which
+    // would cost a wait state each time)
+    float e[16];
 #pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-      z0 += fast_exp2(fmaf(acc[qb][r], c, negm));
-      z1 += fast_exp2(fmaf(acc[qb][r + 1], c, negm));
+    for (int r = 0; r < 16; r += 4) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) e[r + i] = fmaf(acc[qb][r + i], c, negm);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) e[r + i] = fast_exp2(e[r + i]);
+    }
+    float z0 = Z[qb] + e[0], z1 = e[1];
+#pragma unroll
+    for (int r = 2; r < 16; r += 2) {
+      z0 += e[r];
+      z1 += e[r + 1];
     }
     Z[qb] = z0 + z1;
   }

@@ -74,6 +74,15 @@ __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, co
   if (u != nullptr) {
     const float* uu = u + (int64_t)unit * n;
     const bool pooling = D.pool_mode != 0 && D.pool_w > 1;
+    // the NuC marks of the thread's tokens are requested first: their latency passes behind the staging of the row
+    const bool shared_nov = D.nov_sl == 0 && D.nov_sh == 0;
+    const uint8_t* mrow = mask + (int64_t)(shared_nov ? decode_unit(D, unit).b : unit) * n;
+    bool nuc[KPT];
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+      const int t = owned_token<THREADS, KPT, BLOCKED>(tid, j);
+      nuc[j] = D.T > 0 && t < n && mrow[t] != 0;
+    }
     if (u_stage != nullptr && pooling) {
 #pragma unroll
       for (int j = 0; j < KPT; ++j) {
@@ -83,8 +92,6 @@ __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, co
       __syncthreads();
       uu = u_stage + kStagePad;
     }
-    const bool shared_nov = D.nov_sl == 0 && D.nov_sh == 0;
-    const uint8_t* mrow = mask + (int64_t)(shared_nov ? decode_unit(D, unit).b : unit) * n;
     if (BLOCKED && pooling && D.pool_w <= 2 * kStagePad + 1) {
       pooled_block<KPT>(sc, u_stage, tid * KPT, n, D.pool_w, D.pool_mode);
     } else {
@@ -101,7 +108,7 @@ __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, co
       sc[j] = -INFINITY;
       if (t < n) {
         if (fabsf(v) < FLT_MIN) v = 0.f;
-        sc[j] = (D.T > 0 && mrow[t]) ? INFINITY : v;
+        sc[j] = nuc[j] ? INFINITY : v;
         if (scores != nullptr) scores[(int64_t)unit * n + t] = sc[j];
       }
     }
@@ -121,31 +128,31 @@ __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, co
     uint32_t tau, need;
     radix_threshold<THREADS, KPT, BLOCKED>([&](int j, int) { return key[j]; }, n, (uint32_t)D.k, sh, phase, tau, need);
     if (BLOCKED) {
-      // token order is thread order, then j: one scan over the per-thread counts of threshold ties, one over the
-      // per-thread counts of selected tokens
-      uint32_t n_eq = 0;
-#pragma unroll
-      for (int j = 0; j < KPT; ++j) n_eq += (tid * KPT + j < n && key[j] == tau) ? 1u : 0u;
-      uint32_t tot;
-      uint32_t eq_rank = block_exclusive_scan<THREADS>(n_eq, sh, phase, tot);
-      uint32_t sel_bits = 0, n_sel = 0;
+      // token order is thread order, then j.  A token's place among the kept ones is the number of larger keys
+      // before it plus the number of threshold ties before it, capped at `need`: one scan over the two per-thread
+      // counts packed into one word (blocked ownership is only used for n <= 16384, so both stay below 2^16)
+      uint32_t n_gt = 0, n_eq = 0;
 #pragma unroll
       for (int j = 0; j < KPT; ++j) {
         const bool valid = tid * KPT + j < n;
-        const bool eq = valid && key[j] == tau;
-        const bool sel = valid && (key[j] > tau || (eq && eq_rank < need));
-        eq_rank += eq ? 1u : 0u;
-        sel_bits |= sel ? (1u << j) : 0u;
-        n_sel += sel ? 1u : 0u;
+        n_gt += (valid && key[j] > tau) ? 1u : 0u;
+        n_eq += (valid && key[j] == tau) ? 1u : 0u;
       }
-      uint32_t pos = block_exclusive_scan<THREADS>(n_sel, sh, phase, tot);
+      uint32_t tot;
+      const uint32_t before = block_exclusive_scan<THREADS>((n_gt << 16) | n_eq, sh, phase, tot);
+      uint32_t gt_rank = before >> 16, eq_rank = before & 0xFFFFu;
 #pragma unroll
-      for (int j = 0; j < KPT; ++j)
-        if (sel_bits & (1u << j)) {
+      for (int j = 0; j < KPT; ++j) {
+        const bool valid = tid * KPT + j < n;
+        const bool gt = valid && key[j] > tau, eq = valid && key[j] == tau;
+        if (gt || (eq && eq_rank < need)) {
+          const uint32_t pos = gt_rank + min(eq_rank, need);
           if (out != nullptr) out[pos] = tid * KPT + j;
           if (keep_lds != nullptr) keep_lds[pos] = tid * KPT + j;
-          ++pos;
         }
+        gt_rank += gt ? 1u : 0u;
+        eq_rank += eq ? 1u : 0u;
+      }
     } else {
       uint32_t eq_base = 0, out_base = 0;
 #pragma unroll

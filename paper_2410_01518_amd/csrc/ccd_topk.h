@@ -1,8 +1,8 @@
 // Exact top-k threshold selection inside one workgroup, shared by the NuC-slot job and the final selection.
 //
-// Keys are order-preserving 32-bit images of fp32 values.  An MSB-first radix select with digits of 11, 11 and 10
-// bits (LDS histogram, one atomic per key and pass) yields the threshold key tau and the number `need` of keys
-// equal to tau that still belong to the k largest: a token is selected iff key > tau, or key == tau and fewer than
+// Keys are order-preserving 32-bit images of fp32 values.  An MSB-first radix select with digits of up to 11 bits
+// (LDS histogram, one atomic per candidate key and pass) over the range the keys actually span yields the threshold
+// key tau and the number `need` of keys equal to tau that still belong to the k largest: a token is selected iff key > tau, or key == tau and fewer than
 // `need` equal tokens precede it in token order (lowest index wins ties).
 #pragma once
 #include <hip/hip_runtime.h>
@@ -29,6 +29,7 @@ template <int THREADS>
 struct TopkShared {
   uint32_t hist[kRadixBins];
   uint32_t wave_sum[2][THREADS / 64];   // ping-pong: one barrier per scan
+  uint32_t red[4][THREADS / 64];        // per-wave class counts and key range of radix_threshold
   uint32_t digit, remaining;
 };
 
@@ -80,32 +81,98 @@ __device__ __forceinline__ uint32_t block_rank(bool pred, TopkShared<THREADS>& s
 // (n <= THREADS * KPT): tid + j*THREADS, or tid*KPT + j when BLOCKED; key_of(j, t) returns the key of the thread's
 // j-th token t, which the caller holds in registers.
 // On return #{key > tau} < kk <= #{key >= tau} and need = kk - #{key > tau}.  Ends with a barrier.
+//
+// Scores of one row share a few exponents, and a quarter or half of them are the +inf of the NuC slots: the top
+// 11 bits of such keys fall into a handful of histogram bins, and a wave's 64 LDS atomics on one address serialise
+// (measured: 5.2 us for the first pass against 1.4 us for the later ones).  So the keys are first split into three
+// classes by fixed bounds - at or above the key of +inf, at or below the key of -inf, ordinary - with counts and, for
+// the ordinary ones, minimum and maximum from one workgroup reduction.  The class that holds the kk-th largest is
+// known from the counts; inside it the digits are taken from key - lo over the range hi - lo actually spanned, most
+// significant first, 11 bits at a time (fewer passes when the range is narrow, none when it is a single value).
 template <int THREADS, int KPT, bool BLOCKED = false, class KeyFn>
 __device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk, TopkShared<THREADS>& sh, int& phase, uint32_t& tau,
                                 uint32_t& need) {
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int kBinsPerThread = kRadixBins / THREADS;
-  uint32_t prefix = 0, hi_mask = 0, remaining = kk;
+  constexpr int kWaves = THREADS / 64;
+  constexpr uint32_t kHiFrom = 0xFF800000u;   // score_key(+inf)
+  constexpr uint32_t kLoUpTo = 0x007FFFFFu;   // score_key(-inf)
+
+  // class counts and the range of the ordinary keys
+  uint32_t c_hi = 0, c_mid = 0, mn = 0xFFFFFFFFu, mx = 0u;
+#pragma unroll
+  for (int j = 0; j < KPT; ++j) {
+    const int t = BLOCKED ? tid * KPT + j : tid + j * THREADS;
+    if (t < n) {
+      const uint32_t key = key_of(j, t);
+      const bool hi = key >= kHiFrom, mid = !hi && key > kLoUpTo;
+      c_hi += hi ? 1u : 0u;
+      c_mid += mid ? 1u : 0u;
+      mn = mid ? min(mn, key) : mn;
+      mx = mid ? max(mx, key) : mx;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    c_hi += __shfl_xor(c_hi, off);
+    c_mid += __shfl_xor(c_mid, off);
+    mn = min(mn, (uint32_t)__shfl_xor(mn, off));
+    mx = max(mx, (uint32_t)__shfl_xor(mx, off));
+  }
+  for (int i = tid; i < kRadixBins; i += THREADS) sh.hist[i] = 0;
+  if (lane == 0) {
+    sh.red[0][wave] = c_hi;
+    sh.red[1][wave] = c_mid;
+    sh.red[2][wave] = mn;
+    sh.red[3][wave] = mx;
+  }
+  __syncthreads();                             // wave results and the cleared histogram are visible
+  uint32_t n_hi = 0, n_mid = 0;
+  mn = 0xFFFFFFFFu;
+  mx = 0u;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    n_hi += sh.red[0][w];
+    n_mid += sh.red[1][w];
+    mn = min(mn, sh.red[2][w]);
+    mx = max(mx, sh.red[3][w]);
+  }
+
+  // the class of the kk-th largest key: candidates are the keys in [lo, hi]; `remaining` of them are wanted
+  uint32_t lo, hi, remaining;
+  if (kk <= n_hi) {
+    lo = kHiFrom; hi = 0xFFFFFFFFu; remaining = kk;
+  } else if (kk <= n_hi + n_mid) {
+    lo = mn; hi = mx; remaining = kk - n_hi;
+  } else {
+    lo = 0u; hi = kLoUpTo; remaining = kk - n_hi - n_mid;
+  }
+  int rem_bits = 32 - __clz(hi - lo);          // bits of key - lo not yet fixed (__clz(0) = 32)
+  if (rem_bits == 0) __syncthreads();          // a single candidate value: no pass, but still end with a barrier
+  uint32_t prefix = 0;                         // the fixed high bits of tau - lo, as a value (already shifted down)
 #pragma unroll 1
-  for (int pass = 0; pass < 3; ++pass) {
-    const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
-    const uint32_t dmask = pass == 2 ? 1023u : 2047u;
-    for (int i = tid; i < kRadixBins; i += THREADS) sh.hist[i] = 0;
-    __syncthreads();
+  while (rem_bits > 0) {
+    const int width = min(11, rem_bits), shift = rem_bits - width;
+    const uint32_t dmask = (1u << width) - 1u;
 #pragma unroll
     for (int j = 0; j < KPT; ++j) {
       const int t = BLOCKED ? tid * KPT + j : tid + j * THREADS;
       if (t < n) {
         const uint32_t key = key_of(j, t);
-        if ((key & hi_mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & dmask], 1u);
+        const uint32_t rel = key - lo;
+        if (key >= lo && key <= hi && (uint32_t)((uint64_t)rel >> rem_bits) == prefix)
+          atomicAdd(&sh.hist[(rel >> shift) & dmask], 1u);
       }
     }
     __syncthreads();
-    // thread 0 owns the highest bins: prefix sums in thread order are counts of larger digits
+    // thread 0 owns the highest bins: prefix sums in thread order are counts of larger digits.  Each thread
+    // clears the bins it has read: the histogram is zero again before the next pass adds to it (two barriers on).
     uint32_t h[kBinsPerThread], mine = 0;
 #pragma unroll
     for (int i = 0; i < kBinsPerThread; ++i) {
-      h[i] = sh.hist[kRadixBins - 1 - (tid * kBinsPerThread + i)];
+      const int bin = kRadixBins - 1 - (tid * kBinsPerThread + i);
+      h[i] = sh.hist[bin];
+      sh.hist[bin] = 0;
       mine += h[i];
     }
     uint32_t tot;
@@ -120,12 +187,11 @@ __device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk
       excl = incl;
     }
     __syncthreads();
-    prefix |= sh.digit << shift;
-    hi_mask |= dmask << shift;
+    prefix = (prefix << width) | sh.digit;
     remaining = sh.remaining;
+    rem_bits = shift;
   }
-  __syncthreads();
-  tau = prefix;
+  tau = lo + prefix;
   need = remaining;
 }
 
