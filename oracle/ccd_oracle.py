@@ -27,7 +27,8 @@ Steps, per unit (sequence b, layer l, KV head h), in the paper's order:
                 alone (the default: the benchmark's interface hands over the cache only),
                 and, with K_cap, the model's own causal row, in which CaP token i also
                 attends to the CaP keys 0 .. i (Eq. 2 places the CaP tokens at the end of
-                the same sequence).
+                the same sequence).  A sliding attention window (window > 0) hides the oldest
+                cached tokens from the later CaP tokens.
   pool          1-D pooling of the score along the token axis (not in the
                 paper; the paper's implementation follows a code base that
                 clusters scores this way, and the benchmark configs ask for a
@@ -97,7 +98,8 @@ def nuc_slots(novelty: np.ndarray, T: int) -> np.ndarray:
     return np.sort(take)
 
 
-def cap_scores(Q: np.ndarray, K: np.ndarray, scale: float, K_cap: np.ndarray | None = None, P: int | None = None) -> np.ndarray:
+def cap_scores(Q: np.ndarray, K: np.ndarray, scale: float, K_cap: np.ndarray | None = None, P: int | None = None,
+               window: int = 0) -> np.ndarray:
     """Eq. 2: u_t = sum over CaP queries of softmax_t(scale * <q, k_t>).
 
     Q is [G*P, d] (all query rows that attend through this KV head, row g*P + i = CaP token i
@@ -105,15 +107,29 @@ def cap_scores(Q: np.ndarray, K: np.ndarray, scale: float, K_cap: np.ndarray | N
     n context tokens.  With K_cap [P, d] (the CaP tokens' own keys) it is the model's causal
     attention row of Eq. 2: CaP token i also sees the CaP keys 0 .. i, which take their share
     of the probability mass; the score still sums the context columns only.
+    window > 0: sliding-window attention (the footnote on Mistral-v0.1 in Sec. 4): the cached
+    tokens stand at positions 0 .. n-1 and CaP token i at position n + i; a query at position p
+    sees the keys at positions p - window + 1 .. p only, so context token t is hidden from CaP
+    token i when t < n + i + 1 - window.  (CaP keys j <= i are always inside the window:
+    window >= P is required.  Without K_cap a CaP token whose window holds no cached token
+    gives nothing to any score.)
     """
+    n = K.shape[0]
+    if P is None and K_cap is not None:
+        P = K_cap.shape[0]
     S = scale * (Q @ K.T)                      # [G*P, n] attention logits
+    if window and window > 0:
+        assert P is not None and window >= P
+        i = np.arange(Q.shape[0]) % P          # CaP position of each query row
+        first_visible = n + i + 1 - window
+        S = np.where(np.arange(n)[None, :] >= first_visible[:, None], S, -np.inf)
     if K_cap is None:
         m = S.max(axis=1, keepdims=True)
+        m = np.where(np.isneginf(m), 0.0, m)   # a row whose window holds no cached token (window == P at most)
         E = np.exp(S - m)
         Z = E.sum(axis=1, keepdims=True)
-        A = E / Z                              # attention probabilities, rows sum to 1
+        A = np.divide(E, Z, out=np.zeros_like(E), where=Z > 0)   # attention probabilities, rows sum to 1 (or are empty)
         return A.sum(axis=0)                   # sum over the CaP rows
-    P = K_cap.shape[0] if P is None else P
     assert K_cap.shape[0] == P and Q.shape[0] % P == 0
     C = scale * (Q @ K_cap.T)                  # [G*P, P] logits on the CaP keys
     i = np.arange(Q.shape[0]) % P              # CaP position of each query row
@@ -234,9 +250,9 @@ def cr_rope(K_kept: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
     return y.astype(np.float32)
 
 
-def score_unit(Q, K, novelty, *, T, scale, pool_w, pool_mode, K_cap=None):
+def score_unit(Q, K, novelty, *, T, scale, pool_w, pool_mode, K_cap=None, P=None, window=0):
     """Final fp32 scores of one unit. Q [G*P, d], K [n, d], K_cap [P, d] or None: raw inputs; novelty [n] fp32."""
-    u = cap_scores(to_f64(Q), to_f64(K), scale, None if K_cap is None else to_f64(K_cap))
+    u = cap_scores(to_f64(Q), to_f64(K), scale, None if K_cap is None else to_f64(K_cap), P=P, window=window)
     ubar = pool(u, pool_w, pool_mode)
     return combine(ubar, nuc_slots(novelty, T))
 
@@ -246,7 +262,7 @@ def default_scale(d: int) -> float:
 
 
 def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=None,
-             n_valid=None, units=None, rope_cos=None, rope_sin=None, K_score=None, K_cap=None):
+             n_valid=None, units=None, rope_cos=None, rope_sin=None, K_score=None, K_cap=None, window=0):
     """One CCD compression over a whole cache.
 
     Q_cat [B, L, Hq, P, d]; K, V [B, L, Hkv, n_cap, d]; novelty [B, n] (shared by
@@ -260,7 +276,7 @@ def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=
     stored ones - with CR-RoPE the pot stores keys before the rotary embedding while the
     model attends to the embedded keys of the current positions.
     K_cap [B, L, Hkv, P, d]: the CaP tokens' own keys; with them the attention rows are the
-    model's causal ones (see cap_scores).
+    model's causal ones (see cap_scores).  window > 0: sliding-window attention (see cap_scores).
     """
     B, L, Hq, P, d = Q_cat.shape
     Hkv, n_cap = K.shape[2], K.shape[3]
@@ -281,7 +297,7 @@ def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=
         nov = novelty[b, l, h, :n] if per_head else novelty[b, :n]
         Ks = K if K_score is None else K_score
         s = score_unit(Qu, Ks[b, l, h, :n], nov, T=T, scale=scale, pool_w=pool_w, pool_mode=pool_mode,
-                       K_cap=None if K_cap is None else K_cap[b, l, h])
+                       K_cap=None if K_cap is None else K_cap[b, l, h], P=P, window=window)
         keep = select(s, k)
         scores[b, l, h] = s
         keep_idx[b, l, h] = keep
