@@ -46,6 +46,8 @@ def algorithmic_bytes(cfg) -> dict:
         "select_compact": u * N * 4 + cfg.B * N * 4 + u * k * 4 + 4 * rows,
         # causal variant (--kcat): Q_cat and the CaP keys read, one (max, sum) pair per query written
         "cap_block": qbytes + u * cfg.P * d * e + u * GP * 8,
+        # sliding window (--window): both head kernels read Q_cat and the hidden rows of K (at most P + 31 per unit)
+        "window_head": 2 * (qbytes + u * (cfg.P + 31) * d * e),
         # whole call: K read once, Q_cat once, kept V rows read once, K' and V' written once, keep_idx, novelty
         "call": kbytes + qbytes + rows + 2 * rows + u * k * 4 + cfg.B * N * 4,
     }
@@ -129,6 +131,8 @@ def main() -> int:
     ap.add_argument("--kcat", action="store_true",
                     help="the causal variant of Eq. 2: the CaP tokens' own keys join the softmax (ccd_compress_kcat, or "
                          "ccd_compress_rope with K_cap when combined with --rope)")
+    ap.add_argument("--window", type=int, default=0,
+                    help="sliding attention window in tokens (0 = none), e.g. 4096 for a window as long as the pot")
     ap.add_argument("--aux", choices=["nuc", "cr_rope"], default=None,
                     help="time a stand-alone companion kernel instead of the headline call: nuc = ccd_nuc_from_logits on "
                          "4096 x 128256 bf16 logits, cr_rope = ccd_cr_rope on the kept half of a headline pot")
@@ -187,7 +191,8 @@ def main() -> int:
     qsets = [dev0["Q_cat"]] + [randn(cfg.B, cfg.L, cfg.Hq, cfg.P, cfg.d) for _ in range(3)]
     novs = [dev0["novelty"]] + [torch.rand((cfg.B, cfg.N), generator=g, device=dev, dtype=torch.float32)
                                 for _ in range(4)]
-    shape = ip.make_shape(qsets[0], pots[0][0], novs[0], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=ip.CCD_POOL_MAX)
+    shape = ip.make_shape(qsets[0], pots[0][0], novs[0], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=ip.CCD_POOL_MAX,
+                          window=args.window)
     ws = ip.alloc_workspace(shape)
     keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream()
@@ -269,7 +274,7 @@ def main() -> int:
         else:
             r = {"kernel": stage, "bound": "hbm", "achieved": ab[stage] / t / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
         r["frac"] = r["achieved"] / r["peak"]
-        r["traffic"] = MEASURED_TRAFFIC_C3.get(stage) if cfg.name == "c3" and args.score_path == 0 and not args.rope and not args.kcat else None
+        r["traffic"] = MEASURED_TRAFFIC_C3.get(stage) if cfg.name == "c3" and args.score_path == 0 and not args.rope and not args.kcat and not args.window else None
         r["traffic_source"] = "profiles/ccd_compress_c3_hbm_traffic.md" if r["traffic"] else None
         r["avg_us"] = stage_avg_us[stage]
         return r
@@ -290,7 +295,7 @@ def main() -> int:
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B{cfg.B} L{cfg.L} Hq{cfg.Hq} Hkv{cfg.Hkv} d{cfg.d} N{cfg.N}->k{cfg.k} "
                                f"P{cfg.P} T{cfg.T} pool{cfg.w}", "ring": [len(pots), len(qsets), len(novs)], "score_path": args.score_path,
-                   "cap_keys_in_softmax": bool(args.kcat)},
+                   "cap_keys_in_softmax": bool(args.kcat), "window": args.window},
         "call_hbm": {"algorithmic_bytes": ab["call"], "achieved_GBps": call_gbps, "frac_of_peak": call_gbps / HBM_PEAK_GBPS},
         "stage_avg_us": stage_avg_us, "moved_row_fraction": moved,
         "roofline": roof, "roofline_other_kernels": by_kernel,
@@ -310,6 +315,8 @@ def main() -> int:
         rope_kw = dict(rope_cos=cos_h, rope_sin=sin_h) if args.rope else {}
         if args.kcat:
             rope_kw["K_cap"] = k_cap_h
+        if args.window:
+            rope_kw["window"] = args.window
         O.compress(host0["Q_cat"], host0["K"], host0["V"], host0["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w,
                    pool_mode=O.POOL_MAX, units=sample, **rope_kw)
         c1 = time.perf_counter()

@@ -65,6 +65,12 @@ typedef struct {
                               /* avg: zero padding, divide by pool_w.  Pooling precedes the NuC lift.    */
   int32_t dtype;              /* CCD_FP32 or CCD_BF16, for Q_cat, K and V                                */
   float scale;                /* logit scale; 0 means 1/sqrt(d)                                          */
+  int32_t window;             /* sliding attention window in tokens, 0 = none (Sec. 4, footnote on SWA   */
+                              /* models): the cached tokens stand at positions 0 .. n_valid-1 and CaP    */
+                              /* token i at n_valid + i; a query at position p sees the keys at          */
+                              /* p-window+1 .. p only.  window >= P when set; bf16 caches: at most 2048  */
+                              /* tokens may be hidden from the last CaP token (CCD_EUNSUPPORTED beyond). */
+  int32_t reserved;           /* must be 0                                                               */
   int64_t kv_stride_b, kv_stride_l, kv_stride_h;    /* K, V: [B, L, Hkv, n_cap, d], strides in elements */
   int64_t q_stride_b, q_stride_l, q_stride_h;       /* Q_cat: [B, L, Hq, P, d]                          */
   int64_t nov_stride_b, nov_stride_l, nov_stride_h; /* novelty fp32: [B, n] shared by layers and heads  */

@@ -40,8 +40,9 @@ __device__ __forceinline__ int64_t q_offset(const Dims& D, UnitIdx u, int q) {
   int g = q / D.P, i = q - g * D.P;
   return u.b * D.q_sb + u.l * D.q_sl + (int64_t)(u.h * D.G + g) * D.q_sh + (int64_t)i * D.d;
 }
-// where the statistics of the CaP keys' block of (unit, query q) live in `part`: behind the slices of all units
-__device__ __forceinline__ int64_t cap_block_index(const Dims& D, const ScorePlan& pl, int unit, int q) {
+// where the one extra (max, sum) entry of (unit, query q) lives in `part`, behind the slices of all units: the block of
+// the CaP keys on the vector-ALU path, the windowed head on the matrix-core path
+__device__ __forceinline__ int64_t extra_block_index(const Dims& D, const ScorePlan& pl, int unit, int q) {
   return ((int64_t)D.units * pl.n_slices1 + unit) * D.GP + q;
 }
 __device__ __forceinline__ int64_t nov_offset(const Dims& D, UnitIdx u) {

@@ -17,6 +17,9 @@ struct Dims {
   int units;    // B * L * Hkv
   int unit0, units_run;   // the range of units one launch covers (a call may be split into chunks)
   float scale_log2;  // logit scale times log2(e): probabilities are computed with exp2
+  // sliding attention window (0 = none): CaP token i sees cached token t iff t >= win_off + i; tokens below `head`
+  // (a multiple of 32, at most n) are hidden from some CaP token, the others are seen by all
+  int window, win_off, head;
   int64_t kv_sb, kv_sl, kv_sh;
   int64_t q_sb, q_sl, q_sh;
   int64_t nov_sb, nov_sl, nov_sh;
@@ -28,7 +31,8 @@ struct ScorePlan {
   int n_slices1;
   int slice2;     // tokens per workgroup in the probability pass
   int n_slices2;
-  int cap_block;  // 1: `part` also holds the statistics of the CaP keys' block (causal variant of Eq. 2)
+  int cap_block;  // 1 (vector-ALU path): `part` also holds the statistics of the CaP keys' block (causal Eq. 2)
+  int head_block; // 1 (matrix-core path): `part` also holds the statistics of the windowed head (sliding window)
 };
 
 ScorePlan plan_score(const Dims& D);
@@ -50,8 +54,16 @@ void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const 
 // K_cap (nullable; [units, P, d], contiguous): the CaP tokens' own keys join the softmax (Eq. 2 read as the model's
 // causal attention row: query row g * P + i also sees the CaP keys 0 .. i); their statistics are computed in the
 // prologue of pass 2 and merged like one more token slice
+// lse_out ([units, G*P], written when pl.head_block): the final log2-sum-exp per query, for launch_head_prob_mfma
 void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const void* K_cap,
-                      const float2* part, float* u, hipStream_t s);
+                      const float2* part, float* u, float* lse_out, hipStream_t s);
+// Sliding attention window on the matrix-core path: the first D.head tokens are hidden from some CaP tokens and are
+// left out of the two passes above.  launch_head_stats_mfma (before pass 2) leaves their (max, sum) statistics per
+// query in the extra entry of `part` (pl.head_block must be 1); launch_head_prob_mfma (after pass 2) writes
+// u[unit, 0 .. D.head) from the final log2-sum-exps.
+void launch_head_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s);
+void launch_head_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float* lse, float* u,
+                           hipStream_t s);
 
 // The same on the vector-ALU path: statistics of CaP key j under CaP query i for j <= i, written to `part` behind
 // the slices of all units (pl.cap_block must be 1; launch_merge then takes them in).  K_cap as above.

@@ -286,17 +286,17 @@ __device__ __forceinline__ void interleave_hint() {
   }
 }
 
-// Pass 1 of one sweep the careful way (running maximum, rescaled sums), tile by tile without any overlap: the
-// fallback for sweeps whose fixed-reference sums overflowed.  Called by all threads of the workgroup; uses ring slot
-// 0 (`ring` points at it), which must be idle.  q_row0 / q_row1: the lane's query rows of block 0 and 1, or
-// null past the end.  Not inlined: it is rare, and as a function it leaves the registers of the main loop alone.
+// Pass 1 over the tokens [t0, t1) of a unit the careful way (running maximum, rescaled sums), tile by tile without
+// any overlap.  Called by all threads of the workgroup; uses ring slot 0 (`ring` points at it), which must be idle.
+// q_row0 / q_row1: the lane's query rows of block 0 and 1, or null past the end.  WINDOWED: first0 / first1 are the
+// first tokens those queries see (sliding attention window); a query that sees none gets (kNegHuge, 0).
 struct MaxSum2 { float m[kQB], Z[kQB]; };
-template <int HD>
-__device__ __attribute__((noinline)) MaxSum2 stats_sweep_careful(const uint16_t* __restrict__ Ku, int t0, int t1,
-                                                                 const uint16_t* __restrict__ q_row0,
-                                                                 const uint16_t* __restrict__ q_row1,
-                                                                 __attribute__((address_space(3))) uint8_t* ring,
-                                                                 float c) {
+template <int HD, bool WINDOWED>
+__device__ __forceinline__ MaxSum2 stats_sweep_body(const uint16_t* __restrict__ Ku, int t0, int t1,
+                                                    const uint16_t* __restrict__ q_row0,
+                                                    const uint16_t* __restrict__ q_row1,
+                                                    __attribute__((address_space(3))) uint8_t* ring, float c,
+                                                    int first0, int first1) {
   constexpr int KS = HD / 16;
   static_assert(kQB == 2, "two query rows per lane are passed in");
   // arguments of a callable function arrive in vector registers; the DMA wants its base addresses in scalar ones
@@ -335,11 +335,94 @@ __device__ __attribute__((noinline)) MaxSum2 stats_sweep_careful(const uint16_t*
     floatx16 acc[kQB];
     logits<HD, 1>(acc, a, bq);
     const int nvalid = t1 - t0 - s * kStep;
+    if (WINDOWED) {
+      const int tile_t = t0 + s * kStep;
+#pragma unroll
+      for (int qb = 0; qb < kQB; ++qb) {
+        const int first = qb == 0 ? first0 : first1;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (tile_t + acc_row(i, half) < first) acc[qb][i] = -INFINITY;
+      }
+    }
     if (nvalid < kStep) fold_stats<true>(acc, r.m, r.Z, c, half, nvalid);
     else                fold_stats<false>(acc, r.m, r.Z, c, half, kStep);
     __syncthreads();   // slot 0 is overwritten by the next tile
   }
   return r;
+}
+
+// The fallback of the pipelined pass 1 for sweeps whose fixed-reference sums overflowed.  Not inlined: it is rare,
+// and as a function it leaves the registers of the main loop alone.
+template <int HD>
+__device__ __attribute__((noinline)) MaxSum2 stats_sweep_careful(const uint16_t* __restrict__ Ku, int t0, int t1,
+                                                                 const uint16_t* __restrict__ q_row0,
+                                                                 const uint16_t* __restrict__ q_row1,
+                                                                 __attribute__((address_space(3))) uint8_t* ring,
+                                                                 float c) {
+  return stats_sweep_body<HD, false>(Ku, t0, t1, q_row0, q_row1, ring, c, 0, 0);
+}
+
+// Pass 2 for the tokens [t0, t1) that a sliding attention window hides from some queries: probabilities of each
+// token under the workgroup's query rows that do see it, summed per wave into up_w[token - t0] (this wave's row of
+// the partial sums in LDS).  Tile by tile without overlap; ring slot 0 must be idle; ends with a barrier.  qrow_base:
+// index of the wave's first query row; lse_w: the wave's 64 log2-sum-exps (LDS); a query row g*P + i sees token t
+// iff t >= win_off + i.
+template <int HD>
+__device__ __forceinline__ void prob_head_masked(const uint16_t* __restrict__ Ku, int t0, int t1,
+                                                           const uint16_t* __restrict__ q_row0,
+                                                           const uint16_t* __restrict__ q_row1,
+                                                           __attribute__((address_space(3))) uint8_t* ring, float c,
+                                                           const float* lse_w, float* up_w, int qrow_base, int P,
+                                                           int win_off) {
+  constexpr int KS = HD / 16;
+  static_assert(kQB == 2, "two query rows per lane are passed in");
+  const uint64_t ku_bits = reinterpret_cast<uint64_t>(Ku);
+  Ku = reinterpret_cast<const uint16_t*>(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(ku_bits >> 32)) << 32) |
+                                         (uint32_t)__builtin_amdgcn_readfirstlane((int)ku_bits));
+  t0 = __builtin_amdgcn_readfirstlane(t0);
+  t1 = __builtin_amdgcn_readfirstlane(t1);
+  const uint32_t lds_addr = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)ring);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63, col = lane & 31, half = lane >> 5;
+  const uint8_t* lds = (const uint8_t*)ring;
+  int koff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) koff[ks] = col * Tiles<HD>::kRowBytes + (((2 * ks + half) ^ Tiles<HD>::swz(col)) << 4);
+  uint32_t voff_full[Tiles<HD>::kInstrPerWave];
+  tile_offsets<HD>(voff_full, wave, lane);
+  bf16x8 bq[kQB][KS];
+#pragma unroll
+  for (int qb = 0; qb < kQB; ++qb) {
+    const uint16_t* qp = qb == 0 ? q_row0 : q_row1;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      bq[qb][ks] = qp != nullptr ? *reinterpret_cast<const bf16x8*>(qp + half * 8 + ks * 16) : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+  }
+  const int S = (t1 - t0 + kStep - 1) / kStep;
+  for (int s = 0; s < S; ++s) {
+    issue_tile<HD>(Ku, t0, t1, s, lds_addr, wave, lane, voff_full);
+    wait_all_dma();
+    __syncthreads();
+    bf16x8 a[KS];
+    load_k_frags<HD, 0>(a, lds, koff);
+    floatx16 acc[kQB];
+    logits<HD, 2>(acc, a, bq);                   // D[query][token]: the lane owns token s * 32 + col
+    const int t = t0 + s * kStep + col;
+    float us = 0.f;
+#pragma unroll
+    for (int qb = 0; qb < kQB; ++qb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = qb * 32 + acc_row(r, half);
+        const bool sees = t >= win_off + (qrow_base + row) % P;
+        const float p = fast_exp2(fmaf(acc[qb][r], c, -lse_w[row]));
+        us += sees ? p : 0.f;
+      }
+    us += __shfl_xor(us, 32);
+    if (half == 0) up_w[s * kStep + col] = us;
+    __syncthreads();   // slot 0 is overwritten by the next tile; after the last one the sums are visible
+  }
 }
 
 // PASS 1 writes part[unit][slice][q] = (max2, sum); PASS 2 reads part (all slices of the unit), adds the block of
@@ -360,7 +443,8 @@ template <int HD, int PASS>
 __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& pl, int unit, int slice,
                                                 const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
                                                 float2* __restrict__ part, float* __restrict__ u,
-                                                const uint16_t* __restrict__ Kcap, ScoreLds<HD, PASS>& sm) {
+                                                const uint16_t* __restrict__ Kcap, float* __restrict__ lse_out,
+                                                ScoreLds<HD, PASS>& sm) {
   constexpr int KS = HD / 16;
   constexpr int SLOTB = Tiles<HD>::kSlotBytes;
   constexpr int kBatch = Ring<PASS>::kBatch, kDepth = Ring<PASS>::kDepth;
@@ -370,8 +454,12 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
   const int slice_len = PASS == 1 ? pl.slice1 : pl.slice2;
   const UnitIdx ui = decode_unit(D, unit);
   const uint16_t* Ku = K + kv_offset(D, ui);
-  const int t0 = slice * slice_len, t1 = min(D.n, t0 + slice_len);
-  const int S = (t1 - t0 + kStep - 1) / kStep;       // tiles in the slice (the last one may be partial)
+  // [t0s, t1): the slice.  [t0s, t0): its tokens that a sliding attention window hides from some query (none without
+  // a window, and only in the first slice or two with one): they are left to the two small kernels of the windowed
+  // head.  [t0, t1): tokens every query sees - the pipelined loop below.
+  const int t0s = slice * slice_len, t1 = min(D.n, t0s + slice_len);
+  const int t0 = max(t0s, min(D.head, t1));
+  const int S = (t1 - t0 + kStep - 1) / kStep;       // tiles of the main part (the last one may be partial)
   const int S_full = (t1 - t0) / kStep;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63, col = lane & 31, half = lane >> 5;
@@ -411,6 +499,11 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
         cap = cap_block_stats<HD>(D, Kcap + (int64_t)unit * D.P * HD, bq, qc + wave * (kQB * 32), col, half, c);
       if (q < D.GP) {
         const float2* p = part + (int64_t)unit * pl.n_slices1 * D.GP + q;
+        if (pl.head_block) {         // statistics of the windowed head, left there by its own kernel
+          const float2 hd = part[extra_block_index(D, pl, unit, q)];
+          const float Mh = fmaxf(cap.x, hd.x);
+          cap = make_float2(Mh, cap.y * fast_exp2(cap.x - Mh) + hd.y * fast_exp2(hd.x - Mh));
+        }
         float M = cap.x;
         for (int j = 0; j < pl.n_slices1; ++j) M = fmaxf(M, p[(int64_t)j * D.GP].x);
         float z = cap.y * fast_exp2(cap.x - M);
@@ -419,6 +512,7 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
           z += v.y * fast_exp2(v.x - M);
         }
         lse = M + __log2f(z);
+        if (pl.head_block && slice == 0) lse_out[(int64_t)unit * D.GP + q] = lse;   // for the head's probabilities
       }
       lse_s[threadIdx.x] = lse;
     }

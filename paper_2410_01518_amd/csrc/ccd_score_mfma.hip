@@ -66,7 +66,8 @@ __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl
                                                             const uint16_t* __restrict__ K, float2* __restrict__ part,
                                                             float* __restrict__ u, const float* __restrict__ novelty,
                                                             uint8_t* __restrict__ nuc_mask,
-                                                            const uint16_t* __restrict__ Kcap) {
+                                                            const uint16_t* __restrict__ Kcap,
+                                                            float* __restrict__ lse_out) {
   __shared__ ScoreLds<HD, PASS> sm;
   if (PASS == 1 && novelty != nullptr)
     nuc_rank_share(novelty, nuc_mask, D.B, D.n, D.nov_sb, D.T, blockIdx.x, gridDim.x);
@@ -76,7 +77,71 @@ __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl
   // memory-side cache
   if (PASS == 2) unit = D.units_run - 1 - unit;
   unit += D.unit0;
-  score_pass_body<HD, PASS>(D, pl, unit, slice, Q, K, part, u, Kcap, sm);
+  score_pass_body<HD, PASS>(D, pl, unit, slice, Q, K, part, u, Kcap, lse_out, sm);
+}
+
+// Sliding attention window: the tokens [0, D.head) that some CaP token does not see.  Two small kernels, one workgroup
+// per unit, outside the two big passes (which start at D.head): statistics before pass 2, probabilities after it.
+template <int HD>
+struct HeadLds {
+  __attribute__((aligned(1024))) uint8_t slot[Tiles<HD>::kSlotBytes];
+  float lse_s[kQPerPass];
+  float up[4][kMaxSlice];
+};
+
+template <int HD>
+__global__ __launch_bounds__(kMT) void head_stats_kernel(Dims D, ScorePlan pl, const uint16_t* __restrict__ Q,
+                                                         const uint16_t* __restrict__ K, float2* __restrict__ part) {
+  __shared__ HeadLds<HD> sm;
+  const int unit = D.unit0 + blockIdx.x;
+  const UnitIdx ui = decode_unit(D, unit);
+  const uint16_t* Ku = K + kv_offset(D, ui);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63, col = lane & 31, half = lane >> 5;
+  const float c = D.scale_log2;
+  for (int qc = 0; qc < D.GP; qc += kQPerPass) {
+    const int q0 = qc + wave * (kQB * 32) + col;
+    const MaxSum2 r = stats_sweep_body<HD, true>(Ku, 0, D.head, q0 < D.GP ? Q + q_offset(D, ui, q0) : nullptr,
+                                              q0 + 32 < D.GP ? Q + q_offset(D, ui, q0 + 32) : nullptr,
+                                              (__attribute__((address_space(3))) uint8_t*)sm.slot, c,
+                                              D.win_off + q0 % D.P, D.win_off + (q0 + 32) % D.P);
+#pragma unroll
+    for (int qb = 0; qb < kQB; ++qb) {
+      const float m_o = __shfl_xor(r.m[qb], 32), z_o = __shfl_xor(r.Z[qb], 32);
+      const float M = fmaxf(r.m[qb], m_o);
+      const float z = r.Z[qb] * fast_exp2((r.m[qb] - M) * c) + z_o * fast_exp2((m_o - M) * c);
+      const int q = q0 + qb * 32;
+      if (half == 0 && q < D.GP) part[extra_block_index(D, pl, unit, q)] = make_float2(M * c, z);
+    }
+  }
+}
+
+template <int HD>
+__global__ __launch_bounds__(kMT) void head_prob_kernel(Dims D, const uint16_t* __restrict__ Q,
+                                                        const uint16_t* __restrict__ K, const float* __restrict__ lse,
+                                                        float* __restrict__ u) {
+  __shared__ HeadLds<HD> sm;
+  const int unit = D.unit0 + blockIdx.x;
+  const UnitIdx ui = decode_unit(D, unit);
+  const uint16_t* Ku = K + kv_offset(D, ui);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63, col = lane & 31;
+  float* uu = u + (int64_t)unit * D.n;
+  for (int qc = 0; qc < D.GP; qc += kQPerPass) {
+    const int q = qc + threadIdx.x;
+    sm.lse_s[threadIdx.x] = q < D.GP ? lse[(int64_t)unit * D.GP + q] : INFINITY;
+    __syncthreads();
+    const int q0 = qc + wave * (kQB * 32) + col;
+    prob_head_masked<HD>(Ku, 0, D.head, q0 < D.GP ? Q + q_offset(D, ui, q0) : nullptr,
+                         q0 + 32 < D.GP ? Q + q_offset(D, ui, q0 + 32) : nullptr,
+                         (__attribute__((address_space(3))) uint8_t*)sm.slot, D.scale_log2, &sm.lse_s[wave * (kQB * 32)],
+                         &sm.up[wave][0], qc + wave * (kQB * 32), D.P, D.win_off);
+    for (int t = threadIdx.x; t < D.head; t += kMT) {     // the same thread every sweep: no race on u
+      const float v = (sm.up[0][t] + sm.up[1][t]) + (sm.up[2][t] + sm.up[3][t]);
+      uu[t] = qc == 0 ? v : uu[t] + v;
+    }
+    __syncthreads();   // lse_s and up are rewritten by the next sweep
+  }
 }
 
 constexpr int kRankMaxSteps = 256;   // rank-counting steps (of 64 rivals) a wave may be asked to do
@@ -102,22 +167,40 @@ void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const 
   dim3 grid(stats_grid(D, pl)), block(kMT);
   if (D.d == 64)
     hipLaunchKernelGGL((score_pass_kernel<64, 1>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
-                       (float*)nullptr, novelty, nuc_mask, (const uint16_t*)nullptr);
+                       (float*)nullptr, novelty, nuc_mask, (const uint16_t*)nullptr, (float*)nullptr);
   else
     hipLaunchKernelGGL((score_pass_kernel<128, 1>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
-                       (float*)nullptr, novelty, nuc_mask, (const uint16_t*)nullptr);
+                       (float*)nullptr, novelty, nuc_mask, (const uint16_t*)nullptr, (float*)nullptr);
+}
+
+void launch_head_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s) {
+  dim3 grid((unsigned)D.units_run), block(kMT);
+  if (D.d == 64)
+    hipLaunchKernelGGL((head_stats_kernel<64>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part);
+  else
+    hipLaunchKernelGGL((head_stats_kernel<128>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part);
+}
+
+void launch_head_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float* lse, float* u,
+                           hipStream_t s) {
+  (void)pl;
+  dim3 grid((unsigned)D.units_run), block(kMT);
+  if (D.d == 64)
+    hipLaunchKernelGGL((head_prob_kernel<64>), grid, block, 0, s, D, (const uint16_t*)Q, (const uint16_t*)K, lse, u);
+  else
+    hipLaunchKernelGGL((head_prob_kernel<128>), grid, block, 0, s, D, (const uint16_t*)Q, (const uint16_t*)K, lse, u);
 }
 
 // K_cap (nullable; [units, P, d] bf16): the CaP tokens' own keys join the softmax, causally
 void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const void* K_cap,
-                      const float2* part, float* u, hipStream_t s) {
+                      const float2* part, float* u, float* lse_out, hipStream_t s) {
   dim3 grid((unsigned)((D.units_run + 7) / 8 * 8) * pl.n_slices2), block(kMT);
   if (D.d == 64)
     hipLaunchKernelGGL((score_pass_kernel<64, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
-                       const_cast<float2*>(part), u, (const float*)nullptr, (uint8_t*)nullptr, (const uint16_t*)K_cap);
+                       const_cast<float2*>(part), u, (const float*)nullptr, (uint8_t*)nullptr, (const uint16_t*)K_cap, lse_out);
   else
     hipLaunchKernelGGL((score_pass_kernel<128, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
-                       const_cast<float2*>(part), u, (const float*)nullptr, (uint8_t*)nullptr, (const uint16_t*)K_cap);
+                       const_cast<float2*>(part), u, (const float*)nullptr, (uint8_t*)nullptr, (const uint16_t*)K_cap, lse_out);
 }
 
 }  // namespace ccd

@@ -39,6 +39,8 @@ __global__ __launch_bounds__(kThreads) void stats_valu_kernel(Dims D, ScorePlan 
       for (int c = 0; c < HD / 4; ++c) qr[c] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
     float m = -INFINITY, Z = 0.f;
+    // sliding window: the first cached token this query sees (0 without a window)
+    const int first = D.window > 0 ? max(0, D.win_off + q % D.P) : 0;
     for (int tt = t0; tt < t1; tt += kTokTile) {
       __syncthreads();
       for (int e = tid; e < kTokTile * (HD / 4); e += kThreads) {
@@ -49,7 +51,7 @@ __global__ __launch_bounds__(kThreads) void stats_valu_kernel(Dims D, ScorePlan 
       __syncthreads();
       const int nt = min(kTokTile, t1 - tt);
       if (active) {
-        for (int t = 0; t < nt; ++t) {
+        for (int t = max(0, first - tt); t < nt; ++t) {
           float acc = 0.f;
 #pragma unroll
           for (int c = 0; c < HD / 4; ++c) {
@@ -124,7 +126,7 @@ __global__ __launch_bounds__(kThreads) void cap_block_stats_valu_kernel(Dims D, 
         }
       }
     }
-    if (active) part[cap_block_index(D, pl, unit, q)] = make_float2(m, Z);
+    if (active) part[extra_block_index(D, pl, unit, q)] = make_float2(m, Z);
   }
 }
 
@@ -136,17 +138,18 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Dims D, ScorePlan pl, c
   if (q >= D.GP) return;
   const float2* p = part + (int64_t)unit * pl.n_slices1 * D.GP + q;
   float M = -INFINITY, Z = 0.f;
-  if (pl.cap_block) M = part[cap_block_index(D, pl, unit, q)].x;
+  if (pl.cap_block) M = part[extra_block_index(D, pl, unit, q)].x;
   for (int j = 0; j < pl.n_slices1; ++j) M = fmaxf(M, p[(int64_t)j * D.GP].x);
   if (pl.cap_block) {
-    const float2 v = part[cap_block_index(D, pl, unit, q)];
+    const float2 v = part[extra_block_index(D, pl, unit, q)];
     Z = v.y * fast_exp2(v.x - M);
   }
   for (int j = 0; j < pl.n_slices1; ++j) {
     const float2 v = p[(int64_t)j * D.GP];
-    Z += v.y * fast_exp2(v.x - M);
+    if (!(v.y == 0.f)) Z += v.y * fast_exp2(v.x - M);   // a slice may lie outside the query's window: (-inf, 0)
   }
-  lse2[(int64_t)unit * D.GP + q] = M + __log2f(Z);
+  // a query that sees no key at all (window == P at most, no CaP keys): +inf, every probability comes out 0
+  lse2[(int64_t)unit * D.GP + q] = Z == 0.f ? INFINITY : M + __log2f(Z);
 }
 
 template <typename T, int HD>
@@ -180,6 +183,7 @@ __global__ __launch_bounds__(kThreads) void prob_valu_kernel(Dims D, ScorePlan p
     __syncthreads();
     const int nq = min(kQryTile, D.GP - q0);
     for (int qi = 0; qi < nq; ++qi) {
+      if (D.window > 0 && tok < D.win_off + (q0 + qi) % D.P) continue;   // outside this query's window
       float acc = 0.f;
 #pragma unroll
       for (int c = 0; c < HD / 4; ++c) {

@@ -45,6 +45,7 @@ static int check_shape(const ccd_shape_t* s, int need) {
     if (!(s->scale >= 0.f) || isinf(s->scale)) return CCD_EINVAL;
     if (s->pool_mode < CCD_POOL_NONE || s->pool_mode > CCD_POOL_AVG) return CCD_EUNSUPPORTED;
     if (s->pool_w < 1 || s->pool_w % 2 == 0) return CCD_EINVAL;
+    if (s->window < 0 || (s->window > 0 && s->window < s->P) || s->reserved != 0) return CCD_EINVAL;
   }
   if (need & kNeedNov) {
     if (s->T < 0 || s->T > s->k) return CCD_EINVAL;
@@ -68,6 +69,13 @@ static Dims make_dims(const ccd_shape_t* s) {
   D.units_run = D.units;
   const double scale = s->scale > 0.f ? (double)s->scale : 1.0 / sqrt((double)(s->d > 0 ? s->d : 1));
   D.scale_log2 = (float)(scale * 1.4426950408889634074);
+  D.window = s->window;
+  D.win_off = s->window > 0 ? s->n_valid + 1 - s->window : 0;
+  D.head = 0;
+  if (s->window > 0 && s->n_valid + s->P > s->window) {
+    const int64_t hidden = (int64_t)s->n_valid + s->P - s->window;        // tokens hidden from the last CaP token
+    D.head = (int)((hidden + 31) / 32 * 32 < s->n_valid ? (hidden + 31) / 32 * 32 : s->n_valid);
+  }
   D.kv_sb = s->kv_stride_b; D.kv_sl = s->kv_stride_l; D.kv_sh = s->kv_stride_h;
   D.q_sb = s->q_stride_b; D.q_sl = s->q_stride_l; D.q_sh = s->q_stride_h;
   D.nov_sb = s->nov_stride_b; D.nov_sl = s->nov_stride_l; D.nov_sh = s->nov_stride_h;
@@ -107,6 +115,7 @@ static ScorePlan plan_mfma(const Dims& D) {
   pl.n_slices1 = (D.n + pl.slice1 - 1) / pl.slice1;
   pl.n_slices2 = (D.n + pl.slice2 - 1) / pl.slice2;
   pl.cap_block = 0;
+  pl.head_block = 0;
   return pl;
 }
 
@@ -122,6 +131,7 @@ ScorePlan plan_score(const Dims& D) {
   pl.n_slices1 = (D.n + pl.slice1 - 1) / pl.slice1;
   pl.n_slices2 = (D.n + pl.slice2 - 1) / pl.slice2;
   pl.cap_block = 0;
+  pl.head_block = 0;
   return pl;
 }
 
@@ -149,9 +159,9 @@ static int check_workspace(const Workspace& w, const void* ws, size_t ws_bytes) 
 }
 
 // ---- optional per-kernel timing of ccd_compress -------------------------------------------------------
-enum Stage { kStNuc = 0, kStStats, kStMerge, kStProb, kStSelect, kStCompact, kStSelCompact, kStCapBlock, kNumStages };
-static const char* const kStageNames[kNumStages] = {"nuc_mask", "score_stats",    "score_merge", "score_prob", "select",
-                                                    "compact",  "select_compact", "cap_block"};
+enum Stage { kStNuc = 0, kStStats, kStMerge, kStProb, kStSelect, kStCompact, kStSelCompact, kStCapBlock, kStHead, kNumStages };
+static const char* const kStageNames[kNumStages] = {"nuc_mask", "score_stats",    "score_merge", "score_prob",   "select",
+                                                    "compact",  "select_compact", "cap_block",   "window_head"};
 
 // Every profiled launch is bracketed by two events on the stream it runs on.
 struct Profiler {
@@ -206,12 +216,23 @@ static void run_mask_and_cap_scores(const Dims& D, ScorePlan pl, const Workspace
     g_prof.end(st);
   }
   if (pl.use_mfma) {
+    if (D.head > 0) {                        // sliding window: the tokens some CaP token does not see
+      pl.head_block = 1;
+      g_prof.begin(kStHead, st);
+      launch_head_stats_mfma(D, pl, Q, K, part, st);
+      g_prof.end(st);
+    }
     g_prof.begin(kStStats, st);
     launch_stats_mfma(D, pl, Q, K, part, nuc_in_stats ? novelty : nullptr, mask, st);
     g_prof.end(st);
     g_prof.begin(kStProb, st);
-    launch_prob_mfma(D, pl, Q, K, K_cap, part, u, st);
+    launch_prob_mfma(D, pl, Q, K, K_cap, part, u, lse2, st);
     g_prof.end(st);
+    if (D.head > 0) {
+      g_prof.begin(kStHead, st);
+      launch_head_prob_mfma(D, pl, Q, K, lse2, u, st);
+      g_prof.end(st);
+    }
   } else {
     g_prof.begin(kStStats, st);
     launch_stats_valu(D, pl, Q, K, part, st);
@@ -246,6 +267,7 @@ static int score_impl(const ccd_shape_t* shape, const void* Q_cat, const void* K
   if (!aligned16(Q_cat) || !aligned16(K) || !aligned16(K_cap)) return CCD_EALIGN;
   const Dims D = make_dims(shape);
   const ScorePlan pl = plan_score(D);
+  if (pl.use_mfma && D.head > mfma_max_slice()) return CCD_EUNSUPPORTED;   // window far shorter than the pot
   const Workspace w = layout_workspace(D);
   rc = check_workspace(w, workspace, workspace_bytes);
   if (rc != CCD_OK) return rc;
@@ -312,6 +334,7 @@ static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, v
   const void* K_attn = K_score != nullptr ? K_score : K;     // the keys the CaP queries attend to
   const Dims D = make_dims(shape);
   const ScorePlan pl = plan_score(D);
+  if (pl.use_mfma && D.head > mfma_max_slice()) return CCD_EUNSUPPORTED;   // window far shorter than the pot
   const Workspace w = layout_workspace(D);
   rc = check_workspace(w, workspace, workspace_bytes);
   if (rc != CCD_OK) return rc;

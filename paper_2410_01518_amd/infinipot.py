@@ -29,7 +29,7 @@ EXPORTS = ("ccd_workspace_bytes", "ccd_score", "ccd_select", "ccd_compact", "ccd
 class ccd_shape_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("B", "L", "Hq", "Hkv", "d", "n_valid", "n_cap", "k", "P", "T", "pool_w", "pool_mode", "dtype")]
-    _fields_ += [("scale", ctypes.c_float)]
+    _fields_ += [("scale", ctypes.c_float), ("window", ctypes.c_int32), ("reserved", ctypes.c_int32)]
     _fields_ += [(n, ctypes.c_int64) for n in
                  ("kv_stride_b", "kv_stride_l", "kv_stride_h", "q_stride_b", "q_stride_l", "q_stride_h",
                   "nov_stride_b", "nov_stride_l", "nov_stride_h")]
@@ -117,7 +117,8 @@ def _dtype_code(t: torch.Tensor) -> int:
     raise TypeError(f"unsupported cache dtype {t.dtype}")
 
 
-def make_shape(Q_cat, K, novelty, *, k, T=0, pool_w=1, pool_mode=CCD_POOL_MAX, scale=0.0, n_valid=None) -> ccd_shape_t:
+def make_shape(Q_cat, K, novelty, *, k, T=0, pool_w=1, pool_mode=CCD_POOL_MAX, scale=0.0, n_valid=None,
+               window=0) -> ccd_shape_t:
     """Shape descriptor from tensor geometry: Q_cat [B,L,Hq,P,d], K [B,L,Hkv,n_cap,d], novelty [B,n] or
     [B,L,Hkv,n_cap] (may be None when T == 0).  Q_cat may be None for calls that do not read it."""
     B, L, Hkv, n_cap, d = K.shape
@@ -125,6 +126,7 @@ def make_shape(Q_cat, K, novelty, *, k, T=0, pool_w=1, pool_mode=CCD_POOL_MAX, s
     s.B, s.L, s.Hkv, s.d, s.n_cap = B, L, Hkv, d, n_cap
     s.n_valid = n_cap if n_valid is None else n_valid
     s.k, s.T, s.pool_w, s.pool_mode, s.scale = k, T, pool_w, pool_mode, scale
+    s.window = window
     s.dtype = _dtype_code(K)
     assert K.stride(4) == 1 and K.stride(3) == d, "K rows must be contiguous with stride d"
     s.kv_stride_b, s.kv_stride_l, s.kv_stride_h = K.stride(0), K.stride(1), K.stride(2)
