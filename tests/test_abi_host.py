@@ -32,8 +32,9 @@ def test_struct_layout_matches_header():
 #include <stdio.h>
 #include <stddef.h>
 #include "infinipot.h"
-int main(void){ printf("%zu %zu %zu %zu %zu\n", sizeof(ccd_shape_t), offsetof(ccd_shape_t, scale),
-  offsetof(ccd_shape_t, kv_stride_b), offsetof(ccd_shape_t, q_stride_h), offsetof(ccd_shape_t, nov_stride_h));
+int main(void){ printf("%zu %zu %zu %zu %zu %zu\n", sizeof(ccd_shape_t), offsetof(ccd_shape_t, scale),
+  offsetof(ccd_shape_t, kv_stride_b), offsetof(ccd_shape_t, q_stride_h), offsetof(ccd_shape_t, nov_stride_h),
+  offsetof(ccd_shape_t, window));
   printf("%d %d %d %d %d %d %d\n", CCD_OK, CCD_NOOP, CCD_EINVAL, CCD_EUNSUPPORTED, CCD_EALIGN, CCD_EWORKSPACE, CCD_ELAUNCH);
   return 0; }'''
     with tempfile.TemporaryDirectory() as td:
@@ -43,8 +44,9 @@ int main(void){ printf("%zu %zu %zu %zu %zu\n", sizeof(ccd_shape_t), offsetof(cc
         out = subprocess.run([exe], capture_output=True, text=True, check=True).stdout.split()
     vals = [int(v) for v in out]
     S = ip.ccd_shape_t
-    assert vals[:5] == [ctypes.sizeof(S), S.scale.offset, S.kv_stride_b.offset, S.q_stride_h.offset, S.nov_stride_h.offset]
-    assert vals[5:] == [ip.CCD_OK, ip.CCD_NOOP, ip.CCD_EINVAL, ip.CCD_EUNSUPPORTED, ip.CCD_EALIGN, ip.CCD_EWORKSPACE,
+    assert vals[:6] == [ctypes.sizeof(S), S.scale.offset, S.kv_stride_b.offset, S.q_stride_h.offset, S.nov_stride_h.offset,
+                        S.window.offset]
+    assert vals[6:] == [ip.CCD_OK, ip.CCD_NOOP, ip.CCD_EINVAL, ip.CCD_EUNSUPPORTED, ip.CCD_EALIGN, ip.CCD_EWORKSPACE,
                         ip.CCD_ELAUNCH]
 
 
@@ -164,6 +166,16 @@ def test_kcat_argument_errors_are_decided_on_the_host():
     assert score(scores=None) == ip.CCD_EINVAL and score(ws=None) == ip.CCD_EWORKSPACE
     assert compress(Kcap=P) == ip.CCD_EINVAL and compress(Kcap=P + 0x200000) == ip.CCD_EINVAL   # aliases K / V
     assert compress(shape=_shape(n_valid=300, n_cap=512, k=256)) == ip.CCD_NOOP
+
+
+def test_window_errors_are_decided_on_the_host():
+    assert _compress(_shape(window=-1)) == ip.CCD_EINVAL
+    assert _compress(_shape(window=15)) == ip.CCD_EINVAL                      # shorter than the P = 16 CaP tokens
+    assert _compress(_shape(reserved=1)) == ip.CCD_EINVAL
+    big = _shape(n_valid=8192, n_cap=8192, k=4096, T=0, window=8192 + 16 - 2049)
+    assert _compress(big) == ip.CCD_EUNSUPPORTED                              # more than 2048 tokens hidden (bf16 path)
+    assert ip.ccd_workspace_bytes(_shape(window=512)) == ip.ccd_workspace_bytes(_shape())
+    assert _compress(_shape(n_valid=300, n_cap=512, k=256, window=300)) == ip.CCD_NOOP
 
 
 def test_pot_not_full_is_a_noop_decided_on_the_host():
