@@ -131,6 +131,9 @@ def main() -> int:
     ap.add_argument("--kcat", action="store_true",
                     help="the causal variant of Eq. 2: the CaP tokens' own keys join the softmax (ccd_compress_kcat, or "
                          "ccd_compress_rope with K_cap when combined with --rope)")
+    ap.add_argument("--per-head-novelty", action="store_true",
+                    help="novelty carried per (layer, KV head) as in the cycles after the first one: [B, L, Hkv, N] "
+                         "instead of [B, N]; it is compacted in place with K and V")
     ap.add_argument("--window", type=int, default=0,
                     help="sliding attention window in tokens (0 = none), e.g. 4096 for a window as long as the pot")
     ap.add_argument("--aux", choices=["nuc", "cr_rope"], default=None,
@@ -189,8 +192,10 @@ def main() -> int:
     pots = [(dev0["K"], dev0["V"])] + [(fresh(torch.empty_like(dev0["K"])), fresh(torch.empty_like(dev0["V"])))
                                        for _ in range(1, n_pots)]
     qsets = [dev0["Q_cat"]] + [randn(cfg.B, cfg.L, cfg.Hq, cfg.P, cfg.d) for _ in range(3)]
-    novs = [dev0["novelty"]] + [torch.rand((cfg.B, cfg.N), generator=g, device=dev, dtype=torch.float32)
-                                for _ in range(4)]
+    nov_shape = (cfg.B, cfg.L, cfg.Hkv, cfg.N) if args.per_head_novelty else (cfg.B, cfg.N)
+    novs = [dev0["novelty"]] + [torch.rand(nov_shape, generator=g, device=dev, dtype=torch.float32) for _ in range(4)]
+    if args.per_head_novelty:
+        novs = novs[1:]
     shape = ip.make_shape(qsets[0], pots[0][0], novs[0], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=ip.CCD_POOL_MAX,
                           window=args.window)
     ws = ip.alloc_workspace(shape)
@@ -295,7 +300,8 @@ def main() -> int:
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B{cfg.B} L{cfg.L} Hq{cfg.Hq} Hkv{cfg.Hkv} d{cfg.d} N{cfg.N}->k{cfg.k} "
                                f"P{cfg.P} T{cfg.T} pool{cfg.w}", "ring": [len(pots), len(qsets), len(novs)], "score_path": args.score_path,
-                   "cap_keys_in_softmax": bool(args.kcat), "window": args.window},
+                   "cap_keys_in_softmax": bool(args.kcat), "window": args.window,
+                   "per_head_novelty": bool(args.per_head_novelty)},
         "call_hbm": {"algorithmic_bytes": ab["call"], "achieved_GBps": call_gbps, "frac_of_peak": call_gbps / HBM_PEAK_GBPS},
         "stage_avg_us": stage_avg_us, "moved_row_fraction": moved,
         "roofline": roof, "roofline_other_kernels": by_kernel,

@@ -101,7 +101,7 @@ constexpr int kScUnroll = 2;
 // j < k (rows that stay where they are included, so every kept K row is read); the pot itself keeps the plain keys.
 template <int KPT, int ROWB, bool ROPE, bool BF16>
 __global__ __launch_bounds__(kCpThreads) void select_compact_kernel(Dims D, const float* __restrict__ u,
-                                                                    const uint8_t* __restrict__ mask, float* scores,
+                                                                    float* novelty, int carry_novelty, float* scores,
                                                                     int32_t* __restrict__ keep_idx, char* Kbuf,
                                                                     char* Vbuf, const float* __restrict__ rope_cos,
                                                                     const float* __restrict__ rope_sin, char* Krot) {
@@ -109,8 +109,22 @@ __global__ __launch_bounds__(kCpThreads) void select_compact_kernel(Dims D, cons
   __shared__ __attribute__((aligned(16))) float u_stage[KPT * kCpThreads + 2 * kStagePad];
   int32_t* keep_lds = reinterpret_cast<int32_t*>(u_stage);
   const int unit = D.unit0 + blockIdx.x;
-  finalize_select_body<kCpThreads, KPT, true>(D, unit, u, mask, scores, keep_idx, sh, u_stage, keep_lds);
+  finalize_select_body<kCpThreads, KPT, true>(D, unit, u, novelty, scores, keep_idx, sh, u_stage, keep_lds);
   __syncthreads();
+
+  if (carry_novelty) {
+    // novelty carried per head: its kept entries move up like the rows (keep[j] >= j: a chunk's sources are read
+    // before anything at or above them is written)
+    float* nov = novelty + nov_offset(D, decode_unit(D, unit));
+    for (int base = 0; base < D.k; base += kCpThreads) {
+      const int j = base + threadIdx.x;
+      float v = 0.f;
+      if (j < D.k) v = nov[keep_lds[j]];
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (j < D.k) nov[j] = v;
+    }
+  }
 
   constexpr int kLanesPerRow = ROWB / 16;
   constexpr int kRowsPerPass = kCpThreads / kLanesPerRow;
@@ -194,14 +208,14 @@ bool select_compact_supported(const Dims& D) { return D.n <= 16 * kCpThreads; }
 
 // pooling + NuC lift + top-k + in-place compaction of K and V; per-head novelty (if given) follows in its own kernel.
 // Krot != nullptr: CR-RoPE of the kept keys on the side (rope_cos / rope_sin: [>= k, d/2] fp32).
-void launch_select_compact(const Dims& D, const float* u, const uint8_t* mask, float* scores, int32_t* keep_idx, void* K,
-                           void* V, float* novelty, const float* rope_cos, const float* rope_sin, void* Krot,
+void launch_select_compact(const Dims& D, const float* u, float* novelty, bool carry_novelty, float* scores,
+                           int32_t* keep_idx, void* K, void* V, const float* rope_cos, const float* rope_sin, void* Krot,
                            hipStream_t s) {
   const int rowb = D.d * (D.dtype == 0 ? 4 : 2);
   const dim3 grid(D.units_run), block(kCpThreads);
 #define CCD_LAUNCH(KPT, RB, ROPE, BF)                                                                                  \
-  hipLaunchKernelGGL((select_compact_kernel<KPT, RB, ROPE, BF>), grid, block, 0, s, D, u, mask, scores, keep_idx, (char*)K, \
-                     (char*)V, rope_cos, rope_sin, (char*)Krot)
+  hipLaunchKernelGGL((select_compact_kernel<KPT, RB, ROPE, BF>), grid, block, 0, s, D, u, novelty, carry_novelty ? 1 : 0, \
+                     scores, keep_idx, (char*)K, (char*)V, rope_cos, rope_sin, (char*)Krot)
 #define CCD_LAUNCH_RB(KPT, ROPE)                                         \
   if (rowb == 128) CCD_LAUNCH(KPT, 128, ROPE, true);                      \
   else if (rowb == 256 && D.dtype == 1) CCD_LAUNCH(KPT, 256, ROPE, true);  \
@@ -215,8 +229,6 @@ void launch_select_compact(const Dims& D, const float* u, const uint8_t* mask, f
   }
 #undef CCD_LAUNCH_RB
 #undef CCD_LAUNCH
-  if (novelty != nullptr)
-    hipLaunchKernelGGL(compact_novelty_kernel, dim3(D.units_run), block, 0, s, D, keep_idx, novelty);
 }
 
 void launch_rope_rows(const Dims& D, const void* K, const float* rope_cos, const float* rope_sin, int count, void* Krot,

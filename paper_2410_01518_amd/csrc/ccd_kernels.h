@@ -47,9 +47,7 @@ void launch_prob_valu(const Dims& D, const ScorePlan& pl, const void* Q, const v
 
 // the same two passes on the matrix cores (bf16 only)
 int mfma_max_slice();   // longest token slice a workgroup of the matrix-core passes can take
-bool stats_hosts_nuc(const Dims& D, const ScorePlan& pl);   // may pass 1 also write the NuC mask?
-void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part,
-                       const float* novelty, uint8_t* nuc_mask, hipStream_t s);
+void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s);
 // (pass 2 merges the per-slice statistics itself: no merge launch on this path)
 // K_cap (nullable; [units, P, d], contiguous): the CaP tokens' own keys join the softmax (Eq. 2 read as the model's
 // causal attention row: query row g * P + i also sees the CaP keys 0 .. i); their statistics are computed in the
@@ -70,16 +68,16 @@ void launch_head_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, co
 void launch_cap_block_stats_valu(const Dims& D, const ScorePlan& pl, const void* Q, const void* K_cap, float2* part,
                                  hipStream_t s);
 
-// NuC slots: mask[row][t] = 1 for the T tokens of largest novelty (row = sequence when novelty is shared, else unit)
-void launch_nuc_mask(const Dims& D, const float* novelty, uint8_t* mask, hipStream_t s);
-// pooling + NuC lift -> scores (when `u` != null), top-k -> keep_idx (when `keep_idx` != null)
-void launch_finalize_select(const Dims& D, const float* u, const uint8_t* mask, float* scores,
+// NuC slots of the unit's novelty row + pooling + NuC lift -> scores (when `u` != null; novelty may be null when
+// D.T == 0), top-k -> keep_idx (when `keep_idx` != null)
+void launch_finalize_select(const Dims& D, const float* u, const float* novelty, float* scores,
                             int32_t* keep_idx, hipStream_t s);
 
 // selection and compaction of a unit in one workgroup (rows short enough to be staged in LDS)
 bool select_compact_supported(const Dims& D);
-void launch_select_compact(const Dims& D, const float* u, const uint8_t* mask, float* scores, int32_t* keep_idx, void* K,
-                           void* V, float* novelty, const float* rope_cos, const float* rope_sin, void* Krot,
+// (carry_novelty: the novelty is carried per head and its kept entries are compacted in place like the rows)
+void launch_select_compact(const Dims& D, const float* u, float* novelty, bool carry_novelty, float* scores,
+                           int32_t* keep_idx, void* K, void* V, const float* rope_cos, const float* rope_sin, void* Krot,
                            hipStream_t s);
 // CR-RoPE of the first `count` rows of every unit (Sec. 3.5): Krot[j] = rotary embedding at position j of K[j]
 void launch_rope_rows(const Dims& D, const void* K, const float* rope_cos, const float* rope_sin, int count, void* Krot,

@@ -21,56 +21,18 @@
 // s+1 are issued between the ALU instructions that consume tile s): it hides the LDS reads and the little ALU work
 // that does fit under an MFMA.
 #include "ccd_score_mfma.h"
-#include "ccd_topk.h"
 
 namespace ccd {
 
 namespace {
 
-// NuC slots (Sec. 3.3.3 step 1) by rank counting, spread over the workgroups of pass 1: token t of a novelty row
-// is among the T most novel iff fewer than T tokens beat it (larger value, or equal value and lower index).  One wave
-// counts the rivals of one token, 64 at a time.  O(n^2) comparisons per row, but they are shared by every wave of
-// the launch, where a selection kernel of its own is a latency-bound chain of scans run by one workgroup per row.
-// Not inlined on purpose: inside the score kernel its registers and scalar state disturbed the allocation of the
-// main loop (scalar spills in every step, about 8 us per launch); as a function of its own it costs a call.
-constexpr int kRankLoads = 32;
-__device__ __attribute__((noinline)) void nuc_rank_share(const float* __restrict__ novelty, uint8_t* __restrict__ mask,
-                                                         int B, int n, int64_t nov_sb, int T, int blk, int n_blocks) {
-  const int lane = threadIdx.x & 63;
-  const int64_t total = (int64_t)B * n, stride = 4 * (int64_t)n_blocks;
-  for (int64_t gt = 4 * (int64_t)blk + (threadIdx.x >> 6); gt < total; gt += stride) {
-    const int b = (int)(gt / n), t = (int)(gt % n);
-    const float* row = novelty + (int64_t)b * nov_sb;
-    const float vt = row[t] + 0.0f;               // -0 counts as +0
-    const bool eligible = vt == vt && vt != -INFINITY;
-    // For an eligible t plain float compares order the rivals exactly as the keys do: NaN compares false, -inf is
-    // below every eligible value, and rivals past the end are given -inf.
-    uint32_t cnt = 0;
-    for (int base = 0; base < n; base += 64 * kRankLoads) {      // trip count uniform over the wave
-      const int j0 = base + lane;
-      float v[kRankLoads];                      // all loads of a round are in flight together
-#pragma unroll
-      for (int i = 0; i < kRankLoads; ++i) v[i] = j0 + 64 * i < n ? row[j0 + 64 * i] : -INFINITY;
-#pragma unroll
-      for (int i = 0; i < kRankLoads; ++i) {
-        const bool beats = v[i] > vt || (v[i] == vt && j0 + 64 * i < t);
-        cnt += __popcll(__ballot(beats));        // wave-wide count on the scalar unit
-      }
-    }
-    if (lane == 0) mask[gt] = (eligible && cnt < (uint32_t)max(T, 0)) ? 1 : 0;
-  }
-}
-
 template <int HD, int PASS>
 __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl, const uint16_t* __restrict__ Q,
                                                             const uint16_t* __restrict__ K, float2* __restrict__ part,
-                                                            float* __restrict__ u, const float* __restrict__ novelty,
-                                                            uint8_t* __restrict__ nuc_mask,
+                                                            float* __restrict__ u,
                                                             const uint16_t* __restrict__ Kcap,
                                                             float* __restrict__ lse_out) {
   __shared__ ScoreLds<HD, PASS> sm;
-  if (PASS == 1 && novelty != nullptr)
-    nuc_rank_share(novelty, nuc_mask, D.B, D.n, D.nov_sb, D.T, blockIdx.x, gridDim.x);
   int unit, slice;
   if (!decode_block(D, blockIdx.x, PASS == 1 ? pl.n_slices1 : pl.n_slices2, unit, slice)) return;
   // pass 2 walks the units backwards: the keys pass 1 read last are the ones most likely still held by the
@@ -144,33 +106,20 @@ __global__ __launch_bounds__(kMT) void head_prob_kernel(Dims D, const uint16_t* 
   }
 }
 
-constexpr int kRankMaxSteps = 256;   // rank-counting steps (of 64 rivals) a wave may be asked to do
-
 unsigned stats_grid(const Dims& D, const ScorePlan& pl) { return (unsigned)((D.units_run + 7) / 8 * 8) * pl.n_slices1; }
 
 }  // namespace
 
 int mfma_max_slice() { return kMaxSlice; }
 
-// true when the pass-1 launch can also mark the NuC slots: novelty shared by layers and heads (one row per
-// sequence), the full range of units, and a per-wave share of the rank counting that stays small
-bool stats_hosts_nuc(const Dims& D, const ScorePlan& pl) {
-  if (D.nov_sl != 0 || D.nov_sh != 0 || D.unit0 != 0 || D.units_run != D.units) return false;
-  const int64_t waves = 4 * (int64_t)stats_grid(D, pl);
-  const int64_t tokens_per_wave = ((int64_t)D.B * D.n + waves - 1) / waves;
-  return tokens_per_wave * ((D.n + 63) / 64) <= kRankMaxSteps;
-}
-
-// novelty != nullptr (only if stats_hosts_nuc): the launch also writes nuc_mask[B, n]
-void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part,
-                       const float* novelty, uint8_t* nuc_mask, hipStream_t s) {
+void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s) {
   dim3 grid(stats_grid(D, pl)), block(kMT);
   if (D.d == 64)
     hipLaunchKernelGGL((score_pass_kernel<64, 1>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
-                       (float*)nullptr, novelty, nuc_mask, (const uint16_t*)nullptr, (float*)nullptr);
+                       (float*)nullptr, (const uint16_t*)nullptr, (float*)nullptr);
   else
     hipLaunchKernelGGL((score_pass_kernel<128, 1>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
-                       (float*)nullptr, novelty, nuc_mask, (const uint16_t*)nullptr, (float*)nullptr);
+                       (float*)nullptr, (const uint16_t*)nullptr, (float*)nullptr);
 }
 
 void launch_head_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s) {
@@ -197,10 +146,10 @@ void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const v
   dim3 grid((unsigned)((D.units_run + 7) / 8 * 8) * pl.n_slices2), block(kMT);
   if (D.d == 64)
     hipLaunchKernelGGL((score_pass_kernel<64, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
-                       const_cast<float2*>(part), u, (const float*)nullptr, (uint8_t*)nullptr, (const uint16_t*)K_cap, lse_out);
+                       const_cast<float2*>(part), u, (const uint16_t*)K_cap, lse_out);
   else
     hipLaunchKernelGGL((score_pass_kernel<128, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
-                       const_cast<float2*>(part), u, (const float*)nullptr, (uint8_t*)nullptr, (const uint16_t*)K_cap, lse_out);
+                       const_cast<float2*>(part), u, (const uint16_t*)K_cap, lse_out);
 }
 
 }  // namespace ccd

@@ -1,4 +1,4 @@
-// Per-unit selection kernels: NuC slots (Sec. 3.3.3 step 1), pooling + NuC lift, and the final top-k
+// Per-unit selection kernel: NuC slots (Sec. 3.3.3 step 1), pooling + NuC lift, and the final top-k
 // (Sec. 3.3.3 step 2 / App. B "Final Token Selection").  The selection machinery is in ccd_topk.h.
 //
 // finalize_select_kernel: one workgroup of 1024 threads per unit; every thread keeps the scores of its tokens in
@@ -14,24 +14,14 @@ namespace {
 constexpr int kSelThreads = 1024;
 constexpr int kStageMaxKpt = 16;   // rows of up to 16384 tokens (64 KiB) are staged in LDS for pooling
 
-// one workgroup per novelty row: per sequence when novelty is shared by layers and heads, else per unit
-template <int KPT>
-__global__ __launch_bounds__(kSelThreads) void nuc_mask_kernel(Dims D, const float* __restrict__ novelty,
-                                                               uint8_t* __restrict__ mask) {
-  __shared__ TopkShared<kSelThreads> sh;
-  const bool shared_nov = D.nov_sl == 0 && D.nov_sh == 0;
-  const float* nov = novelty + (shared_nov ? (int64_t)blockIdx.x * D.nov_sb : nov_offset(D, decode_unit(D, blockIdx.x)));
-  nuc_mask_job<kSelThreads, KPT>(nov, mask + (int64_t)blockIdx.x * D.n, D.n, D.T, sh);
-}
-
 template <int KPT>
 __global__ __launch_bounds__(kSelThreads) void finalize_select_kernel(Dims D, const float* __restrict__ u,
-                                                                      const uint8_t* __restrict__ mask, float* scores,
+                                                                      const float* __restrict__ novelty, float* scores,
                                                                       int32_t* __restrict__ keep_idx) {
   __shared__ TopkShared<kSelThreads> sh;
   constexpr bool kStaged = KPT <= kStageMaxKpt;
   __shared__ __attribute__((aligned(16))) float u_stage[kStaged ? KPT * kSelThreads + 2 * kStagePad : 4];
-  finalize_select_body<kSelThreads, KPT, kStaged>(D, D.unit0 + blockIdx.x, u, mask, scores, keep_idx, sh,
+  finalize_select_body<kSelThreads, KPT, kStaged>(D, D.unit0 + blockIdx.x, u, novelty, scores, keep_idx, sh,
                                                   kStaged ? u_stage : nullptr);
 }
 
@@ -39,23 +29,11 @@ __global__ __launch_bounds__(kSelThreads) void finalize_select_kernel(Dims D, co
 
 int select_max_tokens() { return 64 * kSelThreads; }
 
-void launch_nuc_mask(const Dims& D, const float* novelty, uint8_t* mask, hipStream_t s) {
-  const bool shared_nov = D.nov_sl == 0 && D.nov_sh == 0;
-  const dim3 grid(shared_nov ? D.B : D.units), block(kSelThreads);
-  const int kpt = (D.n + kSelThreads - 1) / kSelThreads;
-#define CCD_LAUNCH(KPT) hipLaunchKernelGGL((nuc_mask_kernel<KPT>), grid, block, 0, s, D, novelty, mask)
-  if (kpt <= 4) CCD_LAUNCH(4);
-  else if (kpt <= 16) CCD_LAUNCH(16);
-  else if (kpt <= 32) CCD_LAUNCH(32);
-  else CCD_LAUNCH(64);
-#undef CCD_LAUNCH
-}
-
-void launch_finalize_select(const Dims& D, const float* u, const uint8_t* mask, float* scores, int32_t* keep_idx,
+void launch_finalize_select(const Dims& D, const float* u, const float* novelty, float* scores, int32_t* keep_idx,
                             hipStream_t s) {
   const dim3 grid(D.units_run), block(kSelThreads);
   const int kpt = (D.n + kSelThreads - 1) / kSelThreads;
-#define CCD_LAUNCH(KPT) hipLaunchKernelGGL((finalize_select_kernel<KPT>), grid, block, 0, s, D, u, mask, scores, keep_idx)
+#define CCD_LAUNCH(KPT) hipLaunchKernelGGL((finalize_select_kernel<KPT>), grid, block, 0, s, D, u, novelty, scores, keep_idx)
   if (kpt <= 4) CCD_LAUNCH(4);
   else if (kpt <= 16) CCD_LAUNCH(16);
   else if (kpt <= 32) CCD_LAUNCH(32);

@@ -56,7 +56,53 @@ __device__ __forceinline__ void pooled_block(float (&out)[KPT], const float* sta
   }
 }
 
-// u != nullptr: score <- NuC lift (mask) of pooled u, written to `scores` if that is not null.
+// NuC slots (Sec. 3.3.3 step 1): bit j of the result = the thread's j-th token is among the T tokens of largest
+// novelty of the row `nov` (n values).  NaN and -inf never qualify, so fewer than T may be marked; ties go to the lower index.  The
+// novelty keys stay in registers; the row is read once.  Every thread of the workgroup must call this.
+template <int THREADS, int KPT, bool BLOCKED>
+__device__ __forceinline__ uint64_t nuc_slots_of_row(const float* __restrict__ nov, int n, int T,
+                                                     TopkShared<THREADS>& sh, int& phase) {
+  static_assert(KPT <= 64, "one bit per owned token");
+  const int tid = threadIdx.x;
+  uint64_t nuc = 0;
+  uint32_t key[KPT];
+#pragma unroll
+  for (int j = 0; j < KPT; ++j) {
+    const int t = owned_token<THREADS, KPT, BLOCKED>(tid, j);
+    key[j] = t < n ? novelty_key(nov[t]) : 0u;
+  }
+  uint32_t tau, need;
+  radix_threshold<THREADS, KPT, BLOCKED, true>([&](int j, int) { return key[j]; }, n, (uint32_t)max(T, 0), sh, phase, tau, need);
+  if (BLOCKED) {
+    uint32_t n_eq = 0;
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) n_eq += (tid * KPT + j < n && key[j] == tau) ? 1u : 0u;
+    uint32_t tot;
+    uint32_t eq_rank = block_exclusive_scan<THREADS>(n_eq, sh, phase, tot);
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+      const bool valid = tid * KPT + j < n, eq = valid && key[j] == tau;
+      nuc |= (uint64_t)(valid && (key[j] > tau || (eq && eq_rank < need))) << j;
+      eq_rank += eq ? 1u : 0u;
+    }
+  } else {
+    uint32_t eq_base = 0;
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+      if (j * THREADS >= n) continue;      // uniform: whole rounds beyond n are skipped
+      const int t = tid + j * THREADS;
+      const bool eq = t < n && key[j] == tau;
+      uint32_t tot;
+      const uint32_t rank = block_rank<THREADS>(eq, sh, phase, tot);
+      nuc |= (uint64_t)(t < n && (key[j] > tau || (eq && eq_base + rank < need))) << j;
+      eq_base += tot;
+    }
+  }
+  return nuc;
+}
+
+// u != nullptr: score <- pooled u with +inf at the NuC slots of the unit's novelty row (novelty may be null when
+// D.T == 0), written to `scores` if that is not null.
 // u == nullptr: score <- scores (must not be null).      keep_idx != nullptr: keep_idx <- top-k of score.
 // Executed by a whole workgroup of THREADS threads, each owning at most KPT tokens (n <= THREADS * KPT).
 // u_stage (LDS, THREADS * KPT + 2 * kStagePad floats, 16-byte aligned, or null): the unit's row of u is copied there
@@ -65,7 +111,7 @@ __device__ __forceinline__ void pooled_block(float (&out)[KPT], const float* sta
 // may alias u_stage.  Ends without a barrier.
 template <int THREADS, int KPT, bool BLOCKED>
 __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, const float* __restrict__ u,
-                                                     const uint8_t* __restrict__ mask, float* scores,
+                                                     const float* __restrict__ novelty, float* scores,
                                                      int32_t* __restrict__ keep_idx, TopkShared<THREADS>& sh,
                                                      float* u_stage, int32_t* keep_lds = nullptr) {
   const int tid = threadIdx.x, n = D.n;
@@ -74,24 +120,22 @@ __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, co
   if (u != nullptr) {
     const float* uu = u + (int64_t)unit * n;
     const bool pooling = D.pool_mode != 0 && D.pool_w > 1;
-    // the NuC marks of the thread's tokens are requested first: their latency passes behind the staging of the row
-    const bool shared_nov = D.nov_sl == 0 && D.nov_sh == 0;
-    const uint8_t* mrow = mask + (int64_t)(shared_nov ? decode_unit(D, unit).b : unit) * n;
-    bool nuc[KPT];
-#pragma unroll
-    for (int j = 0; j < KPT; ++j) {
-      const int t = owned_token<THREADS, KPT, BLOCKED>(tid, j);
-      nuc[j] = D.T > 0 && t < n && mrow[t] != 0;
-    }
-    if (u_stage != nullptr && pooling) {
+    const bool stage = u_stage != nullptr && pooling;
+    if (stage) {
 #pragma unroll
       for (int j = 0; j < KPT; ++j) {
         const int t = tid + j * THREADS;            // striped copy: coalesced
         if (t < n) u_stage[t + kStagePad] = uu[t];
       }
-      __syncthreads();
-      uu = u_stage + kStagePad;
     }
+    // the NuC slots of the row: the workgroup barriers inside also make the staged row visible
+    uint64_t nuc = 0;
+    if (D.T > 0) {
+      nuc = nuc_slots_of_row<THREADS, KPT, BLOCKED>(novelty + nov_offset(D, decode_unit(D, unit)), n, D.T, sh, phase);
+    } else if (stage) {
+      __syncthreads();
+    }
+    if (stage) uu = u_stage + kStagePad;
     if (BLOCKED && pooling && D.pool_w <= 2 * kStagePad + 1) {
       pooled_block<KPT>(sc, u_stage, tid * KPT, n, D.pool_w, D.pool_mode);
     } else {
@@ -108,7 +152,7 @@ __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, co
       sc[j] = -INFINITY;
       if (t < n) {
         if (fabsf(v) < FLT_MIN) v = 0.f;
-        sc[j] = nuc[j] ? INFINITY : v;
+        sc[j] = ((nuc >> j) & 1u) ? INFINITY : v;
         if (scores != nullptr) scores[(int64_t)unit * n + t] = sc[j];
       }
     }
@@ -126,7 +170,7 @@ __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, co
 #pragma unroll
     for (int j = 0; j < KPT; ++j) key[j] = score_key(sc[j]);
     uint32_t tau, need;
-    radix_threshold<THREADS, KPT, BLOCKED>([&](int j, int) { return key[j]; }, n, (uint32_t)D.k, sh, phase, tau, need);
+    radix_threshold<THREADS, KPT, BLOCKED, false>([&](int j, int) { return key[j]; }, n, (uint32_t)D.k, sh, phase, tau, need);
     if (BLOCKED) {
       // token order is thread order, then j.  A token's place among the kept ones is the number of larger keys
       // before it plus the number of threshold ties before it, capped at `need`: one scan over the two per-thread

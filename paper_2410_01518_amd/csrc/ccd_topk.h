@@ -81,6 +81,8 @@ __device__ __forceinline__ uint32_t block_rank(bool pred, TopkShared<THREADS>& s
 // (n <= THREADS * KPT): tid + j*THREADS, or tid*KPT + j when BLOCKED; key_of(j, t) returns the key of the thread's
 // j-th token t, which the caller holds in registers.
 // On return #{key > tau} < kk <= #{key >= tau} and need = kk - #{key > tau}.  Ends with a barrier.
+// ABOVE_LOW_ONLY: keys at or below the key of -inf never qualify (novelty: NaN and -inf map to key 0): kk is first
+// cut down to the number of other keys, and if none is left nothing is selected (tau = 0xFFFFFFFF, need = 0).
 //
 // Scores of one row share a few exponents, and a quarter or half of them are the +inf of the NuC slots: the top
 // 11 bits of such keys fall into a handful of histogram bins, and a wave's 64 LDS atomics on one address serialise
@@ -89,7 +91,7 @@ __device__ __forceinline__ uint32_t block_rank(bool pred, TopkShared<THREADS>& s
 // the ordinary ones, minimum and maximum from one workgroup reduction.  The class that holds the kk-th largest is
 // known from the counts; inside it the digits are taken from key - lo over the range hi - lo actually spanned, most
 // significant first, 11 bits at a time (fewer passes when the range is narrow, none when it is a single value).
-template <int THREADS, int KPT, bool BLOCKED = false, class KeyFn>
+template <int THREADS, int KPT, bool BLOCKED = false, bool ABOVE_LOW_ONLY = false, class KeyFn>
 __device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk, TopkShared<THREADS>& sh, int& phase, uint32_t& tau,
                                 uint32_t& need) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -138,6 +140,15 @@ __device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk
     mx = max(mx, sh.red[3][w]);
   }
 
+  if (ABOVE_LOW_ONLY) {
+    kk = min(kk, n_hi + n_mid);
+    if (kk == 0) {                               // uniform
+      __syncthreads();
+      tau = 0xFFFFFFFFu;
+      need = 0;
+      return;
+    }
+  }
   // the class of the kk-th largest key: candidates are the keys in [lo, hi]; `remaining` of them are wanted
   uint32_t lo, hi, remaining;
   if (kk <= n_hi) {
@@ -193,38 +204,6 @@ __device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk
   }
   tau = lo + prefix;
   need = remaining;
-}
-
-// The T tokens of largest novelty (Sec. 3.3.3 step 1): mask[t] = 1 for them, 0 otherwise, t < n.  NaN and -inf
-// never qualify; ties go to the lower index.  Every thread of the workgroup must call this.  Thread tid owns tokens
-// tid + j*THREADS, j < KPT (n <= THREADS * KPT), and keeps their keys in registers: novelty is read once.
-template <int THREADS, int KPT>
-__device__ __forceinline__ void nuc_mask_job(const float* __restrict__ nov, uint8_t* __restrict__ mask, int n, int T, TopkShared<THREADS>& sh) {
-  const int tid = threadIdx.x;
-  int phase = 0;
-  uint32_t key[KPT], mine = 0;
-#pragma unroll
-  for (int j = 0; j < KPT; ++j) {
-    const int t = tid + j * THREADS;
-    key[j] = t < n ? novelty_key(nov[t]) : 0u;
-    mine += key[j] != 0u;
-  }
-  uint32_t eligible;
-  block_exclusive_scan<THREADS>(mine, sh, phase, eligible);
-  const uint32_t T_eff = min((uint32_t)max(T, 0), eligible);
-  uint32_t tau = 0xFFFFFFFFu, need = 0;
-  if (T_eff > 0) radix_threshold<THREADS, KPT>([&](int j, int) { return key[j]; }, n, T_eff, sh, phase, tau, need);
-  uint32_t eq_base = 0;
-#pragma unroll
-  for (int j = 0; j < KPT; ++j) {
-    if (j * THREADS >= n) continue;      // uniform: whole rounds beyond n are skipped
-    const int t = tid + j * THREADS;
-    const bool eq = T_eff > 0 && t < n && key[j] == tau;
-    uint32_t tot;
-    const uint32_t rank = block_rank<THREADS>(eq, sh, phase, tot);
-    if (t < n) mask[t] = (T_eff > 0 && (key[j] > tau || (eq && eq_base + rank < need))) ? 1 : 0;
-    eq_base += tot;
-  }
 }
 
 }  // namespace ccd

@@ -136,7 +136,7 @@ ScorePlan plan_score(const Dims& D) {
 }
 
 struct Workspace {
-  size_t off_part, off_lse, off_u, off_mask, total;
+  size_t off_part, off_lse, off_u, total;
 };
 
 // The layout does not depend on the kernel path, so a workspace sized once serves either.
@@ -147,7 +147,6 @@ static Workspace layout_workspace(const Dims& D) {
   w.off_part = off;   off = align_up(off + (size_t)D.units * max_slices * D.GP * sizeof(float2), 256);
   w.off_lse = off;    off = align_up(off + (size_t)D.units * D.GP * sizeof(float), 256);
   w.off_u = off;      off = align_up(off + (size_t)D.units * D.n * sizeof(float), 256);
-  w.off_mask = off;   off = align_up(off + (size_t)D.units * D.n, 256);
   w.total = off;
   return w;
 }
@@ -159,9 +158,9 @@ static int check_workspace(const Workspace& w, const void* ws, size_t ws_bytes) 
 }
 
 // ---- optional per-kernel timing of ccd_compress -------------------------------------------------------
-enum Stage { kStNuc = 0, kStStats, kStMerge, kStProb, kStSelect, kStCompact, kStSelCompact, kStCapBlock, kStHead, kNumStages };
-static const char* const kStageNames[kNumStages] = {"nuc_mask", "score_stats",    "score_merge", "score_prob",   "select",
-                                                    "compact",  "select_compact", "cap_block",   "window_head"};
+enum Stage { kStStats = 0, kStMerge, kStProb, kStSelect, kStCompact, kStSelCompact, kStCapBlock, kStHead, kNumStages };
+static const char* const kStageNames[kNumStages] = {"score_stats", "score_merge",    "score_prob", "select",
+                                                    "compact",     "select_compact", "cap_block",  "window_head"};
 
 // Every profiled launch is bracketed by two events on the stream it runs on.
 struct Profiler {
@@ -194,21 +193,14 @@ static Profiler g_prof;
 
 static int launch_status() { return hipGetLastError() == hipSuccess ? CCD_OK : CCD_ELAUNCH; }
 
-// NuC mask (step a1, when T > 0) and raw CaP score u[unit, t] (steps a2-a3).  On the matrix-core path the first
-// score pass marks the NuC slots on the side when it can; otherwise they take a kernel of their own.  With K_cap the
-// CaP tokens' own keys join the softmax (causally): their statistics become one more entry per unit of `part`.
-static void run_mask_and_cap_scores(const Dims& D, ScorePlan pl, const Workspace& w, const void* Q, const void* K,
-                                    const void* K_cap, const float* novelty, char* ws, hipStream_t st) {
+// Raw CaP score u[unit, t] (steps a2-a3).  With K_cap the CaP tokens' own keys join the softmax (causally): their
+// statistics become one more entry per unit of `part` on the vector-ALU path (the matrix-core pass 2 computes them
+// itself).  (The NuC slots, step a1, are found by the selection kernels from the novelty row.)
+static void run_cap_scores(const Dims& D, ScorePlan pl, const Workspace& w, const void* Q, const void* K,
+                           const void* K_cap, char* ws, hipStream_t st) {
   float2* part = reinterpret_cast<float2*>(ws + w.off_part);
   float* lse2 = reinterpret_cast<float*>(ws + w.off_lse);
   float* u = reinterpret_cast<float*>(ws + w.off_u);
-  uint8_t* mask = reinterpret_cast<uint8_t*>(ws + w.off_mask);
-  const bool nuc_in_stats = D.T > 0 && pl.use_mfma && stats_hosts_nuc(D, pl);
-  if (D.T > 0 && !nuc_in_stats) {
-    g_prof.begin(kStNuc, st);
-    launch_nuc_mask(D, novelty, mask, st);
-    g_prof.end(st);
-  }
   if (K_cap != nullptr && !pl.use_mfma) {    // (the matrix-core pass 2 takes the CaP keys in its prologue)
     pl.cap_block = 1;
     g_prof.begin(kStCapBlock, st);
@@ -223,7 +215,7 @@ static void run_mask_and_cap_scores(const Dims& D, ScorePlan pl, const Workspace
       g_prof.end(st);
     }
     g_prof.begin(kStStats, st);
-    launch_stats_mfma(D, pl, Q, K, part, nuc_in_stats ? novelty : nullptr, mask, st);
+    launch_stats_mfma(D, pl, Q, K, part, st);
     g_prof.end(st);
     g_prof.begin(kStProb, st);
     launch_prob_mfma(D, pl, Q, K, K_cap, part, u, lse2, st);
@@ -273,9 +265,8 @@ static int score_impl(const ccd_shape_t* shape, const void* Q_cat, const void* K
   if (rc != CCD_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  uint8_t* mask = reinterpret_cast<uint8_t*>(ws + w.off_mask);
-  run_mask_and_cap_scores(D, pl, w, Q_cat, K, K_cap, novelty, ws, st);
-  launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), mask, scores, nullptr, st);
+  run_cap_scores(D, pl, w, Q_cat, K, K_cap, ws, st);
+  launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), novelty, scores, nullptr, st);
   return launch_status();
 }
 
@@ -341,20 +332,18 @@ static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, v
   if (shape->n_valid < shape->n_cap || shape->n_valid <= shape->k) return CCD_NOOP;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  uint8_t* mask = reinterpret_cast<uint8_t*>(ws + w.off_mask);
   const float* u = reinterpret_cast<const float*>(ws + w.off_u);
   const bool per_head = shape->nov_stride_l != 0 || shape->nov_stride_h != 0;
   if (g_prof.on) ++g_prof.calls;
-  run_mask_and_cap_scores(D, pl, w, Q_cat, K_attn, K_cap, novelty, ws, st);
+  run_cap_scores(D, pl, w, Q_cat, K_attn, K_cap, ws, st);
   if (select_compact_supported(D)) {
     g_prof.begin(kStSelCompact, st);
-    launch_select_compact(D, u, mask, scores_opt, keep_idx, K, V, per_head ? novelty : nullptr, rope_cos, rope_sin, K_rot,
-                          st);
+    launch_select_compact(D, u, novelty, per_head, scores_opt, keep_idx, K, V, rope_cos, rope_sin, K_rot, st);
     g_prof.end(st);
     return launch_status();
   }
   g_prof.begin(kStSelect, st);
-  launch_finalize_select(D, u, mask, scores_opt, keep_idx, st);
+  launch_finalize_select(D, u, novelty, scores_opt, keep_idx, st);
   g_prof.end(st);
   g_prof.begin(kStCompact, st);
   launch_compact(D, K, V, keep_idx, K, V, per_head ? novelty : nullptr, st);
