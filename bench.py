@@ -25,8 +25,9 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 VALU_FP32_PEAK_TFLOPS = 157.3
 # HBM bytes per launch on the headline config from the committed rocprofv3 counter runs
-# (profiles/ccd_compress_c3_hbm_traffic.md: read requests x 128 B + WRITE_SIZE; a plain copy reads factor 1.00)
-MEASURED_TRAFFIC_C3 = {"score_stats": 287_600_000, "score_prob": 290_600_000, "select_compact": 543_100_000}
+# (profiles/ccd_compress_c3_hbm_traffic.md: FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the factors a plain copy of known
+# size gives; equal to read requests x 128 B + write requests x 64 B)
+MEASURED_TRAFFIC_C3 = {"score_stats": 286_600_000, "score_prob": 290_700_000, "select_compact": 543_300_000}
 
 
 def algorithmic_bytes(cfg) -> dict:
@@ -36,7 +37,6 @@ def algorithmic_bytes(cfg) -> dict:
     kbytes, qbytes = u * N * d * e, u * GP * d * e
     rows = u * k * d * e
     return {
-        "nuc_mask": cfg.B * N * 5,
         "score_stats": kbytes + qbytes,
         "score_merge": 0,
         "score_prob": kbytes + qbytes + u * N * 4,
