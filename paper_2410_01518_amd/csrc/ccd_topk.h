@@ -11,6 +11,7 @@
 namespace ccd {
 
 constexpr int kRadixBins = 2048;
+constexpr int kCandMax = 256;   // at most this many keys left in the chosen bin: they are ranked directly
 
 // fp32 -> uint32 with the same order; NaN ranks with -inf and -0 equals +0
 __device__ __forceinline__ uint32_t score_key(float x) {
@@ -31,6 +32,8 @@ struct TopkShared {
   uint32_t wave_sum[2][THREADS / 64];   // ping-pong: one barrier per scan
   uint32_t red[4][THREADS / 64];        // per-wave class counts and key range of radix_threshold
   uint32_t digit, remaining;
+  uint32_t bin_count, cand_n;           // keys in the chosen bin; candidates gathered so far
+  uint32_t cand_key[kCandMax];          // the keys that share all digits fixed so far, once they are few
 };
 
 // Exclusive prefix sum of v over the workgroup in thread order; `total` receives the workgroup's sum.
@@ -97,6 +100,7 @@ __device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int kBinsPerThread = kRadixBins / THREADS;
   constexpr int kWaves = THREADS / 64;
+  static_assert(THREADS >= kCandMax, "one thread ranks one candidate");
   constexpr uint32_t kHiFrom = 0xFF800000u;   // score_key(+inf)
   constexpr uint32_t kLoUpTo = 0x007FFFFFu;   // score_key(-inf)
 
@@ -194,6 +198,8 @@ __device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk
       if (excl < remaining && remaining <= incl) {
         sh.digit = kRadixBins - 1 - (tid * kBinsPerThread + i);
         sh.remaining = remaining - excl;
+        sh.bin_count = h[i];
+        sh.cand_n = 0;
       }
       excl = incl;
     }
@@ -201,6 +207,39 @@ __device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk
     prefix = (prefix << width) | sh.digit;
     remaining = sh.remaining;
     rem_bits = shift;
+    const uint32_t n_cand = sh.bin_count;
+    if (rem_bits > 0 && n_cand <= (uint32_t)kCandMax) {      // uniform over the workgroup
+      // Few keys share the digits fixed so far (the digits are spread over the range, so this is the rule after one
+      // pass): gather them and rank them against each other instead of two more histogram passes.
+#pragma unroll
+      for (int j = 0; j < KPT; ++j) {
+        const int t = BLOCKED ? tid * KPT + j : tid + j * THREADS;
+        if (t < n) {
+          const uint32_t key = key_of(j, t);
+          const uint32_t rel = key - lo;
+          if (key >= lo && key <= hi && (uint32_t)((uint64_t)rel >> rem_bits) == prefix)
+            sh.cand_key[atomicAdd(&sh.cand_n, 1u)] = key;
+        }
+      }
+      __syncthreads();
+      if ((uint32_t)tid < n_cand) {
+        const uint32_t mine = sh.cand_key[tid];
+        uint32_t gt = 0, ge = 0;
+        for (uint32_t i = 0; i < n_cand; ++i) {
+          const uint32_t other = sh.cand_key[i];
+          gt += other > mine ? 1u : 0u;
+          ge += other >= mine ? 1u : 0u;
+        }
+        if (gt < remaining && remaining <= ge) {             // the threshold key (equal keys write the same values)
+          sh.digit = mine;
+          sh.remaining = remaining - gt;
+        }
+      }
+      __syncthreads();
+      tau = sh.digit;
+      need = sh.remaining;
+      return;
+    }
   }
   tau = lo + prefix;
   need = remaining;
