@@ -26,6 +26,25 @@ __device__ __forceinline__ uint32_t novelty_key(float x) {
   return score_key(x);
 }
 
+// Wave-wide inclusive scan in six data-parallel-primitive steps (shifts inside rows of 16 lanes, then the last lane of
+// a row broadcast into the following rows): one ALU instruction per step where a cross-lane shuffle takes a round trip
+// through the LDS pipeline.  `identity` fills the lanes a step has no source for.
+template <class Op>
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, uint32_t identity, Op op) {
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)v, 0x111, 0xf, 0xf, false));   // row_shr:1
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)v, 0x112, 0xf, 0xf, false));   // row_shr:2
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)v, 0x114, 0xf, 0xf, false));   // row_shr:4
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)v, 0x118, 0xf, 0xf, false));   // row_shr:8
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)v, 0x142, 0xa, 0xf, false));   // row_bcast:15
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)v, 0x143, 0xc, 0xf, false));   // row_bcast:31
+  return v;
+}
+// the operation over all 64 lanes, in every lane
+template <class Op>
+__device__ __forceinline__ uint32_t wave_reduce(uint32_t v, uint32_t identity, Op op) {
+  return (uint32_t)__builtin_amdgcn_readlane((int)wave_inclusive_scan(v, identity, op), 63);
+}
+
 template <int THREADS>
 struct TopkShared {
   uint32_t hist[kRadixBins];
@@ -40,12 +59,7 @@ struct TopkShared {
 template <int THREADS>
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, TopkShared<THREADS>& sh, int& phase, uint32_t& total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  uint32_t inc = v;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t o = __shfl_up(inc, off);
-    if (lane >= off) inc += o;
-  }
+  const uint32_t inc = wave_inclusive_scan(v, 0u, [](uint32_t a, uint32_t b) { return a + b; });
   if (lane == 63) sh.wave_sum[phase][wave] = inc;
   __syncthreads();
   uint32_t before = 0, tot = 0;
@@ -118,13 +132,10 @@ __device__ __forceinline__ void radix_threshold(KeyFn key_of, int n, uint32_t kk
       mx = mid ? max(mx, key) : mx;
     }
   }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    c_hi += __shfl_xor(c_hi, off);
-    c_mid += __shfl_xor(c_mid, off);
-    mn = min(mn, (uint32_t)__shfl_xor(mn, off));
-    mx = max(mx, (uint32_t)__shfl_xor(mx, off));
-  }
+  c_hi = wave_reduce(c_hi, 0u, [](uint32_t a, uint32_t b) { return a + b; });
+  c_mid = wave_reduce(c_mid, 0u, [](uint32_t a, uint32_t b) { return a + b; });
+  mn = wave_reduce(mn, 0xFFFFFFFFu, [](uint32_t a, uint32_t b) { return min(a, b); });
+  mx = wave_reduce(mx, 0u, [](uint32_t a, uint32_t b) { return max(a, b); });
   for (int i = tid; i < kRadixBins; i += THREADS) sh.hist[i] = 0;
   if (lane == 0) {
     sh.red[0][wave] = c_hi;
