@@ -31,7 +31,8 @@ MEASURED_TRAFFIC_C3 = {"score_stats": 286_600_000, "score_prob": 290_700_000, "s
 
 
 def algorithmic_bytes(cfg) -> dict:
-    """Bytes the method has to move per call, by stage and for the whole call ('Algorithmic bytes')."""
+    """Bytes the method has to move per call, by stage and for the whole call: K and Q_cat read once per score pass,
+    kept K and V rows read and written once, the score row, novelty and keep_idx."""
     e = 4 if cfg.dtype == "fp32" else 2
     u, N, k, d, GP = cfg.units, cfg.N, cfg.k, cfg.d, cfg.G * cfg.P
     kbytes, qbytes = u * N * d * e, u * GP * d * e
@@ -146,7 +147,8 @@ def main() -> int:
     ap.add_argument("--cpu-units", type=int, default=0, help="units the CPU oracle is timed on (0 = the whole call)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (units shard without communication; see DESIGN.md); "
+        print("bench.py: this build runs on ONE GPU (the units of a call are independent and would shard without "
+              "communication); "
               f"--gpus {args.gpus} is not supported", file=sys.stderr)
         return 2
 

@@ -82,18 +82,18 @@ typedef struct {
  * The workspace must be 256-byte aligned; its contents need not survive between calls. */
 CCD_API size_t ccd_workspace_bytes(const ccd_shape_t* shape);
 
-/* Steps a1-a5 (Eq. 2, pooling, Sec. 3.3.3 step 1): writes the final fp32 score of every token,
+/* The score step (Eq. 2, pooling, Sec. 3.3.3 step 1): writes the final fp32 score of every token,
  * scores[B, L, Hkv, n_valid] (dense).  NuC-selected tokens hold +inf; finite scores whose magnitude
  * is below FLT_MIN are written as 0.  Tokens whose novelty is NaN or -inf never take a NuC slot. */
 CCD_API int ccd_score(const ccd_shape_t* shape, const void* Q_cat, const void* K, const float* novelty,
               float* scores, void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Step a6 (Sec. 3.3.3 step 2): keep_idx[B, L, Hkv, k] int32 = the k indices of largest score per unit,
+/* The select step (Sec. 3.3.3 step 2): keep_idx[B, L, Hkv, k] int32 = the k indices of largest score per unit,
  * ascending.  Equal scores: lower index first; NaN ranks with -inf; -0 equals +0.  Only B, L, Hkv,
  * n_valid and k of the shape are read. */
 CCD_API int ccd_select(const ccd_shape_t* shape, const float* scores, int32_t* keep_idx, void* hip_stream);
 
-/* Step a7 (App. B gathers): row j of K_dst/V_dst (same layout and strides as the sources) becomes row
+/* The compact step (App. B gathers): row j of K_dst/V_dst (same layout and strides as the sources) becomes row
  * keep_idx[j] of K_src/V_src for j < k; rows >= k of the destination are left as they are.  K_dst may
  * equal K_src and V_dst may equal V_src (in place; keep_idx must be strictly ascending per unit, as
  * ccd_select produces); partially overlapping buffers are not allowed.  If `novelty_inout` is not NULL

@@ -193,9 +193,9 @@ static Profiler g_prof;
 
 static int launch_status() { return hipGetLastError() == hipSuccess ? CCD_OK : CCD_ELAUNCH; }
 
-// Raw CaP score u[unit, t] (steps a2-a3).  With K_cap the CaP tokens' own keys join the softmax (causally): their
+// Raw CaP score u[unit, t] (Eq. 2, before pooling).  With K_cap the CaP tokens' own keys join the softmax (causally): their
 // statistics become one more entry per unit of `part` on the vector-ALU path (the matrix-core pass 2 computes them
-// itself).  (The NuC slots, step a1, are found by the selection kernels from the novelty row.)
+// itself).  (The NuC slots, Sec. 3.3.3 step 1, are found by the selection kernels from the novelty row.)
 static void run_cap_scores(const Dims& D, ScorePlan pl, const Workspace& w, const void* Q, const void* K,
                            const void* K_cap, char* ws, hipStream_t st) {
   float2* part = reinterpret_cast<float2*>(ws + w.off_part);
