@@ -28,7 +28,8 @@ Steps, per unit (sequence b, layer l, KV head h), in the paper's order:
                 and, with K_cap, the model's own causal row, in which CaP token i also
                 attends to the CaP keys 0 .. i (Eq. 2 places the CaP tokens at the end of
                 the same sequence).  A sliding attention window (window > 0) hides the oldest
-                cached tokens from the later CaP tokens.
+                cached tokens from the later CaP tokens.  cap_scores_given_lse is the same sum
+                with each query's normaliser (log-sum-exp of its row) handed in by the caller.
   pool          1-D pooling of the score along the token axis (not in the
                 paper; the paper's implementation follows a code base that
                 clusters scores this way, and the benchmark configs ask for a
@@ -138,6 +139,24 @@ def cap_scores(Q: np.ndarray, K: np.ndarray, scale: float, K_cap: np.ndarray | N
     E, Ec = np.exp(S - m), np.exp(C - m)
     Z = E.sum(axis=1, keepdims=True) + Ec.sum(axis=1, keepdims=True)
     return (E / Z).sum(axis=0)                 # context columns only
+
+
+def cap_scores_given_lse(Q: np.ndarray, K: np.ndarray, scale: float, lse: np.ndarray, P: int | None = None,
+                         window: int = 0) -> np.ndarray:
+    """Eq. 2 with the normalisers handed in: u_t = sum over CaP queries of exp(scale * <q, k_t> - lse_q).
+
+    lse [G*P] is the natural-log-sum-exp of each CaP query's attention row, over whatever keys the model let it
+    attend to (attention kernels return it next to their output); the probabilities on the cached tokens follow from
+    it without a pass over the row.  window > 0 hides cached tokens as in cap_scores (their probability is 0).
+    """
+    n = K.shape[0]
+    S = scale * (Q @ K.T)
+    A = np.exp(S - np.asarray(lse, dtype=np.float64)[:, None])
+    if window and window > 0:
+        assert P is not None and window >= P
+        i = np.arange(Q.shape[0]) % P
+        A = np.where(np.arange(n)[None, :] >= (n + i + 1 - window)[:, None], A, 0.0)
+    return A.sum(axis=0)
 
 
 def pool(u: np.ndarray, w: int, mode: int) -> np.ndarray:
@@ -250,9 +269,13 @@ def cr_rope(K_kept: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
     return y.astype(np.float32)
 
 
-def score_unit(Q, K, novelty, *, T, scale, pool_w, pool_mode, K_cap=None, P=None, window=0):
-    """Final fp32 scores of one unit. Q [G*P, d], K [n, d], K_cap [P, d] or None: raw inputs; novelty [n] fp32."""
-    u = cap_scores(to_f64(Q), to_f64(K), scale, None if K_cap is None else to_f64(K_cap), P=P, window=window)
+def score_unit(Q, K, novelty, *, T, scale, pool_w, pool_mode, K_cap=None, P=None, window=0, lse=None):
+    """Final fp32 scores of one unit. Q [G*P, d], K [n, d], K_cap [P, d] or None: raw inputs; novelty [n] fp32;
+    lse [G*P] fp32 or None: the rows' log-sum-exps handed in (then K_cap is not used)."""
+    if lse is not None:
+        u = cap_scores_given_lse(to_f64(Q), to_f64(K), scale, to_f64(lse), P=P, window=window)
+    else:
+        u = cap_scores(to_f64(Q), to_f64(K), scale, None if K_cap is None else to_f64(K_cap), P=P, window=window)
     ubar = pool(u, pool_w, pool_mode)
     return combine(ubar, nuc_slots(novelty, T))
 
@@ -262,7 +285,7 @@ def default_scale(d: int) -> float:
 
 
 def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=None,
-             n_valid=None, units=None, rope_cos=None, rope_sin=None, K_score=None, K_cap=None, window=0):
+             n_valid=None, units=None, rope_cos=None, rope_sin=None, K_score=None, K_cap=None, window=0, lse=None):
     """One CCD compression over a whole cache.
 
     Q_cat [B, L, Hq, P, d]; K, V [B, L, Hkv, n_cap, d]; novelty [B, n] (shared by
@@ -277,6 +300,7 @@ def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=
     model attends to the embedded keys of the current positions.
     K_cap [B, L, Hkv, P, d]: the CaP tokens' own keys; with them the attention rows are the
     model's causal ones (see cap_scores).  window > 0: sliding-window attention (see cap_scores).
+    lse [B, L, Hq, P] fp32: the log-sum-exp of every CaP query's attention row, handed in (see cap_scores_given_lse).
     """
     B, L, Hq, P, d = Q_cat.shape
     Hkv, n_cap = K.shape[2], K.shape[3]
@@ -297,7 +321,8 @@ def compress(Q_cat, K, V, novelty, *, k, T, pool_w=1, pool_mode=POOL_MAX, scale=
         nov = novelty[b, l, h, :n] if per_head else novelty[b, :n]
         Ks = K if K_score is None else K_score
         s = score_unit(Qu, Ks[b, l, h, :n], nov, T=T, scale=scale, pool_w=pool_w, pool_mode=pool_mode,
-                       K_cap=None if K_cap is None else K_cap[b, l, h], P=P, window=window)
+                       K_cap=None if K_cap is None else K_cap[b, l, h], P=P, window=window,
+                       lse=None if lse is None else lse[b, l, h * G:(h + 1) * G].reshape(G * P))
         keep = select(s, k)
         scores[b, l, h] = s
         keep_idx[b, l, h] = keep
