@@ -175,6 +175,10 @@ def main() -> int:
     ap.add_argument("--kcat", action="store_true",
                     help="the causal variant of Eq. 2: the CaP tokens' own keys join the softmax (ccd_compress_kcat, or "
                          "ccd_compress_rope with K_cap when combined with --rope)")
+    ap.add_argument("--lse", action="store_true",
+                    help="time ccd_compress_lse: the log-sum-exp of every CaP query row is handed in (as the attention "
+                         "kernel of the model returns it), so the statistics pass over K is not run; the normalisers of "
+                         "every pot are computed with torch outside the timed region")
     ap.add_argument("--per-head-novelty", action="store_true",
                     help="novelty carried per (layer, KV head) as in the cycles after the first one: [B, L, Hkv, N] "
                          "instead of [B, N]; it is compacted in place with K and V")
@@ -263,14 +267,35 @@ def main() -> int:
         rope_cos, rope_sin = torch.from_numpy(cos_h).to(dev), torch.from_numpy(sin_h).to(dev)
         k_rot = torch.empty_like(dev0["K"])
 
+    lses = None
+
+    def row_lse(i):
+        """fp32 [B, L, Hq, P]: natural-log-sum-exp of the CaP rows of pot i under its query set (torch, fp32)."""
+        K = pots[i % len(pots)][0].float()                                   # [B, L, Hkv, N, d]
+        Q = qsets[i % len(qsets)].float().reshape(cfg.B, cfg.L, cfg.Hkv, cfg.G * cfg.P, cfg.d)
+        logits = torch.matmul(Q, K.transpose(-1, -2)) * (1.0 / float(np.sqrt(cfg.d)))
+        return torch.logsumexp(logits, dim=-1).reshape(cfg.B, cfg.L, cfg.Hq, cfg.P).contiguous()
+
+    def prepare_lse():
+        nonlocal lses
+        if args.lse:
+            lses = [row_lse(i) for i in range(len(pots))]
+            torch.cuda.synchronize()
+
+    prepare_lse()
     k_cap_h = synth.cap_keys(cfg) if args.kcat else None
     k_cap = upload(k_cap_h) if args.kcat else None
 
     def step(i):
         K, V = pots[i % len(pots)]
         if args.rope:
-            rc = ip.ccd_compress_rope(shape, qsets[i % len(qsets)], K, V, novs[i % len(novs)], keep, rope_cos, rope_sin,
-                                      k_rot, ws, K_cap=k_cap, stream=stream)
+            p = i % len(pots)
+            rc = ip.ccd_compress_rope(shape, qsets[p % len(qsets) if args.lse else i % len(qsets)], K, V, novs[i % len(novs)],
+                                      keep, rope_cos, rope_sin, k_rot, ws, K_cap=k_cap, lse=lses[p] if args.lse else None,
+                                      stream=stream)
+        elif args.lse:
+            p = i % len(pots)                     # the normalisers belong to (pot p, query set p mod 4)
+            rc = ip.ccd_compress_lse(shape, qsets[p % len(qsets)], K, V, lses[p], novs[i % len(novs)], keep, ws, stream=stream)
         elif args.kcat:
             rc = ip.ccd_compress_kcat(shape, qsets[i % len(qsets)], K, V, k_cap, novs[i % len(novs)], keep, ws, stream=stream)
         else:
@@ -290,6 +315,7 @@ def main() -> int:
     # the same K steps again with an event after every kernel: per-kernel average durations
     # (between the bracketed kernels of that pass: which fraction of the kept rows each call really moved)
     refill()
+    prepare_lse()
     torch.cuda.synchronize()
     ar = torch.arange(cfg.k, device=dev)
     moved_acc = torch.zeros((), device=dev)
@@ -327,7 +353,7 @@ def main() -> int:
         else:
             r = {"kernel": stage, "bound": "hbm", "achieved": ab[stage] / t / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
         r["frac"] = r["achieved"] / r["peak"]
-        r["traffic"] = MEASURED_TRAFFIC_C3.get(stage) if cfg.name == "c3" and args.score_path == 0 and not args.rope and not args.kcat and not args.window else None
+        r["traffic"] = MEASURED_TRAFFIC_C3.get(stage) if cfg.name == "c3" and args.score_path == 0 and not args.rope and not args.kcat and not args.window and not args.lse else None
         r["traffic_source"] = "profiles/ccd_compress_c3_hbm_traffic.md" if r["traffic"] else None
         r["avg_us"] = stage_avg_us[stage]
         return r
@@ -342,6 +368,8 @@ def main() -> int:
                    if args.rope else
                    "ccd_compress_kcat calls/s (causal Eq. 2: CaP keys in the softmax; 32L x 8KV x 128d pot 4096->2048)"
                    if args.kcat else
+                   "ccd_compress_lse calls/s (row normalisers handed in: one pass over K; 32L x 8KV x 128d pot 4096->2048)"
+                   if args.lse else
                    "ccd_compress calls/s (fused score+select+compact, 32L x 8KV x 128d pot 4096->2048)"),
         "value": 1e3 / ms_per_step, "unit": "calls/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -349,7 +377,7 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: B{cfg.B} L{cfg.L} Hq{cfg.Hq} Hkv{cfg.Hkv} d{cfg.d} N{cfg.N}->k{cfg.k} "
                                f"P{cfg.P} T{cfg.T} pool{cfg.w}", "ring": [len(pots), len(qsets), len(novs)], "score_path": args.score_path,
                    "cap_keys_in_softmax": bool(args.kcat), "window": args.window,
-                   "per_head_novelty": bool(args.per_head_novelty)},
+                   "per_head_novelty": bool(args.per_head_novelty), "lse_given": bool(args.lse)},
         "call_hbm": {"algorithmic_bytes": ab["call"], "achieved_GBps": call_gbps, "frac_of_peak": call_gbps / HBM_PEAK_GBPS},
         "stage_avg_us": stage_avg_us, "moved_row_fraction": moved,
         "roofline": roof, "roofline_other_kernels": by_kernel,
@@ -371,6 +399,8 @@ def main() -> int:
             rope_kw["K_cap"] = k_cap_h
         if args.window:
             rope_kw["window"] = args.window
+        if args.lse:
+            rope_kw["lse"] = row_lse(0).cpu().numpy()
         O.compress(host0["Q_cat"], host0["K"], host0["V"], host0["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w,
                    pool_mode=O.POOL_MAX, units=sample, **rope_kw)
         c1 = time.perf_counter()

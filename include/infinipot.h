@@ -136,9 +136,10 @@ CCD_API int ccd_cr_rope(const ccd_shape_t* shape, const void* K, const float* ro
  * are not the stored ones - the model attends to the EMBEDDED keys of the current positions 0 .. n_valid-1, i.e. to the
  * attention cache that the previous call left in K_rot and the prefill extended; NULL scores on K itself.  K_score is
  * only read, and only before K_rot is written, so K_score may be the same buffer as K_rot.  K_cap (nullable): the CaP
- * tokens' own keys as in ccd_score_kcat below, embedded like K_score.  On CCD_NOOP nothing is written, K_rot included. */
+ * tokens' own keys as in ccd_score_kcat below, embedded like K_score; lse (nullable, not together with K_cap): the rows'
+ * log-sum-exps as in ccd_score_lse below.  On CCD_NOOP nothing is written, K_rot included. */
 CCD_API int ccd_compress_rope(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty,
-                      float* scores_opt, int32_t* keep_idx, const void* K_score, const void* K_cap,
+                      float* scores_opt, int32_t* keep_idx, const void* K_score, const void* K_cap, const float* lse,
                       const float* rope_cos, const float* rope_sin, void* K_rot, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
 
@@ -153,6 +154,20 @@ CCD_API int ccd_score_kcat(const ccd_shape_t* shape, const void* Q_cat, const vo
 CCD_API int ccd_compress_kcat(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, const void* K_cap,
                       float* novelty, float* scores_opt, int32_t* keep_idx, void* workspace, size_t workspace_bytes,
                       void* hip_stream);
+
+/* Eq. 2 with the normalisers handed in.  The model that ran the CaP tokens already normalised their attention rows; its
+ * attention kernel returns, next to its output, the log-sum-exp of every row.  Given those, the probability of CaP
+ * query (g, i) on cached token t is exp(scale * <q, k_t> - lse[g, i]) and the statistics pass over K is not needed: one
+ * pass instead of two.  The normalisers cover whatever keys the model let the row attend to (the CaP tokens' own keys,
+ * a sliding window), so this is the model's causal attention row of ccd_score_kcat without K_cap; shape.window still
+ * says which cached tokens a row does NOT see (their probability is 0).
+ * lse: device fp32 [B, L, Hq, P] dense, natural logarithm, of the logits scale * <q, k> (scale as in the shape),
+ * 16-byte aligned, only read; must not be NULL (CCD_EINVAL).  Everything else as in ccd_score / ccd_compress; same
+ * workspace. */
+CCD_API int ccd_score_lse(const ccd_shape_t* shape, const void* Q_cat, const void* K, const float* lse, const float* novelty,
+                  float* scores, void* workspace, size_t workspace_bytes, void* hip_stream);
+CCD_API int ccd_compress_lse(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, const float* lse, float* novelty,
+                     float* scores_opt, int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Process-wide choice of kernels: 0 = automatic (bf16: matrix cores; fp32: vector ALUs), 1 = vector ALUs
  * everywhere.  Meant for profiling one path against the other; returns CCD_EINVAL for any other value. */

@@ -33,6 +33,7 @@ struct ScorePlan {
   int n_slices2;
   int cap_block;  // 1 (vector-ALU path): `part` also holds the statistics of the CaP keys' block (causal Eq. 2)
   int head_block; // 1 (matrix-core path): `part` also holds the statistics of the windowed head (sliding window)
+  int lse_given;  // 1: the caller handed in the natural-log-sum-exp of every query row: no statistics pass
 };
 
 ScorePlan plan_score(const Dims& D);
@@ -42,6 +43,7 @@ void launch_stats_valu(const Dims& D, const ScorePlan& pl, const void* Q, const 
 // merge the per-slice statistics into one log2-sum-exp per (unit, query)
 void launch_merge(const Dims& D, const ScorePlan& pl, const float2* part, float* lse2, hipStream_t s);
 // pass 2: u[unit, t] = sum over queries of exp2(logit2 - lse2)
+// (lse2 in log2 units, or the caller's natural-log-sum-exps when pl.lse_given)
 void launch_prob_valu(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float* lse2, float* u,
                       hipStream_t s);
 
@@ -52,14 +54,16 @@ void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const 
 // K_cap (nullable; [units, P, d], contiguous): the CaP tokens' own keys join the softmax (Eq. 2 read as the model's
 // causal attention row: query row g * P + i also sees the CaP keys 0 .. i); their statistics are computed in the
 // prologue of pass 2 and merged like one more token slice
-// lse_out ([units, G*P], written when pl.head_block): the final log2-sum-exp per query, for launch_head_prob_mfma
+// lse_io ([units, G*P]): pl.lse_given: read, the caller's natural-log-sum-exp per query row (`part` is not used
+// then); else written when pl.head_block: the final log2-sum-exp per query, for launch_head_prob_mfma
 void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const void* K_cap,
-                      const float2* part, float* u, float* lse_out, hipStream_t s);
+                      const float2* part, float* u, float* lse_io, hipStream_t s);
 // Sliding attention window on the matrix-core path: the first D.head tokens are hidden from some CaP tokens and are
 // left out of the two passes above.  launch_head_stats_mfma (before pass 2) leaves their (max, sum) statistics per
 // query in the extra entry of `part` (pl.head_block must be 1); launch_head_prob_mfma (after pass 2) writes
 // u[unit, 0 .. D.head) from the final log2-sum-exps.
 void launch_head_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s);
+// (lse in log2 units, or the caller's natural-log ones when pl.lse_given)
 void launch_head_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float* lse, float* u,
                            hipStream_t s);
 

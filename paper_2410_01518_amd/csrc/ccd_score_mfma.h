@@ -497,7 +497,9 @@ __device__ __forceinline__ void score_pass_body(const Dims& D, const ScorePlan& 
       float2 cap = make_float2(kNegHuge, 0.f);         // the block of the CaP keys (causal variant), else nothing
       if (Kcap != nullptr)
         cap = cap_block_stats<HD>(D, Kcap + (int64_t)unit * D.P * HD, bq, qc + wave * (kQB * 32), col, half, c);
-      if (q < D.GP) {
+      if (pl.lse_given) {            // the caller's normalisers (natural log): nothing to merge
+        if (q < D.GP) lse = lse_out[(int64_t)unit * D.GP + q] * 1.44269504088896340736f;
+      } else if (q < D.GP) {
         const float2* p = part + (int64_t)unit * pl.n_slices1 * D.GP + q;
         if (pl.head_block) {         // statistics of the windowed head, left there by its own kernel
           const float2 hd = part[extra_block_index(D, pl, unit, q)];

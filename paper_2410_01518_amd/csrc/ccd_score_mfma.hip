@@ -81,7 +81,7 @@ __global__ __launch_bounds__(kMT) void head_stats_kernel(Dims D, ScorePlan pl, c
 template <int HD>
 __global__ __launch_bounds__(kMT) void head_prob_kernel(Dims D, const uint16_t* __restrict__ Q,
                                                         const uint16_t* __restrict__ K, const float* __restrict__ lse,
-                                                        float* __restrict__ u) {
+                                                        float lse_mul, float* __restrict__ u) {
   __shared__ HeadLds<HD> sm;
   const int unit = D.unit0 + blockIdx.x;
   const UnitIdx ui = decode_unit(D, unit);
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kMT) void head_prob_kernel(Dims D, const uint16_t* 
   float* uu = u + (int64_t)unit * D.n;
   for (int qc = 0; qc < D.GP; qc += kQPerPass) {
     const int q = qc + threadIdx.x;
-    sm.lse_s[threadIdx.x] = q < D.GP ? lse[(int64_t)unit * D.GP + q] : INFINITY;
+    sm.lse_s[threadIdx.x] = q < D.GP ? lse[(int64_t)unit * D.GP + q] * lse_mul : INFINITY;
     __syncthreads();
     const int q0 = qc + wave * (kQB * 32) + col;
     prob_head_masked<HD>(Ku, 0, D.head, q0 < D.GP ? Q + q_offset(D, ui, q0) : nullptr,
@@ -132,24 +132,24 @@ void launch_head_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, c
 
 void launch_head_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float* lse, float* u,
                            hipStream_t s) {
-  (void)pl;
+  const float lse_mul = pl.lse_given ? 1.44269504088896340736f : 1.0f;
   dim3 grid((unsigned)D.units_run), block(kMT);
   if (D.d == 64)
-    hipLaunchKernelGGL((head_prob_kernel<64>), grid, block, 0, s, D, (const uint16_t*)Q, (const uint16_t*)K, lse, u);
+    hipLaunchKernelGGL((head_prob_kernel<64>), grid, block, 0, s, D, (const uint16_t*)Q, (const uint16_t*)K, lse, lse_mul, u);
   else
-    hipLaunchKernelGGL((head_prob_kernel<128>), grid, block, 0, s, D, (const uint16_t*)Q, (const uint16_t*)K, lse, u);
+    hipLaunchKernelGGL((head_prob_kernel<128>), grid, block, 0, s, D, (const uint16_t*)Q, (const uint16_t*)K, lse, lse_mul, u);
 }
 
 // K_cap (nullable; [units, P, d] bf16): the CaP tokens' own keys join the softmax, causally
 void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const void* K_cap,
-                      const float2* part, float* u, float* lse_out, hipStream_t s) {
+                      const float2* part, float* u, float* lse_io, hipStream_t s) {
   dim3 grid((unsigned)((D.units_run + 7) / 8 * 8) * pl.n_slices2), block(kMT);
   if (D.d == 64)
     hipLaunchKernelGGL((score_pass_kernel<64, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
-                       const_cast<float2*>(part), u, (const uint16_t*)K_cap, lse_out);
+                       const_cast<float2*>(part), u, (const uint16_t*)K_cap, lse_io);
   else
     hipLaunchKernelGGL((score_pass_kernel<128, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
-                       const_cast<float2*>(part), u, (const uint16_t*)K_cap, lse_out);
+                       const_cast<float2*>(part), u, (const uint16_t*)K_cap, lse_io);
 }
 
 }  // namespace ccd

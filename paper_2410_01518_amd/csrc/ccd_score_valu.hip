@@ -155,7 +155,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(Dims D, ScorePlan pl, c
 template <typename T, int HD>
 __global__ __launch_bounds__(kThreads) void prob_valu_kernel(Dims D, ScorePlan pl, const T* __restrict__ Q,
                                                              const T* __restrict__ K, const float* __restrict__ lse2,
-                                                             float* __restrict__ u) {
+                                                             float lse_mul, float* __restrict__ u) {
   __shared__ float4 Qs[kQryTile][HD / 4];
   __shared__ float Ls[kQryTile];
   const int unit = D.unit0 + blockIdx.x / pl.n_slices2, tid = threadIdx.x;
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(kThreads) void prob_valu_kernel(Dims D, ScorePlan p
       const int q = q0 + qi;
       Qs[qi][c] = q < D.GP ? load4(Q + q_offset(D, ui, q) + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    if (tid < kQryTile) Ls[tid] = (q0 + tid) < D.GP ? lse2[(int64_t)unit * D.GP + q0 + tid] : INFINITY;
+    if (tid < kQryTile) Ls[tid] = (q0 + tid) < D.GP ? lse2[(int64_t)unit * D.GP + q0 + tid] * lse_mul : INFINITY;
     __syncthreads();
     const int nq = min(kQryTile, D.GP - q0);
     for (int qi = 0; qi < nq; ++qi) {
@@ -228,8 +228,9 @@ void launch_merge(const Dims& D, const ScorePlan& pl, const float2* part, float*
 void launch_prob_valu(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float* lse2, float* u,
                       hipStream_t s) {
   dim3 grid((unsigned)pl.n_slices2 * D.units_run), block(kThreads);
+  const float lse_mul = pl.lse_given ? 1.44269504088896340736f : 1.0f;
 #define CCD_LAUNCH(T, HD) \
-  hipLaunchKernelGGL((prob_valu_kernel<T, HD>), grid, block, 0, s, D, pl, (const T*)Q, (const T*)K, lse2, u)
+  hipLaunchKernelGGL((prob_valu_kernel<T, HD>), grid, block, 0, s, D, pl, (const T*)Q, (const T*)K, lse2, lse_mul, u)
   if (D.dtype == 0) { if (D.d == 64) CCD_LAUNCH(float, 64); else CCD_LAUNCH(float, 128); }
   else              { if (D.d == 64) CCD_LAUNCH(uint16_t, 64); else CCD_LAUNCH(uint16_t, 128); }
 #undef CCD_LAUNCH

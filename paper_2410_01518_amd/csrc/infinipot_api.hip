@@ -116,6 +116,7 @@ static ScorePlan plan_mfma(const Dims& D) {
   pl.n_slices2 = (D.n + pl.slice2 - 1) / pl.slice2;
   pl.cap_block = 0;
   pl.head_block = 0;
+  pl.lse_given = 0;
   return pl;
 }
 
@@ -132,6 +133,7 @@ ScorePlan plan_score(const Dims& D) {
   pl.n_slices2 = (D.n + pl.slice2 - 1) / pl.slice2;
   pl.cap_block = 0;
   pl.head_block = 0;
+  pl.lse_given = 0;
   return pl;
 }
 
@@ -196,11 +198,27 @@ static int launch_status() { return hipGetLastError() == hipSuccess ? CCD_OK : C
 // Raw CaP score u[unit, t] (Eq. 2, before pooling).  With K_cap the CaP tokens' own keys join the softmax (causally): their
 // statistics become one more entry per unit of `part` on the vector-ALU path (the matrix-core pass 2 computes them
 // itself).  (The NuC slots, Sec. 3.3.3 step 1, are found by the selection kernels from the novelty row.)
+// lse (nullable): the caller's natural-log-sum-exp of every CaP query row [units, G*P]: the statistics pass (and
+// with it K_cap) is not needed, the probabilities follow from one pass over K.
 static void run_cap_scores(const Dims& D, ScorePlan pl, const Workspace& w, const void* Q, const void* K,
-                           const void* K_cap, char* ws, hipStream_t st) {
+                           const void* K_cap, const float* lse, char* ws, hipStream_t st) {
   float2* part = reinterpret_cast<float2*>(ws + w.off_part);
   float* lse2 = reinterpret_cast<float*>(ws + w.off_lse);
   float* u = reinterpret_cast<float*>(ws + w.off_u);
+  if (lse != nullptr) {
+    pl.lse_given = 1;
+    float* lse_rw = const_cast<float*>(lse);   // only read when pl.lse_given
+    g_prof.begin(kStProb, st);
+    if (pl.use_mfma) launch_prob_mfma(D, pl, Q, K, nullptr, part, u, lse_rw, st);
+    else             launch_prob_valu(D, pl, Q, K, lse, u, st);
+    g_prof.end(st);
+    if (pl.use_mfma && D.head > 0) {
+      g_prof.begin(kStHead, st);
+      launch_head_prob_mfma(D, pl, Q, K, lse, u, st);
+      g_prof.end(st);
+    }
+    return;
+  }
   if (K_cap != nullptr && !pl.use_mfma) {    // (the matrix-core pass 2 takes the CaP keys in its prologue)
     pl.cap_block = 1;
     g_prof.begin(kStCapBlock, st);
@@ -250,13 +268,13 @@ size_t ccd_workspace_bytes(const ccd_shape_t* shape) {
   return layout_workspace(D).total;
 }
 
-static int score_impl(const ccd_shape_t* shape, const void* Q_cat, const void* K, const void* K_cap, const float* novelty,
-                      float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
+static int score_impl(const ccd_shape_t* shape, const void* Q_cat, const void* K, const void* K_cap, const float* lse,
+                      const float* novelty, float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = check_shape(shape, kNeedFull);
   if (rc != CCD_OK) return rc;
   if (Q_cat == nullptr || K == nullptr || scores == nullptr) return CCD_EINVAL;
   if (novelty == nullptr && shape->T > 0) return CCD_EINVAL;
-  if (!aligned16(Q_cat) || !aligned16(K) || !aligned16(K_cap)) return CCD_EALIGN;
+  if (!aligned16(Q_cat) || !aligned16(K) || !aligned16(K_cap) || !aligned16(lse)) return CCD_EALIGN;
   const Dims D = make_dims(shape);
   const ScorePlan pl = plan_score(D);
   if (pl.use_mfma && D.head > mfma_max_slice()) return CCD_EUNSUPPORTED;   // window far shorter than the pot
@@ -265,20 +283,26 @@ static int score_impl(const ccd_shape_t* shape, const void* Q_cat, const void* K
   if (rc != CCD_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  run_cap_scores(D, pl, w, Q_cat, K, K_cap, ws, st);
+  run_cap_scores(D, pl, w, Q_cat, K, K_cap, lse, ws, st);
   launch_finalize_select(D, reinterpret_cast<const float*>(ws + w.off_u), novelty, scores, nullptr, st);
   return launch_status();
 }
 
 int ccd_score(const ccd_shape_t* shape, const void* Q_cat, const void* K, const float* novelty, float* scores,
               void* workspace, size_t workspace_bytes, void* hip_stream) {
-  return score_impl(shape, Q_cat, K, nullptr, novelty, scores, workspace, workspace_bytes, hip_stream);
+  return score_impl(shape, Q_cat, K, nullptr, nullptr, novelty, scores, workspace, workspace_bytes, hip_stream);
 }
 
 int ccd_score_kcat(const ccd_shape_t* shape, const void* Q_cat, const void* K, const void* K_cap, const float* novelty,
                    float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (K_cap == nullptr) return CCD_EINVAL;
-  return score_impl(shape, Q_cat, K, K_cap, novelty, scores, workspace, workspace_bytes, hip_stream);
+  return score_impl(shape, Q_cat, K, K_cap, nullptr, novelty, scores, workspace, workspace_bytes, hip_stream);
+}
+
+int ccd_score_lse(const ccd_shape_t* shape, const void* Q_cat, const void* K, const float* lse, const float* novelty,
+                  float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (lse == nullptr) return CCD_EINVAL;
+  return score_impl(shape, Q_cat, K, nullptr, lse, novelty, scores, workspace, workspace_bytes, hip_stream);
 }
 
 int ccd_select(const ccd_shape_t* shape, const float* scores, int32_t* keep_idx, void* hip_stream) {
@@ -308,8 +332,9 @@ int ccd_compact(const ccd_shape_t* shape, const void* K_src, const void* V_src, 
 // ccd_compress, optionally with CR-RoPE of the kept keys on the side (K_rot != nullptr), other keys to attend to
 // (K_score != nullptr) and the CaP tokens' own keys in the softmax (K_cap != nullptr)
 static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
-                         int32_t* keep_idx, const void* K_score, const void* K_cap, const float* rope_cos,
-                         const float* rope_sin, void* K_rot, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                         int32_t* keep_idx, const void* K_score, const void* K_cap, const float* lse,
+                         const float* rope_cos, const float* rope_sin, void* K_rot, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
   int rc = check_shape(shape, kNeedFull);
   if (rc != CCD_OK) return rc;
   if (Q_cat == nullptr || K == nullptr || V == nullptr || keep_idx == nullptr) return CCD_EINVAL;
@@ -322,6 +347,8 @@ static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, v
   if (K_score != nullptr && (K_score == V || !aligned16(K_score))) return K_score == V ? CCD_EINVAL : CCD_EALIGN;
   if (K_cap != nullptr && (K_cap == K || K_cap == V || K_cap == K_rot)) return CCD_EINVAL;
   if (!aligned16(K_cap)) return CCD_EALIGN;
+  if (lse != nullptr && K_cap != nullptr) return CCD_EINVAL;     // the normalisers already account for the CaP keys
+  if (!aligned16(lse)) return CCD_EALIGN;
   const void* K_attn = K_score != nullptr ? K_score : K;     // the keys the CaP queries attend to
   const Dims D = make_dims(shape);
   const ScorePlan pl = plan_score(D);
@@ -335,7 +362,7 @@ static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, v
   const float* u = reinterpret_cast<const float*>(ws + w.off_u);
   const bool per_head = shape->nov_stride_l != 0 || shape->nov_stride_h != 0;
   if (g_prof.on) ++g_prof.calls;
-  run_cap_scores(D, pl, w, Q_cat, K_attn, K_cap, ws, st);
+  run_cap_scores(D, pl, w, Q_cat, K_attn, K_cap, lse, ws, st);
   if (select_compact_supported(D)) {
     g_prof.begin(kStSelCompact, st);
     launch_select_compact(D, u, novelty, per_head, scores_opt, keep_idx, K, V, rope_cos, rope_sin, K_rot, st);
@@ -355,6 +382,13 @@ static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, v
 int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
                  int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* hip_stream) {
   return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, nullptr, nullptr, nullptr, nullptr, nullptr,
+                       nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+int ccd_compress_lse(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, const float* lse, float* novelty,
+                     float* scores_opt, int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (lse == nullptr) return CCD_EINVAL;
+  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, nullptr, nullptr, lse, nullptr, nullptr, nullptr,
                        workspace, workspace_bytes, hip_stream);
 }
 
@@ -362,14 +396,14 @@ int ccd_compress_kcat(const ccd_shape_t* shape, const void* Q_cat, void* K, void
                       float* scores_opt, int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (K_cap == nullptr) return CCD_EINVAL;
   return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, nullptr, K_cap, nullptr, nullptr, nullptr,
-                       workspace, workspace_bytes, hip_stream);
+                       nullptr, workspace, workspace_bytes, hip_stream);
 }
 
 int ccd_compress_rope(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
-                      int32_t* keep_idx, const void* K_score, const void* K_cap, const float* rope_cos,
+                      int32_t* keep_idx, const void* K_score, const void* K_cap, const float* lse, const float* rope_cos,
                       const float* rope_sin, void* K_rot, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (K_rot == nullptr) return CCD_EINVAL;
-  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, K_score, K_cap, rope_cos, rope_sin, K_rot,
+  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, K_score, K_cap, lse, rope_cos, rope_sin, K_rot,
                        workspace, workspace_bytes, hip_stream);
 }
 

@@ -22,7 +22,8 @@ CCD_FP32, CCD_BF16 = 0, 1
 CCD_POOL_NONE, CCD_POOL_MAX, CCD_POOL_AVG = 0, 1, 2
 
 EXPORTS = ("ccd_workspace_bytes", "ccd_score", "ccd_select", "ccd_compact", "ccd_compress", "ccd_cr_rope",
-           "ccd_compress_rope", "ccd_score_kcat", "ccd_compress_kcat", "ccd_nuc_from_logits", "ccd_set_score_path", "ccd_profile_enable", "ccd_profile_stages", "ccd_profile_stage_name",
+           "ccd_compress_rope", "ccd_score_kcat", "ccd_compress_kcat", "ccd_score_lse", "ccd_compress_lse",
+           "ccd_nuc_from_logits", "ccd_set_score_path", "ccd_profile_enable", "ccd_profile_stages", "ccd_profile_stage_name",
            "ccd_profile_collect", "ccd_strerror")
 
 
@@ -67,7 +68,11 @@ def lib() -> ctypes.CDLL:
         L.ccd_cr_rope.restype = ctypes.c_int
         L.ccd_cr_rope.argtypes = [sp, vp, vp, vp, ctypes.c_int32, vp, vp]
         L.ccd_compress_rope.restype = ctypes.c_int
-        L.ccd_compress_rope.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ccd_compress_rope.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ccd_score_lse.restype = ctypes.c_int
+        L.ccd_score_lse.argtypes = [sp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ccd_compress_lse.restype = ctypes.c_int
+        L.ccd_compress_lse.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.ccd_score_kcat.restype = ctypes.c_int
         L.ccd_score_kcat.argtypes = [sp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.ccd_compress_kcat.restype = ctypes.c_int
@@ -199,9 +204,10 @@ def ccd_cr_rope(shape, K, rope_cos, rope_sin, count, K_rot, stream=None) -> int:
 
 
 def ccd_compress_rope(shape, Q_cat, K, V, novelty, keep_idx, rope_cos, rope_sin, K_rot, workspace, scores=None,
-                      K_score=None, K_cap=None, stream=None) -> int:
+                      K_score=None, K_cap=None, lse=None, stream=None) -> int:
+    assert lse is None or (lse.is_contiguous() and lse.dtype == torch.float32)
     return _check(lib().ccd_compress_rope(ctypes.byref(shape), _ptr(Q_cat), _ptr(K), _ptr(V), _ptr(novelty), _ptr(scores),
-                                          _ptr(keep_idx), _ptr(K_score), _ptr(K_cap), _ptr(rope_cos), _ptr(rope_sin),
+                                          _ptr(keep_idx), _ptr(K_score), _ptr(K_cap), _ptr(lse), _ptr(rope_cos), _ptr(rope_sin),
                                           _ptr(K_rot), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                           _stream(stream)))
 
@@ -211,6 +217,20 @@ def ccd_score_kcat(shape, Q_cat, K, K_cap, novelty, scores, workspace, stream=No
     assert K_cap is None or K_cap.is_contiguous()
     return _check(lib().ccd_score_kcat(ctypes.byref(shape), _ptr(Q_cat), _ptr(K), _ptr(K_cap), _ptr(novelty), _ptr(scores),
                                        _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+
+
+def ccd_score_lse(shape, Q_cat, K, lse, novelty, scores, workspace, stream=None) -> int:
+    """lse [B, L, Hq, P] fp32, contiguous: the natural-log-sum-exp of every CaP query's attention row."""
+    assert lse is None or (lse.is_contiguous() and lse.dtype == torch.float32)
+    return _check(lib().ccd_score_lse(ctypes.byref(shape), _ptr(Q_cat), _ptr(K), _ptr(lse), _ptr(novelty), _ptr(scores),
+                                      _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+
+
+def ccd_compress_lse(shape, Q_cat, K, V, lse, novelty, keep_idx, workspace, scores=None, stream=None) -> int:
+    assert lse is None or (lse.is_contiguous() and lse.dtype == torch.float32)
+    return _check(lib().ccd_compress_lse(ctypes.byref(shape), _ptr(Q_cat), _ptr(K), _ptr(V), _ptr(lse), _ptr(novelty),
+                                         _ptr(scores), _ptr(keep_idx), _ptr(workspace),
+                                         0 if workspace is None else workspace.numel(), _stream(stream)))
 
 
 def ccd_compress_kcat(shape, Q_cat, K, V, K_cap, novelty, keep_idx, workspace, scores=None, stream=None) -> int:

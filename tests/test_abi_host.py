@@ -135,9 +135,9 @@ def test_cr_rope_argument_errors_are_decided_on_the_host():
     assert rope(cos=P + 4) == ip.CCD_EALIGN and rope(Krot=P2 + 8) == ip.CCD_EALIGN
     assert rope(count=0) == ip.CCD_OK                                                   # nothing to do, nothing launched
 
-    def crope(cos=P, sin=P, Krot=P2, shape=s, Kscore=None, Kcap=None):
-        return L.ccd_compress_rope(ctypes.byref(shape), P, P, P, P, None, P, Kscore, Kcap, cos, sin, Krot, 0x10000, ws_bytes,
-                                   None)
+    def crope(cos=P, sin=P, Krot=P2, shape=s, Kscore=None, Kcap=None, lse=None):
+        return L.ccd_compress_rope(ctypes.byref(shape), P, P, P, P, None, P, Kscore, Kcap, lse, cos, sin, Krot, 0x10000,
+                                   ws_bytes, None)
 
     assert crope(Krot=None) == ip.CCD_EINVAL and crope(cos=None) == ip.CCD_EINVAL and crope(sin=None) == ip.CCD_EINVAL
     assert crope(Krot=P) == ip.CCD_EINVAL                                               # aliases K (and V)
@@ -147,6 +147,24 @@ def test_cr_rope_argument_errors_are_decided_on_the_host():
     assert crope(Kcap=P) == ip.CCD_EINVAL and crope(Kcap=P2) == ip.CCD_EINVAL           # aliases K / K_rot
     assert crope(Kcap=P2 + 0x100004) == ip.CCD_EALIGN
     assert crope(Kcap=P2 + 0x100000, shape=_shape(n_valid=300, n_cap=512, k=256)) == ip.CCD_NOOP
+    assert crope(Kcap=P2 + 0x100000, lse=P2 + 0x200000) == ip.CCD_EINVAL                # normalisers and CaP keys together
+    assert crope(lse=P2 + 0x200004) == ip.CCD_EALIGN
+    assert crope(lse=P2 + 0x200000, shape=_shape(n_valid=300, n_cap=512, k=256)) == ip.CCD_NOOP
+
+
+def test_lse_argument_errors_are_decided_on_the_host():
+    s = _shape()
+    L = ip.lib()
+    ws_bytes = ip.ccd_workspace_bytes(s)
+    P2 = P + 0x100000
+    assert L.ccd_score_lse(ctypes.byref(s), P, P, None, P, P, 0x10000, ws_bytes, None) == ip.CCD_EINVAL
+    assert L.ccd_score_lse(ctypes.byref(s), P, P, P2 + 4, P, P, 0x10000, ws_bytes, None) == ip.CCD_EALIGN
+    assert L.ccd_score_lse(ctypes.byref(s), P, P, P2, P, None, 0x10000, ws_bytes, None) == ip.CCD_EINVAL
+    assert L.ccd_compress_lse(ctypes.byref(s), P, P, P, None, P, None, P, 0x10000, ws_bytes, None) == ip.CCD_EINVAL
+    assert L.ccd_compress_lse(ctypes.byref(s), P, P, P, P2 + 8, P, None, P, 0x10000, ws_bytes, None) == ip.CCD_EALIGN
+    assert L.ccd_compress_lse(ctypes.byref(s), P, P, P, P2, P, None, P, None, ws_bytes, None) == ip.CCD_EWORKSPACE
+    noop = _shape(n_valid=300, n_cap=512, k=256)
+    assert L.ccd_compress_lse(ctypes.byref(noop), P, P, P, P2, P, None, P, 0x10000, ws_bytes, None) == ip.CCD_NOOP
 
 
 def test_kcat_argument_errors_are_decided_on_the_host():
