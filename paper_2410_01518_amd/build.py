@@ -49,7 +49,26 @@ def build_library(verbose: bool = True, extra_flags=()) -> str:
     os.replace(tmp, LIB)
     if verbose:
         print(f"built {LIB}")
+    build_c_client(verbose)
     return LIB
+
+
+C_CLIENT_SRC = os.path.join(os.path.dirname(HERE), "tests", "c_client", "ccd_client.c")
+C_CLIENT = os.path.join(HERE, "ccd_client")
+
+
+def build_c_client(verbose: bool = True) -> str:
+    """The plain C client of the ABI (gcc, C99): the header and the library must be usable without C++ or Python."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-Werror", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(os.path.dirname(HERE), "include"),
+           "-I", os.path.join(rocm, "include"), C_CLIENT_SRC, "-o", C_CLIENT, "-L", HERE, "-linfinipot",
+           "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-Wl,-rpath,$ORIGIN", f"-Wl,-rpath,{os.path.join(rocm, 'lib')}"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"gcc failed on the C client:\n{r.stdout}\n{r.stderr}")
+    if verbose:
+        print(f"built {C_CLIENT}")
+    return C_CLIENT
 
 
 if __name__ == "__main__":
