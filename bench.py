@@ -101,6 +101,81 @@ def stream_bench(args, dev, torch, ip, synth) -> int:
     return 0
 
 
+def stress_bench(args, dev, torch, ip, synth) -> int:
+    """The large-pot configuration at full size: 4 sequences x 80 layers x 8 KV heads (2560 units), 64 query heads,
+    pot 32768 -> 4096, 128 CaP tokens, bf16; keys N(0,1) x sqrt(min(z_t, 64)), z_t ~ Zipf(1.1) per (sequence, token).
+    A pot is 43 GB, so the inputs are drawn on the device, and every call (1 warm-up, up to 3 timed, then as many
+    again with an event after every kernel) gets a pot that has not been compressed before."""
+    cfg = synth.CONFIGS["c5"]
+    g = torch.Generator(device=dev).manual_seed(5005)
+    rng = np.random.default_rng(5005)
+    z = np.minimum(rng.zipf(1.1, size=(cfg.B, cfg.N)), 64).astype(np.float32)
+    gain = torch.from_numpy(np.sqrt(z)).to(dev)[:, None, None, :, None]
+    kv_shape = (cfg.B, cfg.L, cfg.Hkv, cfg.N, cfg.d)
+    pot_bytes = 2 * cfg.units * cfg.N * cfg.d * 2
+    n_pots = min(4, int(0.85 * torch.cuda.mem_get_info()[0]) // pot_bytes)
+    if n_pots < 2:
+        print("bench.py: --aux stress needs room for two 43 GB pots", file=sys.stderr)
+        return 2
+    steps = max(1, min(args.steps, n_pots - 1))
+
+    def draw(K, V):
+        for b in range(cfg.B):
+            K[b] = (torch.randn(K[b].shape, generator=g, device=dev, dtype=torch.float32) * gain[b]).to(torch.bfloat16)
+        V.normal_(generator=g)
+
+    pots = [(torch.empty(kv_shape, dtype=torch.bfloat16, device=dev), torch.empty(kv_shape, dtype=torch.bfloat16, device=dev))
+            for _ in range(n_pots)]
+    for K, V in pots:
+        draw(K, V)
+    Q = torch.randn((cfg.B, cfg.L, cfg.Hq, cfg.P, cfg.d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    nov = torch.rand((cfg.B, cfg.N), generator=g, device=dev, dtype=torch.float32)
+    shape = ip.make_shape(Q, pots[0][0], nov, k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=ip.CCD_POOL_MAX)
+    ws = ip.alloc_workspace(shape)
+    keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        K, V = pots[i]
+        rc = ip.ccd_compress(shape, Q, K, V, nov, keep, ws, stream=stream)
+        assert rc == ip.CCD_OK, rc
+
+    step(n_pots - 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    for K, V in pots[:steps]:
+        draw(K, V)
+    torch.cuda.synchronize()
+    ip.ccd_profile_enable(True)
+    for i in range(steps):
+        step(i)
+    stage_ms, calls = ip.ccd_profile_collect()
+    ip.ccd_profile_enable(False)
+    stage_us = {k: 1e3 * v / max(calls, 1) for k, v in stage_ms.items() if v > 0}
+    ab = algorithmic_bytes(cfg)
+    dom = max(stage_us, key=stage_us.get)
+    t = stage_us[dom] * 1e-6
+    if dom in ("score_stats", "score_prob"):
+        roof = {"kernel": dom, "bound": "mfma", "achieved": algorithmic_flops(cfg) / t / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s"}
+    else:
+        roof = {"kernel": dom, "bound": "hbm", "achieved": ab[dom] / t / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    print(json.dumps({"metric": "ccd_compress calls/s (large pot: 4 x 80L x 8KV x 128d, 64 query heads, pot 32768 -> 4096, 128 CaP tokens)",
+                      "value": 1e3 / ms, "unit": "calls/s", "n_gpus": 1, "steps": steps, "warmup": 1, "ms_per_step": ms,
+                      "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"{cfg.name}: B{cfg.B} L{cfg.L} Hq{cfg.Hq} Hkv{cfg.Hkv} d{cfg.d} N{cfg.N}->k{cfg.k} "
+                                             f"P{cfg.P} T{cfg.T} pool{cfg.w}", "pots": n_pots, "pot_GB": pot_bytes / 1e9},
+                      "call_hbm": {"algorithmic_bytes": ab["call"], "achieved_GBps": ab["call"] / (ms * 1e-3) / 1e9},
+                      "stage_avg_us": stage_us, "roofline": roof, "cpu_baseline": None}))
+    return 0
+
+
 def aux_bench(args, cfg, dev, torch, ip, synth) -> int:
     """Stand-alone companion kernels (HBM-bound): HIP-event time over `steps` calls on rotating cold buffers."""
     g = torch.Generator(device=dev).manual_seed(77)
@@ -184,10 +259,11 @@ def main() -> int:
                          "instead of [B, N]; it is compacted in place with K and V")
     ap.add_argument("--window", type=int, default=0,
                     help="sliding attention window in tokens (0 = none), e.g. 4096 for a window as long as the pot")
-    ap.add_argument("--aux", choices=["nuc", "cr_rope", "stream"], default=None,
+    ap.add_argument("--aux", choices=["nuc", "cr_rope", "stream", "stress"], default=None,
                     help="time something else than the headline call: nuc = ccd_nuc_from_logits on 4096 x 128256 bf16 "
                          "logits, cr_rope = ccd_cr_rope on the kept half of a headline pot, stream = a 131072-token "
-                         "context streamed through a pot of 4096 in 2048-token chunks (62 distillations)")
+                         "context streamed through a pot of 4096 in 2048-token chunks (62 distillations), stress = the "
+                         "large-pot configuration at full size (2560 units, pot 32768 -> 4096, 43 GB per pot)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for scaling rocprofv3's "
@@ -210,6 +286,8 @@ def main() -> int:
     ip.lib()
     if args.aux == "stream":
         return stream_bench(args, dev, torch, ip, synth)
+    if args.aux == "stress":
+        return stress_bench(args, dev, torch, ip, synth)
     if args.aux is not None:
         return aux_bench(args, cfg, dev, torch, ip, synth)
     ip.ccd_set_score_path(args.score_path)

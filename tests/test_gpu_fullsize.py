@@ -78,6 +78,66 @@ def test_large_pot_shape_on_sampled_units():
     np.testing.assert_array_equal(Kh[..., :cfg.k, :], np.take_along_axis(inp["K"], kh.astype(np.int64)[..., None], axis=3))
 
 
+def test_stress_config_full_size_drawn_on_device():
+    """The whole stress configuration in one call: 4 sequences x 80 layers x 8 KV heads = 2560 units, pot 32768 -> 4096,
+    1024 query rows per unit; K and V are 21.5 GB each (element offsets beyond 2^32, a 3 GB workspace).  The inputs
+    are drawn on the device with the recipe of the configuration (keys N(0,1) x sqrt(min(z_t, 64)), z_t ~ Zipf(1.1) per
+    (sequence, token)); the oracle scores sampled units, the selection is replayed on sampled units, and every unit's
+    keep_idx and compacted rows are checked on the device."""
+    cfg = synth.CONFIGS["c5"]
+    free = torch.cuda.mem_get_info()[0]
+    pot_bytes = 2 * cfg.units * cfg.N * cfg.d * 2
+    if free < 2.4 * pot_bytes:
+        pytest.skip(f"needs {2.4 * pot_bytes / 2**30:.0f} GiB of device memory, {free / 2**30:.0f} GiB free")
+    print(f"stress, full size {cfg}", flush=True)
+    g = torch.Generator(device="cuda").manual_seed(5005)
+    rng = np.random.default_rng(5005)
+    z = np.minimum(rng.zipf(1.1, size=(cfg.B, cfg.N)), 64).astype(np.float32)
+    gain = torch.from_numpy(np.sqrt(z)).cuda()[:, None, None, :, None]                  # [B,1,1,N,1]
+    K = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N, cfg.d), dtype=torch.bfloat16, device="cuda")
+    for b in range(cfg.B):                                                              # (fp32 draw, one sequence at a time)
+        K[b] = (torch.randn(K[b].shape, generator=g, device="cuda", dtype=torch.float32) * gain[b]).to(torch.bfloat16)
+    V = torch.empty_like(K).normal_(generator=g)
+    Q = torch.randn((cfg.B, cfg.L, cfg.Hq, cfg.P, cfg.d), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    nov = torch.rand((cfg.B, cfg.N), generator=g, device="cuda", dtype=torch.float32)
+    K0, V0 = K.clone(), V.clone()
+    shape = ip.make_shape(Q, K, nov, k=cfg.k, T=cfg.T, pool_w=cfg.w)
+    ws = ip.alloc_workspace(shape)
+    scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
+    keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    print(f"  inputs drawn, workspace {ws.numel() * ws.element_size() / 2**30:.2f} GiB", flush=True)
+    t0 = torch.cuda.Event(enable_timing=True); t1 = torch.cuda.Event(enable_timing=True)
+    t0.record()
+    assert ip.ccd_compress(shape, Q, K, V, nov, keep, ws, scores=scores) == ip.CCD_OK
+    t1.record()
+    torch.cuda.synchronize()
+    print(f"  ccd_compress: {t0.elapsed_time(t1):.1f} ms", flush=True)
+    # every unit, on the device: ascending in-range keep_idx, T NuC slots lifted, rows bit-exact, tail untouched
+    k64 = keep.to(torch.int64)
+    assert int(k64.min()) >= 0 and int(k64.max()) < cfg.N and bool((k64[..., 1:] > k64[..., :-1]).all())
+    assert bool((torch.isposinf(scores).sum(dim=-1) == cfg.T).all()) and not bool(torch.isnan(scores).any())
+    for b in range(cfg.B):
+        idx = k64[b][..., None].expand(-1, -1, -1, cfg.d)
+        for T_new, T_old in ((K, K0), (V, V0)):
+            got, src = T_new[b].view(torch.int16), T_old[b].view(torch.int16)
+            assert torch.equal(got[..., :cfg.k, :], torch.gather(src, 2, idx))
+            assert torch.equal(got[..., cfg.k:, :], src[..., cfg.k:, :])
+    print("  all units checked on the device", flush=True)
+    # sampled units: replay of the selection, fp64 oracle
+    units = _sample_units(cfg, 2, seed=2)
+    nov_h = gu.to_host(nov)
+    for (b, l, h) in units:
+        sh, kh = gu.to_host(scores[b, l, h]), gu.to_host(keep[b, l, h])
+        np.testing.assert_array_equal(kh, O.select(sh, cfg.k))
+        Qu = gu.to_host(Q[b, l, h * cfg.G:(h + 1) * cfg.G])[None, None]
+        Ku, Vu = gu.to_host(K0[b, l, h])[None, None, None], gu.to_host(V0[b, l, h])[None, None, None]
+        ref = O.compress(Qu, Ku, Vu, nov_h[b:b + 1], k=cfg.k, T=cfg.T, pool_w=cfg.w)
+        gu.assert_scores_close(sh, ref["scores"][0, 0, 0], cfg.G * cfg.P)
+        gu.assert_keep_matches(kh, ref["keep_idx"][0, 0, 0], ref["scores"][0, 0, 0], cfg.k)
+        print(f"  unit {(b, l, h)} matches the oracle", flush=True)
+
+
 def test_streaming_pot_teacher_forced():
     """Continual distillation (Sec. 3.2): a context streamed through a small pot in chunks; every compression is
     checked against the oracle run on the pot's own state just before the call (K, V, carried per-head novelty)."""
