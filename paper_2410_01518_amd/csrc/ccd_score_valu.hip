@@ -20,14 +20,21 @@ template <typename T, int HD>
 __global__ __launch_bounds__(kThreads) void stats_valu_kernel(Dims D, ScorePlan pl, const T* __restrict__ Q,
                                                               const T* __restrict__ K, float2* __restrict__ part) {
   __shared__ float4 Ks[kTokTile][HD / 4];
+  __shared__ float2 red[kThreads];
   const int slice = blockIdx.x % pl.n_slices1, unit = D.unit0 + blockIdx.x / pl.n_slices1, tid = threadIdx.x;
   const UnitIdx ui = decode_unit(D, unit);
   const T* Ku = K + kv_offset(D, ui);
   const int t0 = slice * pl.slice1;
   const int t1 = min(D.n, t0 + pl.slice1);
 
-  for (int q0 = 0; q0 < D.GP; q0 += kThreads) {
-    const int q = q0 + tid;
+  // Fewer query rows than threads: the threads form kThreads / qw groups that share the tokens of a tile
+  // (group g takes the tokens g, g + groups, ...) and merge their (m, Z) pairs at the end of the slice.
+  int qw = kThreads;
+  while (qw / 2 >= D.GP) qw >>= 1;
+  const int groups = kThreads / qw, grp = tid / qw, ql = tid - grp * qw;
+
+  for (int q0 = 0; q0 < D.GP; q0 += qw) {
+    const int q = q0 + ql;
     const bool active = q < D.GP;
     float4 qr[HD / 4];
     if (active) {
@@ -51,7 +58,8 @@ __global__ __launch_bounds__(kThreads) void stats_valu_kernel(Dims D, ScorePlan 
       __syncthreads();
       const int nt = min(kTokTile, t1 - tt);
       if (active) {
-        for (int t = max(0, first - tt); t < nt; ++t) {
+        for (int t = grp; t < nt; t += groups) {
+          if (tt + t < first) continue;
           float acc = 0.f;
 #pragma unroll
           for (int c = 0; c < HD / 4; ++c) {
@@ -71,7 +79,21 @@ __global__ __launch_bounds__(kThreads) void stats_valu_kernel(Dims D, ScorePlan 
         }
       }
     }
-    if (active) part[((int64_t)unit * pl.n_slices1 + slice) * D.GP + q] = make_float2(m, Z);
+    if (groups > 1) {            // (uniform over the workgroup)
+      __syncthreads();
+      red[tid] = make_float2(m, Z);
+      __syncthreads();
+      if (grp == 0) {
+        for (int g = 1; g < groups; ++g) m = fmaxf(m, red[g * qw + ql].x);
+        float z = 0.f;
+        for (int g = 0; g < groups; ++g) {
+          const float2 v = red[g * qw + ql];
+          if (v.y > 0.f) z += v.y * fast_exp2(v.x - m);     // (a group that saw no token holds (-inf, 0))
+        }
+        Z = z;
+      }
+    }
+    if (active && grp == 0) part[((int64_t)unit * pl.n_slices1 + slice) * D.GP + q] = make_float2(m, Z);
   }
 }
 
