@@ -82,7 +82,7 @@ def test_stress_config_full_size_drawn_on_device():
     """The whole stress configuration in one call: 4 sequences x 80 layers x 8 KV heads = 2560 units, pot 32768 -> 4096,
     1024 query rows per unit; K and V are 21.5 GB each (element offsets beyond 2^32, a 3 GB workspace).  The inputs
     are drawn on the device with the recipe of the configuration (keys N(0,1) x sqrt(min(z_t, 64)), z_t ~ Zipf(1.1) per
-    (sequence, token)); the oracle scores sampled units, the selection is replayed on sampled units, and every unit's
+    (sequence, token)); the oracle scores 16 sampled units, the selection is replayed on them, and every unit's
     keep_idx and compacted rows are checked on the device."""
     cfg = synth.CONFIGS["c5"]
     free = torch.cuda.mem_get_info()[0]
@@ -125,7 +125,7 @@ def test_stress_config_full_size_drawn_on_device():
             assert torch.equal(got[..., cfg.k:, :], src[..., cfg.k:, :])
     print("  all units checked on the device", flush=True)
     # sampled units: replay of the selection, fp64 oracle
-    units = _sample_units(cfg, 2, seed=2)
+    units = _sample_units(cfg, 14, seed=2)
     nov_h = gu.to_host(nov)
     for (b, l, h) in units:
         sh, kh = gu.to_host(scores[b, l, h]), gu.to_host(keep[b, l, h])
@@ -136,6 +136,7 @@ def test_stress_config_full_size_drawn_on_device():
         gu.assert_scores_close(sh, ref["scores"][0, 0, 0], cfg.G * cfg.P)
         gu.assert_keep_matches(kh, ref["keep_idx"][0, 0, 0], ref["scores"][0, 0, 0], cfg.k)
         print(f"  unit {(b, l, h)} matches the oracle", flush=True)
+    assert len(units) >= 16
 
 
 def test_streaming_pot_teacher_forced():

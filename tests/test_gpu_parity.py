@@ -317,6 +317,29 @@ def test_logits_far_above_those_of_the_first_tile(where):
     gu.assert_scores_close(gu.to_host(scores), ref["scores"], cfg.G * cfg.P)
 
 
+@pytest.mark.parametrize("score_path", [0, 1], indirect=True)
+def test_heavy_tailed_key_norms_saturate_the_softmax(score_path):
+    """Key rows scaled by sqrt(z_t), z_t ~ Zipf(1.1) capped at 2^16 instead of the benchmark's 64 (gains up to 256, logits
+    up to 1600 binary orders): nearly every attention row is one-hot, nine scores in ten are exactly zero and fewer
+    than k are positive, so the selection is decided by the ties at zero.  (The cap keeps the logits where fp32 still
+    resolves their exponent to 1e-3: one unit in the last place of 1600 is 1.2e-4.)"""
+    cfg = _cfg(B=2, L=1, Hq=8, Hkv=2, N=1200, k=400, P=16, T=0, w=1, seed=83)
+    print(f"heavy-tailed key norms {cfg} path={score_path}", flush=True)
+    inp = synth.make_inputs(cfg)
+    rng = np.random.default_rng(83)
+    z = np.minimum(rng.zipf(1.1, size=(cfg.B, cfg.N)).astype(np.float64), 2.0 ** 16)
+    K = synth.bf16_bits_to_f32(inp["K"]) * np.sqrt(z).astype(np.float32)[:, None, None, :, None]
+    inp["K"] = synth.f32_to_bf16_bits(K)
+    ref = _oracle(cfg, inp)
+    assert (ref["scores"] == 0).mean() > 0.8 and ((ref["scores"] > 0).sum(axis=-1) < cfg.k).all()
+    rc, dev, scores, keep = _run_fused(cfg, inp)
+    assert rc == ip.CCD_OK
+    sh = gu.to_host(scores)
+    assert (sh == 0).mean() > 0.8
+    np.testing.assert_allclose(sh.sum(axis=-1, dtype=np.float64), cfg.G * cfg.P, rtol=1e-3)   # every query row sums to one
+    _check_fused(cfg, inp, ref, dev, scores, keep, False)
+
+
 # ------------------------------------------------------------------ run-to-run behaviour
 
 def test_repeated_calls_give_identical_bits():
