@@ -96,18 +96,72 @@ __global__ __launch_bounds__(kCpThreads) void compact_novelty_kernel(Dims D, con
 // saves a launch, the drain of a latency-bound grid, and the trip of keep_idx through memory; the compaction part
 // runs as fast as with a workgroup per tensor (measured 88.5 against 89.3 us).
 constexpr int kScUnroll = 2;
+constexpr int kSplitFillWorkgroups = 256;   // one 1024-thread workgroup per compute unit
 
 // ROPE (CR-RoPE, Sec. 3.5): the kernel also writes Krot[j] = rotary embedding at position j of the kept key j, for all
 // j < k (rows that stay where they are included, so every kept K row is read); the pot itself keeps the plain keys.
-template <int KPT, int ROWB, bool ROPE, bool BF16>
+//
+// SPLIT (calls with few units, which leave most of the chip idle): `parts` workgroups per unit.  Each of them runs
+// the whole selection for itself (same inputs, same kept list; only the first writes scores and keep_idx) and then
+// moves its share of the bytes: one tensor (K for even parts, V for odd ones) and one column segment of
+// ROWB / (parts / 2) bytes of every row (at least 128 bytes; the whole row with ROPE, which pairs columns d/2 apart).
+// The shares are disjoint, so the workgroups of a unit need no ordering among themselves.  Carried novelty is not
+// compacted here in this form (its entries are still being read by the other workgroups' selections).
+constexpr int kScSplitUnroll = 4;
+
+template <int KPT, int ROWB, bool ROPE, bool BF16, bool SPLIT>
 __global__ __launch_bounds__(kCpThreads) void select_compact_kernel(Dims D, const float* __restrict__ u,
                                                                     float* novelty, int carry_novelty, float* scores,
                                                                     int32_t* __restrict__ keep_idx, char* Kbuf,
                                                                     char* Vbuf, const float* __restrict__ rope_cos,
-                                                                    const float* __restrict__ rope_sin, char* Krot) {
+                                                                    const float* __restrict__ rope_sin, char* Krot,
+                                                                    int parts) {
   __shared__ TopkShared<kCpThreads> sh;
   __shared__ __attribute__((aligned(16))) float u_stage[KPT * kCpThreads + 2 * kStagePad];
   int32_t* keep_lds = reinterpret_cast<int32_t*>(u_stage);
+  if constexpr (SPLIT) {
+    const int part = blockIdx.x % parts, unit = D.unit0 + blockIdx.x / parts;
+    finalize_select_body<kCpThreads, KPT, true>(D, unit, u, novelty, part == 0 ? scores : nullptr,
+                                                part == 0 ? keep_idx : nullptr, sh, u_stage, keep_lds);
+    __syncthreads();
+    const bool is_v = part & 1;
+    const int seg = part >> 1, lanes = (ROWB / 16) / (parts >> 1);     // 16-byte lanes per row segment: 8, 16 or 32
+    const int lane_shift = __ffs(lanes) - 1;
+    const int lane_in_row = seg * lanes + (threadIdx.x & (lanes - 1));
+    const int row_in_pass = threadIdx.x >> lane_shift, rows_per_pass = kCpThreads >> lane_shift;
+    const int lane_off = lane_in_row * 16;
+    const int64_t ubytes = kv_offset(D, decode_unit(D, unit)) * (int64_t)(ROWB / D.d);
+    char* tb = (is_v ? Vbuf : Kbuf) + ubytes;
+    char* rb = ROPE ? Krot + ubytes : nullptr;
+    const bool rot = ROPE && !is_v;
+    const int half_d = D.d / 2;
+    for (int base = 0; base < D.k; base += rows_per_pass * kScSplitUnroll) {
+      uint4 a[kScSplitUnroll];
+      bool move[kScSplitUnroll];
+      RopeCoef<ROWB, BF16> coef[ROPE ? kScSplitUnroll : 1];
+#pragma unroll
+      for (int i = 0; i < kScSplitUnroll; ++i) {
+        const int j = base + i * rows_per_pass + row_in_pass;
+        move[i] = false;
+        if (j < D.k) {
+          const int sidx = keep_lds[j];
+          move[i] = sidx != j;
+          if (move[i] || rot) a[i] = load_streaming(tb + (int64_t)sidx * ROWB + lane_off);
+          if (ROPE && rot) coef[i].load(lane_in_row, rope_cos + (int64_t)j * half_d, rope_sin + (int64_t)j * half_d);
+        }
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < kScSplitUnroll; ++i) {
+        const int j = base + i * rows_per_pass + row_in_pass;
+        if (move[i]) store_streaming(tb + (int64_t)j * ROWB + lane_off, a[i]);
+        if (ROPE && rot && j < D.k)
+          store_streaming(rb + (int64_t)j * ROWB + lane_off, rope_lane<ROWB, BF16>(a[i], lane_in_row, coef[ROPE ? i : 0]));
+      }
+    }
+    return;
+  }
   const int unit = D.unit0 + blockIdx.x;
   finalize_select_body<kCpThreads, KPT, true>(D, unit, u, novelty, scores, keep_idx, sh, u_stage, keep_lds);
   __syncthreads();
@@ -206,29 +260,41 @@ __global__ __launch_bounds__(256) void rope_rows_kernel(Dims D, const char* __re
 
 bool select_compact_supported(const Dims& D) { return D.n <= 16 * kCpThreads; }
 
-// pooling + NuC lift + top-k + in-place compaction of K and V; per-head novelty (if given) follows in its own kernel.
+// pooling + NuC lift + top-k + in-place compaction of K and V (and of carried per-head novelty).
 // Krot != nullptr: CR-RoPE of the kept keys on the side (rope_cos / rope_sin: [>= k, d/2] fp32).
+// A launch with so few units that most compute units would stay idle gives every unit 2, 4 or 8 workgroups (see the
+// kernel); carried novelty then follows in a small kernel of its own.
 void launch_select_compact(const Dims& D, const float* u, float* novelty, bool carry_novelty, float* scores,
                            int32_t* keep_idx, void* K, void* V, const float* rope_cos, const float* rope_sin, void* Krot,
                            hipStream_t s) {
   const int rowb = D.d * (D.dtype == 0 ? 4 : 2);
-  const dim3 grid(D.units_run), block(kCpThreads);
-#define CCD_LAUNCH(KPT, RB, ROPE, BF)                                                                                  \
-  hipLaunchKernelGGL((select_compact_kernel<KPT, RB, ROPE, BF>), grid, block, 0, s, D, u, novelty, carry_novelty ? 1 : 0, \
-                     scores, keep_idx, (char*)K, (char*)V, rope_cos, rope_sin, (char*)Krot)
-#define CCD_LAUNCH_RB(KPT, ROPE)                                         \
-  if (rowb == 128) CCD_LAUNCH(KPT, 128, ROPE, true);                      \
-  else if (rowb == 256 && D.dtype == 1) CCD_LAUNCH(KPT, 256, ROPE, true);  \
-  else if (rowb == 256) CCD_LAUNCH(KPT, 256, ROPE, false);                 \
-  else CCD_LAUNCH(KPT, 512, ROPE, false)
+  const int max_parts = Krot != nullptr ? 2 : 2 * (rowb / 128);
+  int parts = 1;
+  while (parts * 2 <= max_parts && (int64_t)D.units_run * parts * 2 <= kSplitFillWorkgroups) parts *= 2;
+  const bool split = parts > 1;
+  const dim3 grid((unsigned)D.units_run * parts), block(kCpThreads);
+#define CCD_LAUNCH(KPT, RB, ROPE, BF, SPLIT)                                                                           \
+  hipLaunchKernelGGL((select_compact_kernel<KPT, RB, ROPE, BF, SPLIT>), grid, block, 0, s, D, u, novelty,                \
+                     (carry_novelty && !SPLIT) ? 1 : 0, scores, keep_idx, (char*)K, (char*)V, rope_cos, rope_sin,        \
+                     (char*)Krot, parts)
+#define CCD_LAUNCH_RB(KPT, ROPE, SPLIT)                                           \
+  if (rowb == 128) CCD_LAUNCH(KPT, 128, ROPE, true, SPLIT);                        \
+  else if (rowb == 256 && D.dtype == 1) CCD_LAUNCH(KPT, 256, ROPE, true, SPLIT);    \
+  else if (rowb == 256) CCD_LAUNCH(KPT, 256, ROPE, false, SPLIT);                   \
+  else CCD_LAUNCH(KPT, 512, ROPE, false, SPLIT)
+#define CCD_LAUNCH_SPLIT(KPT, ROPE)                              \
+  if (split) { CCD_LAUNCH_RB(KPT, ROPE, true); } else { CCD_LAUNCH_RB(KPT, ROPE, false); }
   const bool small = D.n <= 4 * kCpThreads;
   if (Krot == nullptr) {
-    if (small) { CCD_LAUNCH_RB(4, false); } else { CCD_LAUNCH_RB(16, false); }
+    if (small) { CCD_LAUNCH_SPLIT(4, false); } else { CCD_LAUNCH_SPLIT(16, false); }
   } else {
-    if (small) { CCD_LAUNCH_RB(4, true); } else { CCD_LAUNCH_RB(16, true); }
+    if (small) { CCD_LAUNCH_SPLIT(4, true); } else { CCD_LAUNCH_SPLIT(16, true); }
   }
+#undef CCD_LAUNCH_SPLIT
 #undef CCD_LAUNCH_RB
 #undef CCD_LAUNCH
+  if (split && carry_novelty)
+    hipLaunchKernelGGL(compact_novelty_kernel, dim3(D.units_run), block, 0, s, D, keep_idx, novelty);
 }
 
 void launch_rope_rows(const Dims& D, const void* K, const float* rope_cos, const float* rope_sin, int count, void* Krot,
