@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kCpThreads) void compact_novelty_kernel(Dims D, con
   }
 }
 
-// Selection and compaction of one unit in ONE workgroup (ccd_compress, rows of up to 16384 tokens): the kept indices
+// Selection and compaction of one unit in ONE workgroup (ccd_compress, rows of up to 32768 tokens): the kept indices
 // stay in LDS (in the space of the staged score row, which is dead by then) and K and V chunks move together, two
 // 16-byte loads per tensor in flight per thread.  Against a selection kernel followed by a compaction kernel this
 // saves a launch, the drain of a latency-bound grid, and the trip of keep_idx through memory; the compaction part
@@ -258,7 +258,7 @@ __global__ __launch_bounds__(256) void rope_rows_kernel(Dims D, const char* __re
 
 }  // namespace
 
-bool select_compact_supported(const Dims& D) { return D.n <= 16 * kCpThreads; }
+bool select_compact_supported(const Dims& D) { return D.n <= 32 * kCpThreads; }
 
 // pooling + NuC lift + top-k + in-place compaction of K and V (and of carried per-head novelty).
 // Krot != nullptr: CR-RoPE of the kept keys on the side (rope_cos / rope_sin: [>= k, d/2] fp32).
@@ -284,11 +284,11 @@ void launch_select_compact(const Dims& D, const float* u, float* novelty, bool c
   else CCD_LAUNCH(KPT, 512, ROPE, false, SPLIT)
 #define CCD_LAUNCH_SPLIT(KPT, ROPE)                              \
   if (split) { CCD_LAUNCH_RB(KPT, ROPE, true); } else { CCD_LAUNCH_RB(KPT, ROPE, false); }
-  const bool small = D.n <= 4 * kCpThreads;
+  const int kpt = (D.n + kCpThreads - 1) / kCpThreads;
   if (Krot == nullptr) {
-    if (small) { CCD_LAUNCH_SPLIT(4, false); } else { CCD_LAUNCH_SPLIT(16, false); }
+    if (kpt <= 4) { CCD_LAUNCH_SPLIT(4, false); } else if (kpt <= 16) { CCD_LAUNCH_SPLIT(16, false); } else { CCD_LAUNCH_SPLIT(32, false); }
   } else {
-    if (small) { CCD_LAUNCH_SPLIT(4, true); } else { CCD_LAUNCH_SPLIT(16, true); }
+    if (kpt <= 4) { CCD_LAUNCH_SPLIT(4, true); } else if (kpt <= 16) { CCD_LAUNCH_SPLIT(16, true); } else { CCD_LAUNCH_SPLIT(32, true); }
   }
 #undef CCD_LAUNCH_SPLIT
 #undef CCD_LAUNCH_RB

@@ -2,7 +2,7 @@
 // (Sec. 3.3.3 step 2 / App. B "Final Token Selection").  The selection machinery is in ccd_topk.h.
 //
 // finalize_select_kernel: one workgroup of 1024 threads per unit; every thread keeps the scores of its tokens in
-// registers (consecutive tokens for rows of up to 16384 tokens, which are staged in LDS; strided tokens for longer
+// registers (consecutive tokens for rows of up to 32768 tokens, which are staged in LDS; strided tokens for longer
 // rows).  Prefix counts taken in token order give both the lowest-index tie-break and the output slot of every kept
 // token, so keep_idx comes out ascending without a sort.
 #include "ccd_select_body.h"
@@ -12,7 +12,7 @@ namespace ccd {
 namespace {
 
 constexpr int kSelThreads = 1024;
-constexpr int kStageMaxKpt = 16;   // rows of up to 16384 tokens (64 KiB) are staged in LDS for pooling
+constexpr int kStageMaxKpt = 32;   // rows of up to 32768 tokens (128 KiB) are staged in LDS for pooling
 
 template <int KPT>
 __global__ __launch_bounds__(kSelThreads) void finalize_select_kernel(Dims D, const float* __restrict__ u,

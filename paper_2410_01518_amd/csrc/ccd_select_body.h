@@ -174,7 +174,7 @@ __device__ __forceinline__ void finalize_select_body(const Dims& D, int unit, co
     if (BLOCKED) {
       // token order is thread order, then j.  A token's place among the kept ones is the number of larger keys
       // before it plus the number of threshold ties before it, capped at `need`: one scan over the two per-thread
-      // counts packed into one word (blocked ownership is only used for n <= 16384, so both stay below 2^16)
+      // counts packed into one word (blocked ownership is only used for n <= 32768, so both stay below 2^16)
       uint32_t n_gt = 0, n_eq = 0;
 #pragma unroll
       for (int j = 0; j < KPT; ++j) {
