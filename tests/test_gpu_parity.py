@@ -230,9 +230,22 @@ def test_fused_compress_small(per_head, want_scores):
     _check_fused(cfg, inp, ref, dev, scores, keep, per_head)
 
 
-@pytest.mark.parametrize("per_head,N", [(False, 6000), (True, 4100), (False, 16384)])
+@pytest.mark.parametrize("per_head", [False, True])
+def test_fused_compress_many_units(per_head):
+    """More units than half the chip's compute units: one selection + compaction workgroup per unit (calls with
+    fewer units split a unit's rows over several workgroups), novelty shared or carried per head."""
+    cfg = _cfg(B=1, L=17, Hq=16, Hkv=8, P=4, N=520, k=250, T=60, w=5, seed=53)
+    print(f"fused many units per_head={per_head} {cfg}", flush=True)
+    inp = synth.make_inputs(cfg, per_head_novelty=per_head)
+    ref = _oracle(cfg, inp)
+    rc, dev, scores, keep = _run_fused(cfg, inp, per_head=per_head)
+    assert rc == ip.CCD_OK
+    _check_fused(cfg, inp, ref, dev, scores, keep, per_head)
+
+
+@pytest.mark.parametrize("per_head,N", [(False, 6000), (True, 4100), (False, 16384), (True, 20000), (False, 32768)])
 def test_fused_compress_rows_of_several_thousand_tokens(per_head, N):
-    """Rows between 4097 and 16384 tokens: the one-workgroup selection + compaction with 16 tokens per thread."""
+    """Rows between 4097 and 32768 tokens: the one-workgroup selection + compaction with 16 or 32 tokens per thread."""
     cfg = _cfg(B=1, L=1, Hq=4, Hkv=2, P=8, N=N, k=N // 3, T=N // 8)
     print(f"fused N={N} per_head={per_head} {cfg}", flush=True)
     inp = synth.make_inputs(cfg, per_head_novelty=per_head)

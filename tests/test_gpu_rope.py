@@ -74,7 +74,9 @@ FUSED_CASES = [
     dict(d=64, N=513, k=100, P=3, T=10, w=1),                                       # bf16, d 64
     dict(dtype="fp32", d=64, Hq=4, Hkv=4, N=512, k=256, P=16, T=128, w=1),           # fp32 rows of 256 bytes
     dict(dtype="fp32", d=128, N=300, k=299, P=5, T=3, w=3),                          # fp32 rows of 512 bytes, one row dropped
-    dict(B=1, L=1, Hq=2, Hkv=1, d=64, N=17000, k=5000, P=2, T=100, w=7),             # long rows: separate kernels
+    dict(B=1, L=1, Hq=2, Hkv=1, d=64, N=17000, k=5000, P=2, T=100, w=7),             # long rows: 32 tokens per thread
+    dict(B=1, L=1, Hq=2, Hkv=1, d=64, N=33000, k=5000, P=2, T=100, w=7),             # longer rows: separate kernels
+    dict(B=1, L=17, Hq=8, Hkv=8, N=520, k=250, P=4, T=60, w=5),                      # 136 units: one workgroup per unit
 ]
 
 
