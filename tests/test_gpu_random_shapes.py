@@ -36,9 +36,43 @@ def _draw(seed):
     return cfg, pool_mode, per_head, with_cap, window
 
 
+def _draw_wide(seed):
+    """Long rows on a few units (the selection with 16 or 32 tokens per thread, or the separate kernels above 32768
+    tokens), or many units with short rows (one selection + compaction workgroup per unit)."""
+    r = np.random.default_rng(5000 + seed)
+    dtype = "bf16" if r.random() < 0.8 else "fp32"
+    d = int(r.choice([64, 128]))
+    if r.random() < 0.5:
+        Hkv, G, B, L = int(r.choice([1, 2])), int(r.choice([1, 2])), 1, 1
+        N = int(r.integers(4097, 34000 if dtype == "bf16" else 9000))
+    else:
+        Hkv, G, B, L = int(r.choice([4, 8])), int(r.choice([1, 2])), int(r.choice([1, 2, 3])), int(r.integers(4, 20))
+        N = int(r.integers(40, 700))
+    P = int(r.choice([1, 3, 8]))
+    k = int(r.integers(1, N))
+    T = int(r.integers(0, k + 1)) if r.random() < 0.8 else 0
+    w = int(r.choice([1, 3, 5, 7, 9]))
+    pool_mode = int(r.choice([O.POOL_MAX, O.POOL_AVG]))
+    per_head = bool(r.random() < 0.5)
+    with_cap = bool(r.random() < 0.3)
+    window = int(r.integers(max(P, N - 200), N + P + 2)) if r.random() < 0.3 else 0
+    keys = str(r.choice(["normal", "outlier1pct", "zipf"]))
+    cfg = synth.CCDConfig(name=f"w{seed}", B=B, L=L, Hq=Hkv * G, Hkv=Hkv, d=d, N=N, k=k, P=P, T=T, w=w, dtype=dtype, keys=keys,
+                          seed=7000 + seed)
+    return cfg, pool_mode, per_head, with_cap, window
+
+
 @pytest.mark.parametrize("seed", range(32))
 def test_random_shape(seed):
-    cfg, pool_mode, per_head, with_cap, window = _draw(seed)
+    _run(seed, *_draw(seed))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shape_long_rows_or_many_units(seed):
+    _run(seed, *_draw_wide(seed))
+
+
+def _run(seed, cfg, pool_mode, per_head, with_cap, window):
     print(f"random shape {seed}: {cfg} pool_mode={pool_mode} per_head={per_head} with_cap={with_cap} window={window}", flush=True)
     inp = synth.make_inputs(cfg, per_head_novelty=per_head)
     if seed % 5 == 0:                                    # ties and tokens that may not take a NuC slot
