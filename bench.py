@@ -257,6 +257,10 @@ def main() -> int:
     ap.add_argument("--per-head-novelty", action="store_true",
                     help="novelty carried per (layer, KV head) as in the cycles after the first one: [B, L, Hkv, N] "
                          "instead of [B, N]; it is compacted in place with K and V")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="issue the timed calls round-robin over this many HIP streams (default priority), each with its "
+                         "own workspace: how a server drives the step for several independent sequences; the per-kernel "
+                         "pass stays on one stream")
     ap.add_argument("--window", type=int, default=0,
                     help="sliding attention window in tokens (0 = none), e.g. 4096 for a window as long as the pot")
     ap.add_argument("--aux", choices=["nuc", "cr_rope", "stream", "stress"], default=None,
@@ -331,6 +335,9 @@ def main() -> int:
     ws = ip.alloc_workspace(shape)
     keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream()
+    n_streams = max(1, args.streams)
+    lanes = [(stream, ws, keep)] + [(torch.cuda.Stream(), ip.alloc_workspace(shape), torch.empty_like(keep))
+                                    for _ in range(n_streams - 1)]
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -364,8 +371,9 @@ def main() -> int:
     k_cap_h = synth.cap_keys(cfg) if args.kcat else None
     k_cap = upload(k_cap_h) if args.kcat else None
 
-    def step(i):
+    def step(i, lane=0):
         K, V = pots[i % len(pots)]
+        stream, ws, keep = lanes[lane]
         if args.rope:
             p = i % len(pots)
             rc = ip.ccd_compress_rope(shape, qsets[p % len(qsets) if args.lse else i % len(qsets)], K, V, novs[i % len(novs)],
@@ -380,12 +388,13 @@ def main() -> int:
             rc = ip.ccd_compress(shape, qsets[i % len(qsets)], K, V, novs[i % len(novs)], keep, ws, stream=stream)
         assert rc == ip.CCD_OK, rc
 
+    torch.cuda.synchronize()                             # the inputs were drawn on the default stream
     for i in range(args.warmup):
-        step(args.steps + i)                             # the warm-up calls use the pots behind the timed ones
+        step(args.steps + i, i % n_streams)              # the warm-up calls use the pots behind the timed ones
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i)
+        step(i, i % n_streams)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -455,7 +464,7 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: B{cfg.B} L{cfg.L} Hq{cfg.Hq} Hkv{cfg.Hkv} d{cfg.d} N{cfg.N}->k{cfg.k} "
                                f"P{cfg.P} T{cfg.T} pool{cfg.w}", "ring": [len(pots), len(qsets), len(novs)], "score_path": args.score_path,
                    "cap_keys_in_softmax": bool(args.kcat), "window": args.window,
-                   "per_head_novelty": bool(args.per_head_novelty), "lse_given": bool(args.lse)},
+                   "per_head_novelty": bool(args.per_head_novelty), "lse_given": bool(args.lse), "streams": n_streams},
         "call_hbm": {"algorithmic_bytes": ab["call"], "achieved_GBps": call_gbps, "frac_of_peak": call_gbps / HBM_PEAK_GBPS},
         "stage_avg_us": stage_avg_us, "moved_row_fraction": moved,
         "roofline": roof, "roofline_other_kernels": by_kernel,
