@@ -255,6 +255,61 @@ def test_fused_compress_rows_of_several_thousand_tokens(per_head, N):
     _check_fused(cfg, inp, ref, dev, scores, keep, per_head)
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp32", 64)])
+@pytest.mark.parametrize("fused", [True, False])
+def test_strided_layouts(dtype, d, fused):
+    """K and V stored head-major with padding rows ([B, Hkv + 1, L, n_cap + 8, d], seen as [B, L, Hkv, n_cap, d] through
+    strides: layer stride below head stride), Q_cat cut out of a longer prompt buffer, per-head novelty with padded
+    rows: results as for dense tensors, and nothing outside the views is written."""
+    cfg = _cfg(B=2, L=3, Hq=6, Hkv=3, d=d, dtype=dtype, N=600, k=250, P=7, T=90, w=5, seed=61)
+    print(f"strided {cfg} fused={fused}", flush=True)
+    inp = synth.make_inputs(cfg, per_head_novelty=True)
+    ref = _oracle(cfg, inp)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    fill = 3.0
+
+    def embed(x, extra_heads, extra_rows):            # [B, L, H, n, d] -> view of a [B, H + eh, L, n + er, d] buffer
+        B, L, H, n, dd = x.shape
+        big = torch.full((B, H + extra_heads, L, n + extra_rows, dd), fill, dtype=tdt, device="cuda")
+        view = big.permute(0, 2, 1, 3, 4)[:, :, :H, :n]
+        view.copy_(gu.to_dev(x))
+        return big, view
+
+    Kbig, K = embed(inp["K"], 1, 8)
+    Vbig, V = embed(inp["V"], 1, 8)
+    Qbig = torch.full((cfg.B, cfg.L, cfg.Hq, cfg.P + 3, d), fill, dtype=tdt, device="cuda")
+    Q = Qbig[:, :, :, :cfg.P]
+    Q.copy_(gu.to_dev(inp["Q_cat"]))
+    novbig = torch.full((cfg.B, cfg.L, cfg.Hkv, cfg.N + 5), fill, dtype=torch.float32, device="cuda")
+    nov = novbig[..., :cfg.N]
+    nov.copy_(gu.to_dev(inp["novelty"]))
+    assert not K.is_contiguous() and not Q.is_contiguous() and not nov.is_contiguous()
+    shape = ip.make_shape(Q, K, nov, k=cfg.k, T=cfg.T, pool_w=cfg.w)
+    assert shape.kv_stride_l < shape.kv_stride_h
+    ws = ip.alloc_workspace(shape)
+    scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
+    keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device="cuda")
+    if fused:
+        assert ip.ccd_compress(shape, Q, K, V, nov, keep, ws, scores=scores) == ip.CCD_OK
+    else:
+        assert ip.ccd_score(shape, Q, K, nov, scores, ws) == ip.CCD_OK
+        assert ip.ccd_select(shape, scores, keep) == ip.CCD_OK
+        assert ip.ccd_compact(shape, K, V, keep, K, V, nov) == ip.CCD_OK
+    torch.cuda.synchronize()
+    sh, kh = gu.to_host(scores), gu.to_host(keep)
+    gu.assert_scores_close(sh, ref["scores"], cfg.G * cfg.P)
+    gu.assert_keep_matches(kh, ref["keep_idx"], ref["scores"], cfg.k)
+    np.testing.assert_array_equal(kh, gu.replay_select(sh, cfg.k))
+    idx = kh.astype(np.int64)
+    np.testing.assert_array_equal(gu.to_host(K.contiguous())[..., :cfg.k, :], np.take_along_axis(inp["K"], idx[..., None], axis=3))
+    np.testing.assert_array_equal(gu.to_host(V.contiguous())[..., :cfg.k, :], np.take_along_axis(inp["V"], idx[..., None], axis=3))
+    np.testing.assert_array_equal(gu.to_host(nov.contiguous())[..., :cfg.k], np.take_along_axis(inp["novelty"], idx, axis=3))
+    # the padding: the extra head, the extra rows, the rest of the prompt buffer, the novelty tails
+    for big in (Kbig, Vbig):
+        assert bool((big[:, cfg.Hkv:] == fill).all()) and bool((big[:, :, :, cfg.N:] == fill).all())
+    assert bool((Qbig[:, :, :, cfg.P:] == fill).all()) and bool((novbig[..., cfg.N:] == fill).all())
+
+
 def test_not_full_pot_is_left_untouched():
     cfg = _cfg()
     inp = synth.make_inputs(cfg)
