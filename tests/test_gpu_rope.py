@@ -123,6 +123,55 @@ def test_compress_with_cr_rope(case, per_head):
     print(f"  units with the oracle's keep_idx: {same}/{cfg.units}", flush=True)
 
 
+@pytest.mark.parametrize("stand_alone", [False, True])
+def test_cr_rope_on_strided_layouts(stand_alone):
+    """K, V and K_rot stored head-major with padding rows and seen through strides (K_rot has K's layout): the rotated
+    rows land at the right places and the padding stays as it was."""
+    cfg = synth.CCDConfig(name="t", B=2, L=3, Hq=6, Hkv=3, d=128, N=500, k=200, P=5, T=60, w=3, dtype="bf16", keys="normal", seed=37)
+    print(f"rope strided stand_alone={stand_alone} {cfg}", flush=True)
+    inp = synth.make_inputs(cfg)
+    cos, sin = O.rope_tables(cfg.k, cfg.d)
+    fill = 3.0
+
+    def embed(x):
+        B, L, H, n, dd = x.shape
+        big = torch.full((B, H + 1, L, n + 8, dd), fill, dtype=torch.bfloat16, device="cuda")
+        view = big.permute(0, 2, 1, 3, 4)[:, :, :H, :n]
+        if x is not None:
+            view.copy_(gu.to_dev(x))
+        return big, view
+
+    Kbig, K = embed(inp["K"])
+    Vbig, V = embed(inp["V"])
+    Rbig, Krot = embed(inp["K"])
+    Krot.fill_(7.0)
+    Q, nov = gu.to_dev(inp["Q_cat"]), gu.to_dev(inp["novelty"])
+    shape = ip.make_shape(Q, K, nov, k=cfg.k, T=cfg.T, pool_w=cfg.w)
+    tc, ts = torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda()
+    if stand_alone:
+        assert ip.ccd_cr_rope(shape, K, tc, ts, cfg.k, Krot) == ip.CCD_OK
+        torch.cuda.synchronize()
+        Kh = inp["K"]
+    else:
+        ws = ip.alloc_workspace(shape)
+        keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device="cuda")
+        assert ip.ccd_compress_rope(shape, Q, K, V, nov, keep, tc, ts, Krot, ws) == ip.CCD_OK
+        torch.cuda.synchronize()
+        kh = gu.to_host(keep)
+        ref = O.compress(inp["Q_cat"], inp["K"], inp["V"], inp["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w)
+        gu.assert_keep_matches(kh, ref["keep_idx"], ref["scores"], cfg.k)
+        Kh = gu.to_host(K.contiguous())
+        np.testing.assert_array_equal(Kh[..., :cfg.k, :], np.take_along_axis(inp["K"], kh.astype(np.int64)[..., None], axis=3))
+    got = gu.to_host(Krot.contiguous())
+    for b in range(cfg.B):
+        for l in range(cfg.L):
+            for h in range(cfg.Hkv):
+                _check_rot(got[b, l, h, :cfg.k], Kh[b, l, h, :cfg.k], cos, sin)
+    assert bool((Krot[..., cfg.k:, :] == 7.0).all())
+    for big in (Kbig, Vbig, Rbig):
+        assert bool((big[:, cfg.Hkv:] == fill).all()) and bool((big[:, :, :, cfg.N:] == fill).all())
+
+
 def test_compress_with_cr_rope_on_a_pot_that_is_not_full_writes_nothing():
     cfg = synth.CCDConfig(name="t", B=1, L=1, Hq=2, Hkv=2, d=64, N=256, k=100, P=2, T=10, w=1, dtype="bf16", keys="normal", seed=41)
     inp = synth.make_inputs(cfg)
