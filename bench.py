@@ -41,6 +41,7 @@ def algorithmic_bytes(cfg) -> dict:
         "score_stats": kbytes + qbytes,
         "score_merge": 0,
         "score_prob": kbytes + qbytes + u * N * 4,
+        "score_unit": 2 * kbytes + qbytes + u * N * 4,      # both passes in one kernel: K twice
         "select": u * N * 4 + cfg.B * N * 4 + u * k * 4,
         "compact": 4 * rows + u * k * 4,
         # selection and compaction in one kernel: keep_idx is written once and never read back
@@ -159,8 +160,8 @@ def stress_bench(args, dev, torch, ip, synth) -> int:
     ab = algorithmic_bytes(cfg)
     dom = max(stage_us, key=stage_us.get)
     t = stage_us[dom] * 1e-6
-    if dom in ("score_stats", "score_prob"):
-        roof = {"kernel": dom, "bound": "mfma", "achieved": algorithmic_flops(cfg) / t / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+    if dom in ("score_stats", "score_prob", "score_unit"):
+        roof = {"kernel": dom, "bound": "mfma", "achieved": algorithmic_flops(cfg) * (2 if dom == "score_unit" else 1) / t / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s"}
     else:
         roof = {"kernel": dom, "bound": "hbm", "achieved": ab[dom] / t / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
@@ -244,7 +245,9 @@ def main() -> int:
     ap.add_argument("--ring", type=int, default=0,
                     help="pots cycled through (0: one fresh pot per call of a pass, as far as 60 %% of free HBM allows)")
     ap.add_argument("--config", default="c3")
-    ap.add_argument("--score-path", type=int, default=0, help="0 auto (matrix cores for bf16), 1 vector ALUs")
+    ap.add_argument("--score-path", type=int, default=0,
+                    help="kernels for Eq. 2: 0 automatic, 1 vector ALUs, 2 matrix cores with a workgroup per token slice, "
+                         "3 matrix cores with a workgroup per unit")
     ap.add_argument("--rope", action="store_true",
                     help="time ccd_compress_rope (CR-RoPE of the kept keys written on the side) instead of ccd_compress")
     ap.add_argument("--kcat", action="store_true",
@@ -294,7 +297,6 @@ def main() -> int:
         return stress_bench(args, dev, torch, ip, synth)
     if args.aux is not None:
         return aux_bench(args, cfg, dev, torch, ip, synth)
-    ip.ccd_set_score_path(args.score_path)
 
     def upload(a):
         if a.dtype == np.uint16:
@@ -331,7 +333,7 @@ def main() -> int:
     if args.per_head_novelty:
         novs = novs[1:]
     shape = ip.make_shape(qsets[0], pots[0][0], novs[0], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=ip.CCD_POOL_MAX,
-                          window=args.window)
+                          window=args.window, score_path=args.score_path)
     ws = ip.alloc_workspace(shape)
     keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream()
@@ -431,8 +433,8 @@ def main() -> int:
         ab["call"] += extra
     def roofline_of(stage):
         t = stage_avg_us[stage] * 1e-6
-        if stage in ("score_stats", "score_prob"):
-            flops = algorithmic_flops(cfg)
+        if stage in ("score_stats", "score_prob", "score_unit"):
+            flops = algorithmic_flops(cfg) * (2 if stage == "score_unit" and not args.lse else 1)   # both passes in one kernel
             if args.score_path == 1 or cfg.dtype == "fp32":
                 r = {"kernel": stage, "bound": "alu", "achieved": flops / t / 1e12, "peak": VALU_FP32_PEAK_TFLOPS, "unit": "TFLOP/s"}
             else:

@@ -45,7 +45,8 @@ enum {
   CCD_OK = 0,
   CCD_NOOP = 1,          /* pot not full (n_valid < n_cap) or nothing to drop (n_valid <= k): untouched */
   CCD_EINVAL = -1,       /* NULL pointer, or a shape field out of range                                 */
-  CCD_EUNSUPPORTED = -2, /* d not in {64, 128}, unknown dtype or pool_mode, n_valid > 65536             */
+  CCD_EUNSUPPORTED = -2, /* d not in {64, 128}, unknown dtype or pool_mode, n_valid > 65536, a matrix-  */
+                         /* core score_path for fp32, a window hiding > 2048 tokens of a bf16 cache     */
   CCD_EALIGN = -3,       /* pointer or stride not 16-byte aligned                                       */
   CCD_EWORKSPACE = -4,   /* workspace NULL, misaligned or smaller than ccd_workspace_bytes()            */
   CCD_ELAUNCH = -5       /* the HIP runtime refused a kernel launch                                    */
@@ -53,6 +54,7 @@ enum {
 
 enum { CCD_FP32 = 0, CCD_BF16 = 1 };
 enum { CCD_POOL_NONE = 0, CCD_POOL_MAX = 1, CCD_POOL_AVG = 2 };
+enum { CCD_PATH_AUTO = 0, CCD_PATH_VALU = 1, CCD_PATH_MFMA_SLICES = 2, CCD_PATH_MFMA_UNIT = 3 };
 
 typedef struct {
   int32_t B, L, Hq, Hkv, d;   /* sequences, layers, query heads, KV heads (Hq % Hkv == 0), head dim      */
@@ -70,7 +72,10 @@ typedef struct {
                               /* token i at n_valid + i; a query at position p sees the keys at          */
                               /* p-window+1 .. p only.  window >= P when set; bf16 caches: at most 2048  */
                               /* tokens may be hidden from the last CaP token (CCD_EUNSUPPORTED beyond). */
-  int32_t reserved;           /* must be 0                                                               */
+  int32_t score_path;         /* kernels for Eq. 2: CCD_PATH_AUTO (0) unless two paths are to be compared:       */
+                              /* CCD_PATH_VALU vector ALUs; bf16 caches only: CCD_PATH_MFMA_SLICES matrix cores, */
+                              /* a workgroup per token slice; CCD_PATH_MFMA_UNIT matrix cores, a workgroup per   */
+                              /* unit.  All give the same scores up to fp32 rounding order.                      */
   int64_t kv_stride_b, kv_stride_l, kv_stride_h;    /* K, V: [B, L, Hkv, n_cap, d], strides in elements */
   int64_t q_stride_b, q_stride_l, q_stride_h;       /* Q_cat: [B, L, Hq, P, d]                          */
   int64_t nov_stride_b, nov_stride_l, nov_stride_h; /* novelty fp32: [B, n] shared by layers and heads  */
@@ -169,11 +174,8 @@ CCD_API int ccd_score_lse(const ccd_shape_t* shape, const void* Q_cat, const voi
 CCD_API int ccd_compress_lse(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, const float* lse, float* novelty,
                      float* scores_opt, int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Process-wide choice of kernels: 0 = automatic (bf16: matrix cores; fp32: vector ALUs), 1 = vector ALUs
- * everywhere.  Meant for profiling one path against the other; returns CCD_EINVAL for any other value. */
-CCD_API int ccd_set_score_path(int path);
-
-/* Per-kernel timing of ccd_compress for benchmarks (host-side aid, off by default).  While enabled, each
+/* Per-kernel timing of ccd_compress for benchmarks: a host-side aid, off by default, and the only state the library
+ * keeps between calls (process-wide: enable it from one thread, for calls on one stream).  While enabled, each
  * kernel of ccd_compress is bracketed by two HIP events on the stream it runs on (events are created on demand
  * and reused; nothing else changes).  ccd_profile_collect waits for the recorded
  * events, adds up the elapsed milliseconds per stage into stage_ms[ccd_profile_stages()] (host array) and stores

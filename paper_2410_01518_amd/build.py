@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -9,7 +10,13 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libinfinipot.so")
-SOURCES = ["infinipot_api.hip", "ccd_score_valu.hip", "ccd_score_mfma.hip", "ccd_select.hip", "ccd_compact.hip", "ccd_nuc.hip"]
+SOURCES = ["infinipot_api.hip", "ccd_score_valu.hip", "ccd_score_mfma.hip", "ccd_score_unit.hip", "ccd_select.hip", "ccd_compact.hip",
+           "ccd_nuc.hip"]
+# ccd_score_unit.hip keeps its query fragments at fixed places in the accumulation registers (named in its inline
+# assembly): the compiler must put nothing of its own there, so matrix-instruction results go to vector registers and
+# the generated code is checked for accumulation registers outside the assembly statements.
+SOURCE_FLAGS = {"ccd_score_unit.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+ACC_REGISTERS_RESERVED = {"ccd_score_unit.hip"}
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
 
@@ -21,6 +28,29 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
+_ACC_REG = re.compile(r"(?<![A-Za-z0-9_.$])a(\[\d+(:\d+)?\]|\d+)(?![A-Za-z0-9_])")
+
+
+def check_acc_registers_untouched(asm_path: str) -> None:
+    """Fails if compiler-generated code (outside inline assembly) names an accumulation register, or spills."""
+    in_asm = False
+    bad = []
+    with open(asm_path) as f:
+        for n, line in enumerate(f, 1):
+            if ";;#ASMSTART" in line:
+                in_asm = True
+            elif ";;#ASMEND" in line:
+                in_asm = False
+            elif not in_asm:
+                code = line.split(";")[0]
+                if code.lstrip().startswith("."):
+                    continue
+                if _ACC_REG.search(code):
+                    bad.append(f"{n}: {line.rstrip()}")
+    if bad:
+        raise RuntimeError(f"{asm_path}: the compiler uses accumulation registers that the kernel reserves:\n" + "\n".join(bad[:10]))
+
+
 def build_library(verbose: bool = True, extra_flags=()) -> str:
     """Compiles every kernel source and links the shared library; returns its path."""
     hipcc = _hipcc()
@@ -29,7 +59,15 @@ def build_library(verbose: bool = True, extra_flags=()) -> str:
 
     def compile_one(src):
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        flags = [*FLAGS, *SOURCE_FLAGS.get(src, []), *extra_flags]
+        if src in ACC_REGISTERS_RESERVED:
+            asm = os.path.join(objdir, src.replace(".hip", ".s"))
+            r = subprocess.run([hipcc, *flags, "-S", "--cuda-device-only", os.path.join(CSRC, src), "-o", asm],
+                               capture_output=True, text=True)
+            if r.returncode != 0:
+                raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")
+            check_acc_registers_untouched(asm)
+        cmd = [hipcc, *flags, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")

@@ -17,6 +17,7 @@ struct Dims {
   int units;    // B * L * Hkv
   int unit0, units_run;   // the range of units one launch covers (a call may be split into chunks)
   float scale_log2;  // logit scale times log2(e): probabilities are computed with exp2
+  int score_path;    // the caller's choice of kernels for Eq. 2 (CCD_PATH_*), read by the host-side plan only
   // sliding attention window (0 = none): CaP token i sees cached token t iff t >= win_off + i; tokens below `head`
   // (a multiple of 32, at most n) are hidden from some CaP token, the others are seen by all
   int window, win_off, head;
@@ -34,6 +35,7 @@ struct ScorePlan {
   int cap_block;  // 1 (vector-ALU path): `part` also holds the statistics of the CaP keys' block (causal Eq. 2)
   int head_block; // 1 (matrix-core path): `part` also holds the statistics of the windowed head (sliding window)
   int lse_given;  // 1: the caller handed in the natural-log-sum-exp of every query row: no statistics pass
+  int unit_kernel;  // 1 (matrix-core path): both passes in one kernel, one workgroup per unit (launch_score_unit)
 };
 
 ScorePlan plan_score(const Dims& D);
@@ -58,6 +60,12 @@ void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const 
 // then); else written when pl.head_block: the final log2-sum-exp per query, for launch_head_prob_mfma
 void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const void* K_cap,
                       const float2* part, float* u, float* lse_io, hipStream_t s);
+// Both passes in one kernel, one workgroup per unit (bf16, any shape; it pays when the units fill the chip round by
+// round).  Same roles of K_cap, lse_io and the windowed head's entry of `part` as in launch_prob_mfma; `part` is not
+// used otherwise.
+bool score_unit_supported(const Dims& D);
+void launch_score_unit(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const void* K_cap,
+                       const float2* part, float* u, float* lse_io, hipStream_t s);
 // Sliding attention window on the matrix-core path: the first D.head tokens are hidden from some CaP tokens and are
 // left out of the two passes above.  launch_head_stats_mfma (before pass 2) leaves their (max, sum) statistics per
 // query in the extra entry of `part` (pl.head_block must be 1); launch_head_prob_mfma (after pass 2) writes

@@ -1,0 +1,451 @@
+// Representative score of Eq. 2 for bf16 caches, one workgroup per unit: both passes in one kernel.
+//
+// The slice kernels of ccd_score_mfma.hip share every K tile among the four waves of a workgroup through LDS (each
+// wave owns 64 query rows), and the traffic that goes with it - DMA into the ring, eight fragment reads per wave and
+// tile, a barrier per batch - costs more than the arithmetic hides.  Here the roles are turned round: a wave owns a
+// quarter of the unit's TOKENS and all 256 query rows of a sweep.  The fragments of the 256 query rows (256 registers
+// per lane) stay in the accumulation registers for the whole unit - matrix instructions read their operands from
+// there directly - and the wave's own K tiles come straight from global memory into vector registers, two tiles
+// ahead of their use.  No LDS on the K path, no barrier, no wave ever waits for another one inside a pass.  One
+// workgroup per compute unit (each lane holds 512 registers).
+//
+// Because one workgroup sees all tokens of its unit, the statistics of pass 1 change hands through LDS: pass 2
+// follows in the same kernel, the per-slice statistics buffer and the second launch are not needed.
+//
+//   pass 1  D[token][query] = Kfrag x Qfrag: a lane owns one query row of each of the eight 32-row blocks and adds
+//           2^((x - reference) c) of its 16 token rows to that row's sum (fixed reference per wave and row: the maximum
+//           over the wave's first tile; a sum that leaves the fp32 range makes the wave redo its tokens with a
+//           running maximum);
+//   merge   the four waves' (reference, sum) pairs, the CaP keys' block (causal variant) and the windowed head become
+//           one log2-sum-exp per query row;
+//   pass 2  D[query][token] = Qfrag x Kfrag: a lane owns one token and adds 2^(x c - lse2[query]) over the 16 query
+//           rows of each accumulator; the negated lse2 values of a block pair are re-read from LDS (two addresses per
+//           wave: a broadcast) one step ahead.  Tiles are walked backwards: what pass 1 read last is still cached.
+//
+// Steps are software pipelined inside a wave: the 16 MFMAs of one (tile, block pair) are issued between the ALU
+// instructions that consume the accumulators of the step before.  Compiled with the VGPR form of the matrix
+// instructions (results land in vector registers, where the ALU reads them; the query fragments are pinned to the
+// accumulation registers).
+#include <type_traits>
+
+#include "ccd_score_mfma.h"
+
+namespace ccd {
+
+namespace {
+
+constexpr int kUPairs = 4;                    // pairs of 32-query blocks per sweep
+constexpr int kUQ = kUPairs * kQB * 32;       // query rows per sweep: 256
+static_assert(kQB == 2, "a step covers two query blocks");
+
+template <int HD>
+struct UnitLds {
+  float2 stat[4][kUQ];     // per wave: (max2, sum) of every query row of the sweep over the wave's tokens
+  float neg_lse[kUQ];      // -log2-sum-exp per query row of the sweep
+};
+
+// fragments of one 32-token tile, straight from global memory: lane (col, half) holds elements 16 ks + 8 half .. + 7
+// of token row t_tile + col (rows past t_last re-read row t_last: masked in pass 1, never stored in pass 2)
+template <int HD>
+__device__ __forceinline__ void load_k_tile(bf16x8 (&a)[HD / 16], const uint16_t* __restrict__ Ku, int t_tile, int t_last,
+                                            int col, int half) {
+  const uint16_t* p = Ku + (int64_t)min(t_tile + col, t_last) * HD + half * 8;
+#pragma unroll
+  for (int ks = 0; ks < HD / 16; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(p + ks * 16);
+}
+
+// The matrix instructions are written out, with the query fragments at fixed places in the accumulation registers:
+// fragment (pair p, block qb, k-step ks) of the sweep lives in a[4 f .. 4 f + 3], f = (p kQB + qb) KS + ks, for the
+// whole sweep.  (Left to the compiler, these 256 registers per lane wander between the two register files and push
+// the K fragments and accumulators into scratch memory.)  K fragments and results are ordinary values in vector
+// registers, where the ALU reads the results.  PASS 1: D[token][query] = K x Q, PASS 2: D[query][token] = Q x K.
+// The compiler does not know what these statements are and keeps no distance between them and the readers of their
+// results.  The rule kept by hand: a result is read by an ALU instruction only after two more matrix instructions
+// have been issued behind the one that produced it (pipelined steps: the order of every step is fixed by scheduling
+// barriers), or after mma_results_ready().
+#define CCD_ALL_ACC_REGISTERS "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15", "a16", "a17", "a18", "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31", "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47", "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", "a62", "a63", "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79", "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95", "a96", "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111", "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127", "a128", "a129", "a130", "a131", "a132", "a133", "a134", "a135", "a136", "a137", "a138", "a139", "a140", "a141", "a142", "a143", "a144", "a145", "a146", "a147", "a148", "a149", "a150", "a151", "a152", "a153", "a154", "a155", "a156", "a157", "a158", "a159", "a160", "a161", "a162", "a163", "a164", "a165", "a166", "a167", "a168", "a169", "a170", "a171", "a172", "a173", "a174", "a175", "a176", "a177", "a178", "a179", "a180", "a181", "a182", "a183", "a184", "a185", "a186", "a187", "a188", "a189", "a190", "a191", "a192", "a193", "a194", "a195", "a196", "a197", "a198", "a199", "a200", "a201", "a202", "a203", "a204", "a205", "a206", "a207", "a208", "a209", "a210", "a211", "a212", "a213", "a214", "a215", "a216", "a217", "a218", "a219", "a220", "a221", "a222", "a223", "a224", "a225", "a226", "a227", "a228", "a229", "a230", "a231", "a232", "a233", "a234", "a235", "a236", "a237", "a238", "a239", "a240", "a241", "a242", "a243", "a244", "a245", "a246", "a247", "a248", "a249", "a250", "a251", "a252", "a253", "a254", "a255"
+
+// every accumulation register belongs to the fragments from here on (the clobber list also makes the kernel claim them)
+__device__ __forceinline__ void claim_acc_registers() { asm volatile("" ::: CCD_ALL_ACC_REGISTERS); }
+
+template <int F>
+__device__ __forceinline__ void store_q_frag(const bf16x8& q) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 w = __builtin_bit_cast(u32x4, q);
+  asm volatile("v_accvgpr_write_b32 a[%4], %0\n\tv_accvgpr_write_b32 a[%5], %1\n\t"
+               "v_accvgpr_write_b32 a[%6], %2\n\tv_accvgpr_write_b32 a[%7], %3"
+               :: "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "n"(4 * F), "n"(4 * F + 1), "n"(4 * F + 2), "n"(4 * F + 3)
+               : CCD_ALL_ACC_REGISTERS);
+}
+
+// F: index of the query fragment
+template <int PASS, int F>
+__device__ __forceinline__ void mma_first(floatx16& d, const bf16x8& k) {
+  if (PASS == 1) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, a[%2:%3], 0" : "=&v"(d) : "v"(k), "n"(4 * F), "n"(4 * F + 3) : CCD_ALL_ACC_REGISTERS);
+  else           asm volatile("v_mfma_f32_32x32x16_bf16 %0, a[%2:%3], %1, 0" : "=&v"(d) : "v"(k), "n"(4 * F), "n"(4 * F + 3) : CCD_ALL_ACC_REGISTERS);
+}
+template <int PASS, int F>
+__device__ __forceinline__ void mma_next(floatx16& d, const bf16x8& k) {
+  if (PASS == 1) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, a[%2:%3], %0" : "+v"(d) : "v"(k), "n"(4 * F), "n"(4 * F + 3) : CCD_ALL_ACC_REGISTERS);
+  else           asm volatile("v_mfma_f32_32x32x16_bf16 %0, a[%2:%3], %1, %0" : "+v"(d) : "v"(k), "n"(4 * F), "n"(4 * F + 3) : CCD_ALL_ACC_REGISTERS);
+}
+// 24 idle issue cycles: more than the 8 passes of the last matrix instruction need to write their result
+__device__ __forceinline__ void mma_results_ready(floatx16 (&acc)[kQB]) {
+  asm volatile("s_nop 15\n\ts_nop 7" : "+v"(acc[0]), "+v"(acc[1]));
+}
+
+// compile-time loop: f(integral_constant<int, I>) for I = 0 .. N - 1
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+// logits of one tile against block pair P, not overlapped with anything (first tile, ragged tile, careful redo)
+template <int HD, int PASS, int P>
+__device__ __forceinline__ void logits_now(floatx16 (&acc)[kQB], const bf16x8 (&ak)[HD / 16]) {
+  constexpr int KS = HD / 16;
+  static_for<0, 2 * KS>([&](auto I) {
+    constexpr int i = decltype(I)::value, ks = i / 2, qb = i % 2, F = (P * kQB + qb) * KS + ks;
+    if constexpr (ks == 0) mma_first<PASS, F>(acc[qb], ak[0]);
+    else                   mma_next<PASS, F>(acc[qb], ak[ks]);
+  });
+  mma_results_ready(acc);
+}
+
+// One pipelined step: the 2 KS matrix instructions of (tile, block pair P) into `nxt`, and between them the ALU work
+// on the accumulators of the step before, cut into 2 KS chunks.  chunk(j) runs behind matrix instruction j + 1 (the
+// last two behind the last one): the results it reads - block 0 in the first half of the chunks, block 1 in the
+// second - were produced at least three matrix instructions earlier.
+template <int HD, int PASS, int P, class Chunk>
+__device__ __forceinline__ void pipelined_step(floatx16 (&nxt)[kQB], const bf16x8 (&ak)[HD / 16], Chunk&& chunk) {
+  constexpr int KS = HD / 16, NM = 2 * KS;
+  __builtin_amdgcn_sched_barrier(0);
+  static_for<0, NM>([&](auto I) {
+    constexpr int i = decltype(I)::value, ks = i / 2, qb = i % 2, F = (P * kQB + qb) * KS + ks;
+    if constexpr (ks == 0) mma_first<PASS, F>(nxt[qb], ak[0]);
+    else                   mma_next<PASS, F>(nxt[qb], ak[ks]);
+    if constexpr (i >= 1) chunk(i - 1);
+    if constexpr (i == NM - 1) chunk(NM - 1);
+    __builtin_amdgcn_sched_barrier(0);
+  });
+}
+
+__device__ __forceinline__ float max16(const floatx16& v) {
+  float t0 = fmaxf(fmaxf(v[0], v[1]), v[2]), t1 = fmaxf(fmaxf(v[3], v[4]), v[5]);
+  float t2 = fmaxf(fmaxf(v[6], v[7]), v[8]), t3 = fmaxf(fmaxf(v[9], v[10]), v[11]);
+  float t4 = fmaxf(fmaxf(v[12], v[13]), v[14]);
+  return fmaxf(fmaxf(fmaxf(t0, t1), fmaxf(t2, t3)), fmaxf(t4, v[15]));
+}
+
+// negated log2-sum-exps of 32-row block `blk` of the sweep for the accumulator rows of this lane: rows
+// 8 j + 4 half + 0..3 of a block are four consecutive floats.  `lane_base` = LDS byte address of neg_lse + 4 half, passed through an empty
+// asm statement by the caller so that the reads are not hoisted out of the tile loop (the table does not change in
+// there, and all 128 values of a lane would be kept in registers)
+typedef __attribute__((address_space(3))) const float* LdsFloats;
+__device__ __forceinline__ void load_neg_lse(float (&nl)[16], uint32_t lane_base, int blk) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) const f32x4* LdsQuad;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const f32x4 v = *reinterpret_cast<LdsQuad>((uintptr_t)(lane_base + (blk * 32 + 8 * j) * 4));
+    nl[4 * j + 0] = v.x; nl[4 * j + 1] = v.y; nl[4 * j + 2] = v.z; nl[4 * j + 3] = v.w;
+  }
+}
+
+template <int HD>
+__global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl, const uint16_t* __restrict__ Q,
+                                                            const uint16_t* __restrict__ K,
+                                                            const float2* __restrict__ part, float* __restrict__ u,
+                                                            const uint16_t* __restrict__ Kcap,
+                                                            float* __restrict__ lse_io) {
+  constexpr int KS = HD / 16;
+  constexpr int NM = 2 * KS;           // matrix instructions and ALU chunks per step
+  constexpr int EPC = 32 / NM;         // accumulator elements per chunk
+  __shared__ UnitLds<HD> sm;
+  const int unit = D.unit0 + blockIdx.x;
+  const UnitIdx ui = decode_unit(D, unit);
+  const uint16_t* Ku = K + kv_offset(D, ui);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63, col = lane & 31, half = lane >> 5;
+  const float c = D.scale_log2;
+  // Tokens [D.head, n) are seen by every query row (all of them without a sliding window); the hidden head is left to
+  // its own two small kernels.  Full 32-token tiles are dealt to the four waves in runs; a ragged last tile goes to the
+  // last wave.
+  const int tb = D.head;
+  const int n_main = D.n - tb;
+  const int full = n_main / kStep;
+  const bool ragged = n_main > full * kStep;
+  const int per = full / 4, rem = full % 4;
+  const int s0 = wave * per + min(wave, rem);
+  const int s1 = s0 + per + (wave < rem ? 1 : 0);            // full tiles [s0, s1) of pass 1
+  const int s1p = s1 + ((ragged && wave == 3) ? 1 : 0);      // pass 2 takes the ragged tile like any other
+  const int t_last = D.n - 1;
+  float* uu = u + (int64_t)unit * D.n;
+  claim_acc_registers();
+
+  for (int qc = 0; qc < D.GP; qc += kUQ) {
+    // fragments of the sweep's query rows into the accumulation registers, a block pair at a time
+    static_for<0, kUPairs>([&](auto Pc) {
+      constexpr int p = decltype(Pc)::value;
+      bf16x8 bw[kQB][KS];
+      load_q_frags<HD>(bw, D, ui, Q, qc + p * (kQB * 32), col, half);
+      static_for<0, kQB * KS>([&](auto Fc) {
+        constexpr int f = decltype(Fc)::value;
+        store_q_frag<p * kQB * KS + f>(bw[f / KS][f % KS]);
+      });
+    });
+
+    bf16x8 a[2][KS];
+    floatx16 accA[kQB], accB[kQB];
+
+    if (!pl.lse_given) {
+      // ---------------- pass 1 ----------------
+      // per (pair, block): -reference * c and the sum in two partial chains
+      float nm[kUPairs][kQB], Z[kUPairs][kQB][2];
+#pragma unroll
+      for (int p = 0; p < kUPairs; ++p)
+#pragma unroll
+        for (int qb = 0; qb < kQB; ++qb) { nm[p][qb] = -kNegHuge * c; Z[p][qb][0] = 0.f; Z[p][qb][1] = 0.f; }
+      float m_ref[kUPairs][kQB], Zs[kUPairs][kQB];       // (reference, sum) pairs once the sweep is done
+      // chunk j of the fold of pair P: elements j EPC .. + EPC - 1 of the 32 accumulator registers
+#define CCD_FOLD1(CUR, P)                                                                 \
+      [&](int j) {                                                                        \
+        float t[EPC];                                                                     \
+        _Pragma("unroll") for (int i = 0; i < EPC; ++i) {                                 \
+          const int e = j * EPC + i;                                                      \
+          t[i] = fmaf(CUR[e / 16][e % 16], c, nm[P][e / 16]);                             \
+        }                                                                                 \
+        _Pragma("unroll") for (int i = 0; i < EPC; ++i) t[i] = fast_exp2(t[i]);           \
+        _Pragma("unroll") for (int i = 0; i < EPC; ++i) {                                 \
+          const int e = j * EPC + i;                                                      \
+          Z[P][e / 16][e & 1] += t[i];                                                    \
+        }                                                                                 \
+        /* the chunk ends here: its sums are demanded now, so its instructions are not  */  \
+        /* sunk behind later matrix instructions (the sums are only read after the tile) */  \
+        asm volatile("" : "+v"(Z[P][(j * EPC) / 16][0]), "+v"(Z[P][(j * EPC) / 16][1]));    \
+      }
+      if (s0 < s1) {
+        load_k_tile<HD>(a[0], Ku, tb + s0 * kStep, t_last, col, half);
+        if (s0 + 1 < s1) load_k_tile<HD>(a[1], Ku, tb + (s0 + 1) * kStep, t_last, col, half);
+        // the wave's first tile fixes the references and is folded without overlap
+        static_for<0, kUPairs>([&](auto Pc) {
+          constexpr int p = decltype(Pc)::value;
+          logits_now<HD, 1, p>(accA, a[0]);
+#pragma unroll
+          for (int qb = 0; qb < kQB; ++qb) nm[p][qb] = -max16(accA[qb]) * c;
+          auto fold = CCD_FOLD1(accA, p);
+#pragma unroll
+          for (int j = 0; j < NM; ++j) fold(j);
+        });
+        if (s0 + 2 < s1) load_k_tile<HD>(a[0], Ku, tb + (s0 + 2) * kStep, t_last, col, half);
+        int s = s0 + 1;
+        if (s < s1) logits_now<HD, 1, 0>(accA, a[1]);
+        // Tile s: accA holds the logits of (s, pair 0).  Steps 1 - 3 take pairs 1 - 3 of tile s from buffer CB, the
+        // last step pair 0 of tile s + 1 from buffer NB; every step folds the pair computed by the step before.  The
+        // buffer of tile s is free after step 3 and takes tile s + 2.
+#define CCD_P1_TILE(CB, NB)                                                                       \
+        pipelined_step<HD, 1, 1>(accB, a[CB], CCD_FOLD1(accA, 0));                            \
+        pipelined_step<HD, 1, 2>(accA, a[CB], CCD_FOLD1(accB, 1));                            \
+        pipelined_step<HD, 1, 3>(accB, a[CB], CCD_FOLD1(accA, 2));                            \
+        if (s + 2 < s1) load_k_tile<HD>(a[CB], Ku, tb + (s + 2) * kStep, t_last, col, half);      \
+        if (s + 1 < s1) {                                                                         \
+          pipelined_step<HD, 1, 0>(accA, a[NB], CCD_FOLD1(accB, 3));                          \
+        } else {                                                                                  \
+          mma_results_ready(accB);                                                                \
+          auto fold = CCD_FOLD1(accB, 3);                                                         \
+          _Pragma("unroll") for (int j = 0; j < NM; ++j) fold(j);                                 \
+        }
+        while (true) {
+          if (s >= s1) break;
+          CCD_P1_TILE(1, 0)
+          ++s;
+          if (s >= s1) break;
+          CCD_P1_TILE(0, 1)
+          ++s;
+        }
+#undef CCD_P1_TILE
+#undef CCD_FOLD1
+        // Did a sum leave the fp32 range (or meet a NaN)?  Then this wave redoes its tokens with a running maximum.
+        bool bad = false;
+        const float inv_c = 1.0f / c;
+#pragma unroll
+        for (int p = 0; p < kUPairs; ++p)
+#pragma unroll
+          for (int qb = 0; qb < kQB; ++qb) {
+            Zs[p][qb] = Z[p][qb][0] + Z[p][qb][1];
+            m_ref[p][qb] = -nm[p][qb] * inv_c;
+            bad |= !(Zs[p][qb] < INFINITY);
+          }
+        if (__any(bad)) {
+#pragma unroll
+          for (int p = 0; p < kUPairs; ++p)
+#pragma unroll
+            for (int qb = 0; qb < kQB; ++qb) { m_ref[p][qb] = kNegHuge; Zs[p][qb] = 0.f; }
+          for (int t = s0; t < s1; ++t) {
+            load_k_tile<HD>(a[0], Ku, tb + t * kStep, t_last, col, half);
+            static_for<0, kUPairs>([&](auto Pc) {
+              constexpr int p = decltype(Pc)::value;
+              logits_now<HD, 1, p>(accA, a[0]);
+              fold_stats<false>(accA, m_ref[p], Zs[p], c, half, kStep);
+            });
+          }
+        } else {
+          // move each reference to where its sum is of order one (Z = mant * 2^e -> reference + e / c): the ragged
+          // tile and the merges expect the magnitudes of a (maximum, sum) pair
+#pragma unroll
+          for (int p = 0; p < kUPairs; ++p)
+#pragma unroll
+            for (int qb = 0; qb < kQB; ++qb) {
+              const int e = __builtin_amdgcn_frexp_expf(Zs[p][qb]);
+              const float m_new = m_ref[p][qb] + (float)e * inv_c;
+              Zs[p][qb] = __builtin_amdgcn_ldexpf(Zs[p][qb], -e) * fast_exp2(fmaf(m_ref[p][qb] - m_new, c, (float)e));
+              m_ref[p][qb] = m_new;
+            }
+        }
+      } else {
+#pragma unroll
+        for (int p = 0; p < kUPairs; ++p)
+#pragma unroll
+          for (int qb = 0; qb < kQB; ++qb) { m_ref[p][qb] = kNegHuge; Zs[p][qb] = 0.f; }
+      }
+      if (ragged && wave == 3) {
+        load_k_tile<HD>(a[0], Ku, tb + full * kStep, t_last, col, half);
+        static_for<0, kUPairs>([&](auto Pc) {
+          constexpr int p = decltype(Pc)::value;
+          logits_now<HD, 1, p>(accA, a[0]);
+          fold_stats<true>(accA, m_ref[p], Zs[p], c, half, n_main - full * kStep);
+        });
+      }
+      // the two lane halves hold different token rows of the same query row: merge, lower half writes
+#pragma unroll
+      for (int p = 0; p < kUPairs; ++p)
+#pragma unroll
+        for (int qb = 0; qb < kQB; ++qb) {
+          const float m_o = __shfl_xor(m_ref[p][qb], 32), z_o = __shfl_xor(Zs[p][qb], 32);
+          const float M = fmaxf(m_ref[p][qb], m_o);
+          const float z = Zs[p][qb] * fast_exp2((m_ref[p][qb] - M) * c) + z_o * fast_exp2((m_o - M) * c);
+          if (half == 0) sm.stat[wave][(p * kQB + qb) * 32 + col] = make_float2(M * c, z);
+        }
+    }
+
+    // ---------------- merge: one log2-sum-exp per query row (thread = row of the sweep) ----------------
+    {
+      float2 cap = make_float2(kNegHuge, 0.f);     // the block of the CaP keys (causal variant), else nothing
+      if (Kcap != nullptr) {
+        const uint16_t* Kc = Kcap + (int64_t)unit * D.P * HD;
+        // the thread's own query row is one of the 2 x 32 rows of block pair `wave`: their fragments once more, in
+        // vector registers this time (the registers of pass 1 are free here)
+        bf16x8 bw[kQB][KS];
+        load_q_frags<HD>(bw, D, ui, Q, qc + wave * (kQB * 32), col, half);
+        cap = cap_block_stats<HD>(D, Kc, bw, qc + wave * (kQB * 32), col, half, c);
+      }
+      __syncthreads();
+      const int q = qc + threadIdx.x;
+      float lse = INFINITY;
+      if (pl.lse_given) {            // the caller's normalisers (natural log): nothing to merge
+        if (q < D.GP) lse = lse_io[(int64_t)unit * D.GP + q] * 1.44269504088896340736f;
+      } else if (q < D.GP) {
+        if (pl.head_block) {         // statistics of the windowed head, left there by its own kernel
+          const float2 hd = part[extra_block_index(D, pl, unit, q)];
+          const float Mh = fmaxf(cap.x, hd.x);
+          cap = make_float2(Mh, cap.y * fast_exp2(cap.x - Mh) + hd.y * fast_exp2(hd.x - Mh));
+        }
+        float M = cap.x;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) M = fmaxf(M, sm.stat[w][threadIdx.x].x);
+        float z = cap.y * fast_exp2(cap.x - M);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const float2 v = sm.stat[w][threadIdx.x];
+          z += v.y * fast_exp2(v.x - M);
+        }
+        lse = M + __log2f(z);
+        if (pl.head_block) lse_io[(int64_t)unit * D.GP + q] = lse;   // for the head's probabilities
+      }
+      sm.neg_lse[threadIdx.x] = -lse;
+      __syncthreads();
+    }
+
+    // ---------------- pass 2: tiles s1p - 1 down to s0 ----------------
+    if (s0 < s1p) {
+      float nl[kQB][16];      // normalisers of the pair being folded; each half is reloaded as soon as it is done with
+      float us[2];
+      uint32_t nl_base = (uint32_t)(uintptr_t)(LdsFloats)sm.neg_lse + 16 * half;
+      // chunk j of the fold of a pair: 2^(x c - lse2) of EPC accumulator elements added to the token's sum; behind
+      // the last chunk of a block, the normalisers of that block of pair NP (the pair folded next) are requested
+#define CCD_FOLD2(CUR, NP)                                                                \
+      [&](int j) {                                                                        \
+        float t[EPC];                                                                     \
+        _Pragma("unroll") for (int i = 0; i < EPC; ++i) {                                 \
+          const int e = j * EPC + i;                                                      \
+          t[i] = fmaf(CUR[e / 16][e % 16], c, nl[e / 16][e % 16]);                        \
+        }                                                                                 \
+        _Pragma("unroll") for (int i = 0; i < EPC; ++i) t[i] = fast_exp2(t[i]);           \
+        _Pragma("unroll") for (int i = 0; i < EPC; ++i) us[i & 1] += t[i];                \
+        asm volatile("" : "+v"(us[0]), "+v"(us[1]));     /* as in pass 1 */               \
+        if (j == NM / 2 - 1) load_neg_lse(nl[0], nl_base, (NP) * kQB);                    \
+        if (j == NM - 1) load_neg_lse(nl[1], nl_base, (NP) * kQB + 1);                    \
+      }
+      int s = s1p - 1;
+      load_k_tile<HD>(a[0], Ku, tb + s * kStep, t_last, col, half);
+      if (s - 1 >= s0) load_k_tile<HD>(a[1], Ku, tb + (s - 1) * kStep, t_last, col, half);
+      load_neg_lse(nl[0], nl_base, 0);
+      load_neg_lse(nl[1], nl_base, 1);
+      logits_now<HD, 2, 0>(accA, a[0]);
+      // Tile s: accA holds the logits of (s, pair 0) and nl the normalisers of pair 0.  Same step structure as pass 1,
+      // walking down; the token's sum is complete after the fourth step and is stored then.
+#define CCD_P2_TILE(CB, NB)                                                                          \
+      us[0] = 0.f; us[1] = 0.f;                                                                      \
+      asm volatile("" : "+v"(nl_base));                                                              \
+      pipelined_step<HD, 2, 1>(accB, a[CB], CCD_FOLD2(accA, 1));                                     \
+      pipelined_step<HD, 2, 2>(accA, a[CB], CCD_FOLD2(accB, 2));                                     \
+      pipelined_step<HD, 2, 3>(accB, a[CB], CCD_FOLD2(accA, 3));                                     \
+      if (s - 2 >= s0) load_k_tile<HD>(a[CB], Ku, tb + (s - 2) * kStep, t_last, col, half);          \
+      if (s - 1 >= s0) {                                                                             \
+        pipelined_step<HD, 2, 0>(accA, a[NB], CCD_FOLD2(accB, 0));                                   \
+      } else {                                                                                       \
+        mma_results_ready(accB);                                                                     \
+        auto fold = CCD_FOLD2(accB, 0);                                                              \
+        _Pragma("unroll") for (int j = 0; j < NM; ++j) fold(j);                                      \
+      }                                                                                              \
+      {                                                                                              \
+        float v = us[0] + us[1];                                                                     \
+        v += __shfl_xor(v, 32);                                                                      \
+        const int t = tb + s * kStep + col;                                                          \
+        if (half == 0 && t < D.n) uu[t] = (qc == 0) ? v : uu[t] + v;                                 \
+      }
+      while (true) {
+        if (s < s0) break;
+        CCD_P2_TILE(0, 1)
+        --s;
+        if (s < s0) break;
+        CCD_P2_TILE(1, 0)
+        --s;
+      }
+#undef CCD_P2_TILE
+#undef CCD_FOLD2
+    }
+    __syncthreads();   // the LDS tables are rewritten by the next sweep
+  }
+}
+
+}  // namespace
+
+// One workgroup per unit pays when the units fill the chip round by round.
+bool score_unit_supported(const Dims& D) { return D.dtype == 1 && (D.d == 64 || D.d == 128); }
+
+void launch_score_unit(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const void* K_cap,
+                       const float2* part, float* u, float* lse_io, hipStream_t s) {
+  dim3 grid((unsigned)D.units_run), block(kMT);
+  if (D.d == 64)
+    hipLaunchKernelGGL((score_unit_kernel<64>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part, u,
+                       (const uint16_t*)K_cap, lse_io);
+  else
+    hipLaunchKernelGGL((score_unit_kernel<128>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part, u,
+                       (const uint16_t*)K_cap, lse_io);
+}
+
+}  // namespace ccd

@@ -13,8 +13,6 @@
 
 namespace ccd {
 
-static int g_score_path = 0;   // 0 auto (matrix cores for bf16), 1 vector ALUs everywhere
-
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -45,7 +43,9 @@ static int check_shape(const ccd_shape_t* s, int need) {
     if (!(s->scale >= 0.f) || isinf(s->scale)) return CCD_EINVAL;
     if (s->pool_mode < CCD_POOL_NONE || s->pool_mode > CCD_POOL_AVG) return CCD_EUNSUPPORTED;
     if (s->pool_w < 1 || s->pool_w % 2 == 0) return CCD_EINVAL;
-    if (s->window < 0 || (s->window > 0 && s->window < s->P) || s->reserved != 0) return CCD_EINVAL;
+    if (s->window < 0 || (s->window > 0 && s->window < s->P)) return CCD_EINVAL;
+    if (s->score_path < CCD_PATH_AUTO || s->score_path > CCD_PATH_MFMA_UNIT) return CCD_EINVAL;
+    if (s->dtype != CCD_BF16 && s->score_path >= CCD_PATH_MFMA_SLICES) return CCD_EUNSUPPORTED;
   }
   if (need & kNeedNov) {
     if (s->T < 0 || s->T > s->k) return CCD_EINVAL;
@@ -69,6 +69,7 @@ static Dims make_dims(const ccd_shape_t* s) {
   D.units_run = D.units;
   const double scale = s->scale > 0.f ? (double)s->scale : 1.0 / sqrt((double)(s->d > 0 ? s->d : 1));
   D.scale_log2 = (float)(scale * 1.4426950408889634074);
+  D.score_path = s->score_path;
   D.window = s->window;
   D.win_off = s->window > 0 ? s->n_valid + 1 - s->window : 0;
   D.head = 0;
@@ -84,18 +85,20 @@ static Dims make_dims(const ccd_shape_t* s) {
 
 constexpr int kMinSlice = 256;   // smallest token slice any plan uses: sizes the per-slice statistics
 
-// workgroup slots of the current device for the score kernels (two workgroups per compute unit)
-static int score_slots() {
-  static int slots = 0;
-  if (slots == 0) {
+// compute units of the current device (asked once; the answer of the first device serves all: one GPU model per node)
+static int compute_units() {
+  static int cus = 0;
+  if (cus == 0) {
     int dev = 0;
     hipDeviceProp_t prop;
-    int cus = 0;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
-    slots = 2 * (cus > 0 ? cus : 256);
+    int n = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n = prop.multiProcessorCount;
+    cus = n > 0 ? n : 256;
   }
-  return slots;
+  return cus;
 }
+// workgroup slots for the slice kernels of the score passes (two workgroups per compute unit)
+static int score_slots() { return 2 * compute_units(); }
 
 // Token slice per workgroup: the longest of 2048 / 1024 / 512 / 256 that still gives every slot a workgroup.  Long
 // slices amortise the per-workgroup prologue, and a grid of exactly one round has no half-empty last round (the
@@ -117,12 +120,21 @@ static ScorePlan plan_mfma(const Dims& D) {
   pl.cap_block = 0;
   pl.head_block = 0;
   pl.lse_given = 0;
+  // One workgroup per unit (both passes in one kernel) when the units fill the chip round by round and a sweep of 256
+  // query rows is mostly real rows; the slice kernels otherwise (few units: they cut a unit into token slices).
+  if (D.score_path == CCD_PATH_MFMA_UNIT) {
+    pl.unit_kernel = 1;
+  } else if (D.score_path == CCD_PATH_AUTO && score_unit_supported(D)) {
+    const int cus = compute_units();
+    const int rounds = (D.units_run + cus - 1) / cus;
+    pl.unit_kernel = (D.GP > 128 && 4 * D.units_run >= 3 * rounds * cus) ? 1 : 0;
+  }
   return pl;
 }
 
 ScorePlan plan_score(const Dims& D) {
   ScorePlan pl{};
-  pl.use_mfma = (D.dtype == CCD_BF16 && g_score_path != 1) ? 1 : 0;
+  pl.use_mfma = (D.dtype == CCD_BF16 && D.score_path != CCD_PATH_VALU) ? 1 : 0;
   if (pl.use_mfma) {
     return plan_mfma(D);
   } else {
@@ -160,9 +172,9 @@ static int check_workspace(const Workspace& w, const void* ws, size_t ws_bytes) 
 }
 
 // ---- optional per-kernel timing of ccd_compress -------------------------------------------------------
-enum Stage { kStStats = 0, kStMerge, kStProb, kStSelect, kStCompact, kStSelCompact, kStCapBlock, kStHead, kNumStages };
-static const char* const kStageNames[kNumStages] = {"score_stats", "score_merge",    "score_prob", "select",
-                                                    "compact",     "select_compact", "cap_block",  "window_head"};
+enum Stage { kStStats = 0, kStMerge, kStProb, kStSelect, kStCompact, kStSelCompact, kStCapBlock, kStHead, kStUnit, kNumStages };
+static const char* const kStageNames[kNumStages] = {"score_stats", "score_merge",    "score_prob", "select",     "compact",
+                                                    "select_compact", "cap_block",   "window_head", "score_unit"};
 
 // Every profiled launch is bracketed by two events on the stream it runs on.
 struct Profiler {
@@ -205,6 +217,28 @@ static void run_cap_scores(const Dims& D, ScorePlan pl, const Workspace& w, cons
   float2* part = reinterpret_cast<float2*>(ws + w.off_part);
   float* lse2 = reinterpret_cast<float*>(ws + w.off_lse);
   float* u = reinterpret_cast<float*>(ws + w.off_u);
+  if (pl.unit_kernel) {
+    // statistics, merge and probabilities of every unit in one kernel; a windowed head keeps its two small kernels
+    float* lse_io = lse2;
+    if (lse != nullptr) {
+      pl.lse_given = 1;
+      lse_io = const_cast<float*>(lse);   // only read when pl.lse_given
+    } else if (D.head > 0) {
+      pl.head_block = 1;
+      g_prof.begin(kStHead, st);
+      launch_head_stats_mfma(D, pl, Q, K, part, st);
+      g_prof.end(st);
+    }
+    g_prof.begin(kStUnit, st);
+    launch_score_unit(D, pl, Q, K, K_cap, part, u, lse_io, st);
+    g_prof.end(st);
+    if (D.head > 0) {
+      g_prof.begin(kStHead, st);
+      launch_head_prob_mfma(D, pl, Q, K, lse_io, u, st);
+      g_prof.end(st);
+    }
+    return;
+  }
   if (lse != nullptr) {
     pl.lse_given = 1;
     float* lse_rw = const_cast<float*>(lse);   // only read when pl.lse_given
@@ -431,12 +465,6 @@ int ccd_nuc_from_logits(const void* logits, const int32_t* labels, float* novelt
   return launch_status();
 }
 
-int ccd_set_score_path(int path) {
-  if (path < 0 || path > 1) return CCD_EINVAL;
-  g_score_path = path;
-  return CCD_OK;
-}
-
 int ccd_profile_enable(int on) {
   g_prof.on = on != 0;
   return CCD_OK;
@@ -469,7 +497,9 @@ const char* ccd_strerror(int code) {
     case CCD_OK: return "ok";
     case CCD_NOOP: return "pot not full or nothing to drop: nothing done";
     case CCD_EINVAL: return "invalid argument (null pointer or shape field out of range)";
-    case CCD_EUNSUPPORTED: return "unsupported head dimension, dtype or pool mode";
+    case CCD_EUNSUPPORTED:
+      return "unsupported: head dimension not 64 or 128, unknown dtype or pool mode, more than 65536 tokens, a matrix-core "
+             "score path for an fp32 cache, or (bf16) a window that hides more than 2048 tokens from the last CaP token";
     case CCD_EALIGN: return "pointer or stride not 16-byte aligned";
     case CCD_EWORKSPACE: return "workspace null, misaligned or too small";
     case CCD_ELAUNCH: return "HIP kernel launch failed";

@@ -20,17 +20,18 @@ CCD_OK, CCD_NOOP = 0, 1
 CCD_EINVAL, CCD_EUNSUPPORTED, CCD_EALIGN, CCD_EWORKSPACE, CCD_ELAUNCH = -1, -2, -3, -4, -5
 CCD_FP32, CCD_BF16 = 0, 1
 CCD_POOL_NONE, CCD_POOL_MAX, CCD_POOL_AVG = 0, 1, 2
+CCD_PATH_AUTO, CCD_PATH_VALU, CCD_PATH_MFMA_SLICES, CCD_PATH_MFMA_UNIT = 0, 1, 2, 3
 
 EXPORTS = ("ccd_workspace_bytes", "ccd_score", "ccd_select", "ccd_compact", "ccd_compress", "ccd_cr_rope",
            "ccd_compress_rope", "ccd_score_kcat", "ccd_compress_kcat", "ccd_score_lse", "ccd_compress_lse",
-           "ccd_nuc_from_logits", "ccd_set_score_path", "ccd_profile_enable", "ccd_profile_stages", "ccd_profile_stage_name",
+           "ccd_nuc_from_logits", "ccd_profile_enable", "ccd_profile_stages", "ccd_profile_stage_name",
            "ccd_profile_collect", "ccd_strerror")
 
 
 class ccd_shape_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("B", "L", "Hq", "Hkv", "d", "n_valid", "n_cap", "k", "P", "T", "pool_w", "pool_mode", "dtype")]
-    _fields_ += [("scale", ctypes.c_float), ("window", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+    _fields_ += [("scale", ctypes.c_float), ("window", ctypes.c_int32), ("score_path", ctypes.c_int32)]
     _fields_ += [(n, ctypes.c_int64) for n in
                  ("kv_stride_b", "kv_stride_l", "kv_stride_h", "q_stride_b", "q_stride_l", "q_stride_h",
                   "nov_stride_b", "nov_stride_l", "nov_stride_h")]
@@ -79,8 +80,6 @@ def lib() -> ctypes.CDLL:
         L.ccd_compress_kcat.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.ccd_nuc_from_logits.restype = ctypes.c_int
         L.ccd_nuc_from_logits.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp]
-        L.ccd_set_score_path.restype = ctypes.c_int
-        L.ccd_set_score_path.argtypes = [ctypes.c_int]
         L.ccd_profile_enable.restype = ctypes.c_int
         L.ccd_profile_enable.argtypes = [ctypes.c_int]
         L.ccd_profile_stages.restype = ctypes.c_int
@@ -123,7 +122,7 @@ def _dtype_code(t: torch.Tensor) -> int:
 
 
 def make_shape(Q_cat, K, novelty, *, k, T=0, pool_w=1, pool_mode=CCD_POOL_MAX, scale=0.0, n_valid=None,
-               window=0) -> ccd_shape_t:
+               window=0, score_path=CCD_PATH_AUTO) -> ccd_shape_t:
     """Shape descriptor from tensor geometry: Q_cat [B,L,Hq,P,d], K [B,L,Hkv,n_cap,d], novelty [B,n] or
     [B,L,Hkv,n_cap] (may be None when T == 0).  Q_cat may be None for calls that do not read it."""
     B, L, Hkv, n_cap, d = K.shape
@@ -132,6 +131,7 @@ def make_shape(Q_cat, K, novelty, *, k, T=0, pool_w=1, pool_mode=CCD_POOL_MAX, s
     s.n_valid = n_cap if n_valid is None else n_valid
     s.k, s.T, s.pool_w, s.pool_mode, s.scale = k, T, pool_w, pool_mode, scale
     s.window = window
+    s.score_path = score_path
     s.dtype = _dtype_code(K)
     assert K.stride(4) == 1 and K.stride(3) == d, "K rows must be contiguous with stride d"
     s.kv_stride_b, s.kv_stride_l, s.kv_stride_h = K.stride(0), K.stride(1), K.stride(2)
@@ -238,10 +238,6 @@ def ccd_compress_kcat(shape, Q_cat, K, V, K_cap, novelty, keep_idx, workspace, s
     return _check(lib().ccd_compress_kcat(ctypes.byref(shape), _ptr(Q_cat), _ptr(K), _ptr(V), _ptr(K_cap), _ptr(novelty),
                                           _ptr(scores), _ptr(keep_idx), _ptr(workspace),
                                           0 if workspace is None else workspace.numel(), _stream(stream)))
-
-
-def ccd_set_score_path(path: int) -> int:
-    return _check(lib().ccd_set_score_path(path))
 
 
 def ccd_profile_enable(on: bool) -> int:

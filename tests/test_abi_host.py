@@ -117,7 +117,6 @@ def test_null_misaligned_and_workspace_errors():
     assert L.ccd_compact(ctypes.byref(s), P, P, None, P, P, None, None) == ip.CCD_EINVAL
     assert L.ccd_compact(ctypes.byref(s), P, P + 4, P, P, P, None, None) == ip.CCD_EALIGN
     assert L.ccd_compact(ctypes.byref(_shape(d=80)), P, P, P, P, P, None, None) == ip.CCD_EUNSUPPORTED
-    assert L.ccd_set_score_path(7) == ip.CCD_EINVAL and L.ccd_set_score_path(0) == ip.CCD_OK
 
 
 def test_cr_rope_argument_errors_are_decided_on_the_host():
@@ -189,7 +188,10 @@ def test_kcat_argument_errors_are_decided_on_the_host():
 def test_window_errors_are_decided_on_the_host():
     assert _compress(_shape(window=-1)) == ip.CCD_EINVAL
     assert _compress(_shape(window=15)) == ip.CCD_EINVAL                      # shorter than the P = 16 CaP tokens
-    assert _compress(_shape(reserved=1)) == ip.CCD_EINVAL
+    assert _compress(_shape(score_path=4)) == ip.CCD_EINVAL and _compress(_shape(score_path=-1)) == ip.CCD_EINVAL
+    for path in (ip.CCD_PATH_MFMA_SLICES, ip.CCD_PATH_MFMA_UNIT):         # the matrix-core kernels are bf16 only
+        assert _compress(_shape(dtype=ip.CCD_FP32, score_path=path)) == ip.CCD_EUNSUPPORTED
+    assert "fp32" in ip.ccd_strerror(ip.CCD_EUNSUPPORTED) and "2048" in ip.ccd_strerror(ip.CCD_EUNSUPPORTED)
     big = _shape(n_valid=8192, n_cap=8192, k=4096, T=0, window=8192 + 16 - 2049)
     assert _compress(big) == ip.CCD_EUNSUPPORTED                              # more than 2048 tokens hidden (bf16 path)
     assert ip.ccd_workspace_bytes(_shape(window=512)) == ip.ccd_workspace_bytes(_shape())

@@ -21,15 +21,11 @@ def _score(cfg, gain=1.0, path=0, K_cap=None):
     inp = synth.make_inputs(cfg)
     K_cap = synth.cap_keys(cfg, gain=gain) if K_cap is None else K_cap
     dev = {k: gu.to_dev(v) for k, v in inp.items()}
-    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, score_path=path)
     ws = ip.alloc_workspace(shape)
     scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
-    ip.lib().ccd_set_score_path(path)
-    try:
-        assert ip.ccd_score_kcat(shape, dev["Q_cat"], dev["K"], gu.to_dev(K_cap), dev["novelty"], scores, ws) == ip.CCD_OK
-        torch.cuda.synchronize()
-    finally:
-        ip.lib().ccd_set_score_path(0)
+    assert ip.ccd_score_kcat(shape, dev["Q_cat"], dev["K"], gu.to_dev(K_cap), dev["novelty"], scores, ws) == ip.CCD_OK
+    torch.cuda.synchronize()
     return inp, K_cap, gu.to_host(scores)
 
 
@@ -48,11 +44,17 @@ KCAT_CASES = [
 ]
 
 
+MFMA_PATHS = [ip.CCD_PATH_MFMA_SLICES, ip.CCD_PATH_MFMA_UNIT]     # a workgroup per token slice / per unit
+
+
+@pytest.mark.parametrize("path", [ip.CCD_PATH_AUTO] + MFMA_PATHS)
 @pytest.mark.parametrize("case", KCAT_CASES, ids=lambda c: "-".join(f"{k}{v}" for k, v in c.items()))
-def test_score_kcat_matches_oracle(case):
+def test_score_kcat_matches_oracle(case, path):
     cfg = _cfg(**case)
-    print(f"score_kcat {cfg}", flush=True)
-    inp, K_cap, got = _score(cfg)
+    if cfg.dtype == "fp32" and path != ip.CCD_PATH_AUTO:
+        pytest.skip("fp32 caches have one path")
+    print(f"score_kcat {cfg} path={path}", flush=True)
+    inp, K_cap, got = _score(cfg, path=path)
     ref = O.compress(inp["Q_cat"], inp["K"], inp["V"], inp["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, K_cap=K_cap)
     gu.assert_scores_close(got, ref["scores"], cfg.G * cfg.P)
     # the CaP keys matter in these cases: without them the scores would be out of tolerance
@@ -61,12 +63,13 @@ def test_score_kcat_matches_oracle(case):
     assert np.median(plain["scores"][fin] / ref["scores"][fin]) > 1.0 + 0.25 * ((cfg.P + 1) / 2) / (cfg.N + cfg.P)
 
 
+@pytest.mark.parametrize("path", MFMA_PATHS)
 @pytest.mark.parametrize("gain", [0.0, 6.0])
-def test_score_kcat_weak_and_dominant_cap_keys(gain):
+def test_score_kcat_weak_and_dominant_cap_keys(gain, path):
     """gain 0: every CaP key has logit 0; gain 6: a few CaP keys take nearly all of the mass of their queries."""
     cfg = _cfg(P=24, N=640, k=200)
-    print(f"score_kcat gain={gain} {cfg}", flush=True)
-    inp, K_cap, got = _score(cfg, gain=gain)
+    print(f"score_kcat gain={gain} path={path} {cfg}", flush=True)
+    inp, K_cap, got = _score(cfg, gain=gain, path=path)
     ref = O.compress(inp["Q_cat"], inp["K"], inp["V"], inp["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, K_cap=K_cap)
     gu.assert_scores_close(got, ref["scores"], cfg.G * cfg.P)
 
@@ -74,7 +77,7 @@ def test_score_kcat_weak_and_dominant_cap_keys(gain):
 def test_score_kcat_on_the_vector_alu_path_for_bf16():
     cfg = _cfg(P=17, N=400, k=150)
     print(f"score_kcat valu path {cfg}", flush=True)
-    inp, K_cap, got = _score(cfg, path=1)
+    inp, K_cap, got = _score(cfg, path=ip.CCD_PATH_VALU)
     ref = O.compress(inp["Q_cat"], inp["K"], inp["V"], inp["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, K_cap=K_cap)
     gu.assert_scores_close(got, ref["scores"], cfg.G * cfg.P)
 

@@ -45,15 +45,11 @@ def _row_lse(cfg, inp, K_cap=None, window=0):
 
 def _score_lse(cfg, inp, lse, window=0, path=0):
     dev = {k: gu.to_dev(v) for k, v in inp.items()}
-    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, window=window)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, window=window, score_path=path)
     ws = ip.alloc_workspace(shape)
     scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
-    ip.lib().ccd_set_score_path(path)
-    try:
-        assert ip.ccd_score_lse(shape, dev["Q_cat"], dev["K"], torch.from_numpy(lse).cuda(), dev["novelty"], scores, ws) == ip.CCD_OK
-        torch.cuda.synchronize()
-    finally:
-        ip.lib().ccd_set_score_path(0)
+    assert ip.ccd_score_lse(shape, dev["Q_cat"], dev["K"], torch.from_numpy(lse).cuda(), dev["novelty"], scores, ws) == ip.CCD_OK
+    torch.cuda.synchronize()
     return gu.to_host(scores)
 
 
@@ -67,18 +63,23 @@ LSE_CASES = [
 ]
 
 
+@pytest.mark.parametrize("path", [ip.CCD_PATH_MFMA_SLICES, ip.CCD_PATH_MFMA_UNIT])
 @pytest.mark.parametrize("case", range(len(LSE_CASES)))
 @pytest.mark.parametrize("reading", ["cache_only", "causal", "causal_window"])
-def test_score_lse_matches_oracle(case, reading):
+def test_score_lse_matches_oracle(case, reading, path):
     cfg = _cfg(**LSE_CASES[case])
-    print(f"score_lse case={case} reading={reading} {cfg}", flush=True)
+    if cfg.dtype == "fp32":
+        if path != ip.CCD_PATH_MFMA_SLICES:
+            pytest.skip("fp32 caches have one path")
+        path = ip.CCD_PATH_AUTO
+    print(f"score_lse case={case} reading={reading} path={path} {cfg}", flush=True)
     inp = synth.make_inputs(cfg)
     K_cap = synth.cap_keys(cfg) if reading != "cache_only" else None
     window = cfg.N - 30 if reading == "causal_window" else 0
     if window and window < cfg.P:
         pytest.skip("window shorter than the CaP")
     lse = _row_lse(cfg, inp, K_cap, window)
-    got = _score_lse(cfg, inp, lse, window)
+    got = _score_lse(cfg, inp, lse, window, path=path)
     kw = dict(k=cfg.k, T=cfg.T, pool_w=cfg.w)
     ref = O.compress(inp["Q_cat"], inp["K"], inp["V"], inp["novelty"], lse=lse, window=window, **kw)
     gu.assert_scores_close(got, ref["scores"], cfg.G * cfg.P)

@@ -107,24 +107,31 @@ SCORE_CASES = [
 ]
 
 
-@pytest.fixture
-def score_path(request):
-    """Selects the logit kernels (0 automatic: matrix cores for bf16; 1: vector ALUs) and restores the default."""
-    ip.ccd_set_score_path(request.param)
-    yield request.param
-    ip.ccd_set_score_path(0)
+# the kernels of Eq. 2: vector ALUs, matrix cores with a workgroup per token slice, matrix cores with a workgroup per unit
+SCORE_PATHS = [ip.CCD_PATH_VALU, ip.CCD_PATH_MFMA_SLICES, ip.CCD_PATH_MFMA_UNIT]
+
+
+def _path_for(cfg, score_path):
+    """fp32 caches have the vector-ALU path only: they run once, under the automatic choice."""
+    if cfg.dtype == "fp32":
+        if score_path != ip.CCD_PATH_VALU:
+            pytest.skip("fp32 caches have one path")
+        return ip.CCD_PATH_AUTO
+    return score_path
 
 
 @pytest.mark.parametrize("case", range(len(SCORE_CASES)))
 @pytest.mark.parametrize("pool_mode", [O.POOL_MAX, O.POOL_AVG])
-@pytest.mark.parametrize("score_path", [0, 1], indirect=True)
+@pytest.mark.parametrize("score_path", SCORE_PATHS)
 def test_scores_and_staged_calls(case, pool_mode, score_path):
     cfg = _cfg(**SCORE_CASES[case])
+    score_path = _path_for(cfg, score_path)
     print(f"score case={case} cfg={cfg} pool_mode={pool_mode} path={score_path}", flush=True)
     inp = synth.make_inputs(cfg, per_head_novelty=(case % 2 == 1))
     ref = _oracle(cfg, inp, pool_mode)
     dev = _upload(inp)
-    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=pool_mode)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=pool_mode,
+                          score_path=score_path)
     ws = ip.alloc_workspace(shape)
     scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
     keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device="cuda")
@@ -139,7 +146,7 @@ def test_scores_and_staged_calls(case, pool_mode, score_path):
 
 
 @pytest.mark.parametrize("per_head", [False, True])
-@pytest.mark.parametrize("score_path", [0, 1], indirect=True)
+@pytest.mark.parametrize("score_path", SCORE_PATHS)
 @pytest.mark.parametrize("T", [1, 37, 200, 699])
 def test_nuc_slots_with_ties_and_non_finite_novelty(per_head, score_path, T):
     """Sec. 3.3.3 step 1 on novelty rows full of equal values, NaN and -inf: the +inf entries of the scores must
@@ -156,7 +163,8 @@ def test_nuc_slots_with_ties_and_non_finite_novelty(per_head, score_path, T):
         nov[..., 5:] = np.where(rng.random(nov[..., 5:].shape) < 0.9, -np.inf, nov[..., 5:])   # fewer eligible than T
     inp["novelty"] = nov
     dev = _upload(inp)
-    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=T, pool_w=cfg.w, pool_mode=O.POOL_MAX)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=T, pool_w=cfg.w, pool_mode=O.POOL_MAX,
+                          score_path=score_path)
     ws = ip.alloc_workspace(shape)
     scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
     assert ip.ccd_score(shape, dev["Q_cat"], dev["K"], dev["novelty"], scores, ws) == ip.CCD_OK
@@ -173,9 +181,10 @@ def test_nuc_slots_with_ties_and_non_finite_novelty(per_head, score_path, T):
 
 # ------------------------------------------------------------------ fused ccd_compress
 
-def _run_fused(cfg, inp, pool_mode=O.POOL_MAX, per_head=False, want_scores=True):
+def _run_fused(cfg, inp, pool_mode=O.POOL_MAX, per_head=False, want_scores=True, score_path=ip.CCD_PATH_AUTO):
     dev = _upload(inp)
-    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=pool_mode)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=pool_mode,
+                          score_path=score_path)
     ws = ip.alloc_workspace(shape)
     scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda") if want_scores else None
     keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device="cuda")
@@ -219,13 +228,14 @@ def test_fused_compress_configs(name):
         assert set(nuc.tolist()) <= set(kh[0, 0, h].tolist())
 
 
+@pytest.mark.parametrize("score_path", [ip.CCD_PATH_AUTO, ip.CCD_PATH_MFMA_UNIT])
 @pytest.mark.parametrize("per_head,want_scores", [(True, False), (False, False), (True, True)])
-def test_fused_compress_small(per_head, want_scores):
+def test_fused_compress_small(per_head, want_scores, score_path):
     cfg = _cfg(B=2, L=2, N=640, k=320, T=160)
-    print(f"fused small per_head={per_head} want_scores={want_scores}", flush=True)
+    print(f"fused small per_head={per_head} want_scores={want_scores} path={score_path}", flush=True)
     inp = synth.make_inputs(cfg, per_head_novelty=per_head)
     ref = _oracle(cfg, inp)
-    rc, dev, scores, keep = _run_fused(cfg, inp, per_head=per_head, want_scores=want_scores)
+    rc, dev, scores, keep = _run_fused(cfg, inp, per_head=per_head, want_scores=want_scores, score_path=score_path)
     assert rc == ip.CCD_OK
     _check_fused(cfg, inp, ref, dev, scores, keep, per_head)
 
@@ -243,14 +253,15 @@ def test_fused_compress_many_units(per_head):
     _check_fused(cfg, inp, ref, dev, scores, keep, per_head)
 
 
+@pytest.mark.parametrize("score_path", [ip.CCD_PATH_AUTO, ip.CCD_PATH_MFMA_UNIT])
 @pytest.mark.parametrize("per_head,N", [(False, 6000), (True, 4100), (False, 16384), (True, 20000), (False, 32768)])
-def test_fused_compress_rows_of_several_thousand_tokens(per_head, N):
+def test_fused_compress_rows_of_several_thousand_tokens(per_head, N, score_path):
     """Rows between 4097 and 32768 tokens: the one-workgroup selection + compaction with 16 or 32 tokens per thread."""
     cfg = _cfg(B=1, L=1, Hq=4, Hkv=2, P=8, N=N, k=N // 3, T=N // 8)
-    print(f"fused N={N} per_head={per_head} {cfg}", flush=True)
+    print(f"fused N={N} per_head={per_head} path={score_path} {cfg}", flush=True)
     inp = synth.make_inputs(cfg, per_head_novelty=per_head)
     ref = _oracle(cfg, inp)
-    rc, dev, scores, keep = _run_fused(cfg, inp, per_head=per_head)
+    rc, dev, scores, keep = _run_fused(cfg, inp, per_head=per_head, score_path=score_path)
     assert rc == ip.CCD_OK
     _check_fused(cfg, inp, ref, dev, scores, keep, per_head)
 
@@ -385,7 +396,7 @@ def test_logits_far_above_those_of_the_first_tile(where):
     gu.assert_scores_close(gu.to_host(scores), ref["scores"], cfg.G * cfg.P)
 
 
-@pytest.mark.parametrize("score_path", [0, 1], indirect=True)
+@pytest.mark.parametrize("score_path", SCORE_PATHS)
 def test_heavy_tailed_key_norms_saturate_the_softmax(score_path):
     """Key rows scaled by sqrt(z_t), z_t ~ Zipf(1.1) capped at 2^16 instead of the benchmark's 64 (gains up to 256, logits
     up to 1600 binary orders): nearly every attention row is one-hot, nine scores in ten are exactly zero and fewer
@@ -400,7 +411,7 @@ def test_heavy_tailed_key_norms_saturate_the_softmax(score_path):
     inp["K"] = synth.f32_to_bf16_bits(K)
     ref = _oracle(cfg, inp)
     assert (ref["scores"] == 0).mean() > 0.8 and ((ref["scores"] > 0).sum(axis=-1) < cfg.k).all()
-    rc, dev, scores, keep = _run_fused(cfg, inp)
+    rc, dev, scores, keep = _run_fused(cfg, inp, score_path=score_path)
     assert rc == ip.CCD_OK
     sh = gu.to_host(scores)
     assert (sh == 0).mean() > 0.8

@@ -21,19 +21,15 @@ def _score(cfg, window, path=0, with_cap=False, inp=None):
     inp = synth.make_inputs(cfg) if inp is None else inp
     K_cap = synth.cap_keys(cfg) if with_cap else None
     dev = {k: gu.to_dev(v) for k, v in inp.items()}
-    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, window=window)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, window=window, score_path=path)
     ws = ip.alloc_workspace(shape)
     scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
-    ip.lib().ccd_set_score_path(path)
-    try:
-        if with_cap:
-            rc = ip.ccd_score_kcat(shape, dev["Q_cat"], dev["K"], gu.to_dev(K_cap), dev["novelty"], scores, ws)
-        else:
-            rc = ip.ccd_score(shape, dev["Q_cat"], dev["K"], dev["novelty"], scores, ws)
-        assert rc == ip.CCD_OK
-        torch.cuda.synchronize()
-    finally:
-        ip.lib().ccd_set_score_path(0)
+    if with_cap:
+        rc = ip.ccd_score_kcat(shape, dev["Q_cat"], dev["K"], gu.to_dev(K_cap), dev["novelty"], scores, ws)
+    else:
+        rc = ip.ccd_score(shape, dev["Q_cat"], dev["K"], dev["novelty"], scores, ws)
+    assert rc == ip.CCD_OK
+    torch.cuda.synchronize()
     ref = O.compress(inp["Q_cat"], inp["K"], inp["V"], inp["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, K_cap=K_cap,
                      window=window)
     return gu.to_host(scores), ref
@@ -54,13 +50,18 @@ SWA_CASES = [
 ]
 
 
+@pytest.mark.parametrize("path", [ip.CCD_PATH_MFMA_SLICES, ip.CCD_PATH_MFMA_UNIT])
 @pytest.mark.parametrize("with_cap", [False, True])
 @pytest.mark.parametrize("case", range(len(SWA_CASES)))
-def test_scores_under_a_sliding_window(case, with_cap):
+def test_scores_under_a_sliding_window(case, with_cap, path):
     cfg = _cfg(**SWA_CASES[case]["cfg"])
     window = SWA_CASES[case]["window"](cfg)
-    print(f"swa case={case} window={window} with_cap={with_cap} {cfg}", flush=True)
-    got, ref = _score(cfg, window, with_cap=with_cap)
+    if cfg.dtype == "fp32":
+        if path != ip.CCD_PATH_MFMA_SLICES:
+            pytest.skip("fp32 caches have one path")
+        path = ip.CCD_PATH_AUTO
+    print(f"swa case={case} window={window} with_cap={with_cap} path={path} {cfg}", flush=True)
+    got, ref = _score(cfg, window, with_cap=with_cap, path=path)
     gu.assert_scores_close(got, ref["scores"], cfg.G * cfg.P)
 
 
