@@ -36,12 +36,14 @@ namespace {
 
 constexpr int kUPairs = 4;                    // pairs of 32-query blocks per sweep
 constexpr int kUQ = kUPairs * kQB * 32;       // query rows per sweep: 256
+constexpr int kUBlock = 128;                  // tiles of a wave between two write-outs of its token sums (pass 2)
 static_assert(kQB == 2, "a step covers two query blocks");
 
 template <int HD>
 struct UnitLds {
   float2 stat[4][kUQ];     // per wave: (max2, sum) of every query row of the sweep over the wave's tokens
   float neg_lse[kUQ];      // -log2-sum-exp per query row of the sweep
+  float ubuf[4][kUBlock * kStep];   // per wave: the token sums of the block of tiles it is working on (pass 2)
 };
 
 // fragments of one 32-token tile, straight from global memory: lane (col, half) holds elements 16 ks + 8 half .. + 7
@@ -68,15 +70,22 @@ __device__ __forceinline__ void load_k_tile(bf16x8 (&a)[HD / 16], const uint16_t
 // every accumulation register belongs to the fragments from here on (the clobber list also makes the kernel claim them)
 __device__ __forceinline__ void claim_acc_registers() { asm volatile("" ::: CCD_ALL_ACC_REGISTERS); }
 
+// query fragment F (8 elements of the lane's query row, at `row` + byte_off) straight from global memory into its
+// accumulation registers; the caller waits with q_frags_arrived() (the compiler does not see these loads)
+template <int F, int BYTE_OFF>
+__device__ __forceinline__ void load_q_frag_at(const uint16_t* row) {
+  asm volatile("global_load_dwordx4 a[%1:%2], %0, off offset:%3"
+               :: "v"(row), "n"(4 * F), "n"(4 * F + 3), "n"(BYTE_OFF)
+               : "memory", CCD_ALL_ACC_REGISTERS);
+}
 template <int F>
-__device__ __forceinline__ void store_q_frag(const bf16x8& q) {
-  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  const u32x4 w = __builtin_bit_cast(u32x4, q);
-  asm volatile("v_accvgpr_write_b32 a[%4], %0\n\tv_accvgpr_write_b32 a[%5], %1\n\t"
-               "v_accvgpr_write_b32 a[%6], %2\n\tv_accvgpr_write_b32 a[%7], %3"
-               :: "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "n"(4 * F), "n"(4 * F + 1), "n"(4 * F + 2), "n"(4 * F + 3)
+__device__ __forceinline__ void zero_q_frag() {
+  asm volatile("v_accvgpr_write_b32 a[%0], 0\n\tv_accvgpr_write_b32 a[%1], 0\n\t"
+               "v_accvgpr_write_b32 a[%2], 0\n\tv_accvgpr_write_b32 a[%3], 0"
+               :: "n"(4 * F), "n"(4 * F + 1), "n"(4 * F + 2), "n"(4 * F + 3)
                : CCD_ALL_ACC_REGISTERS);
 }
+__device__ __forceinline__ void q_frags_arrived() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // F: index of the query fragment
 template <int PASS, int F>
@@ -187,17 +196,22 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
   claim_acc_registers();
 
   for (int qc = 0; qc < D.GP; qc += kUQ) {
-    // fragments of the sweep's query rows into the accumulation registers, a block pair at a time
-    static_for<0, kUPairs>([&](auto Pc) {
-      constexpr int p = decltype(Pc)::value;
-      bf16x8 bw[kQB][KS];
-      load_q_frags<HD>(bw, D, ui, Q, qc + p * (kQB * 32), col, half);
-      static_for<0, kQB * KS>([&](auto Fc) {
-        constexpr int f = decltype(Fc)::value;
-        store_q_frag<p * kQB * KS + f>(bw[f / KS][f % KS]);
-      });
+    // Fragments of the sweep's query rows into the accumulation registers: all 8 KS loads of a lane are in flight at
+    // once, together with the first K tiles requested further down.  Rows past G * P (last sweep only) stay zero.
+    if (qc + kUQ > D.GP) {
+      static_for<0, kUPairs * kQB * KS>([&](auto Fc) { zero_q_frag<decltype(Fc)::value>(); });
+    }
+    static_for<0, kUPairs * kQB>([&](auto Bc) {
+      constexpr int blk = decltype(Bc)::value;
+      const int q = qc + blk * 32 + col;
+      if (q < D.GP) {
+        const uint16_t* row = Q + q_offset(D, ui, q) + half * 8;
+        static_for<0, KS>([&](auto Kc) {
+          constexpr int ks = decltype(Kc)::value;
+          load_q_frag_at<blk * KS + ks, ks * 32>(row);
+        });
+      }
     });
-
     bf16x8 a[2][KS];
     floatx16 accA[kQB], accB[kQB];
 
@@ -229,7 +243,8 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
       }
       if (s0 < s1) {
         load_k_tile<HD>(a[0], Ku, tb + s0 * kStep, t_last, col, half);
-        if (s0 + 1 < s1) load_k_tile<HD>(a[1], Ku, tb + (s0 + 1) * kStep, t_last, col, half);
+        load_k_tile<HD>(a[1], Ku, tb + min(s0 + 1, s1 - 1) * kStep, t_last, col, half);
+        q_frags_arrived();
         // the wave's first tile fixes the references and is folded without overlap
         static_for<0, kUPairs>([&](auto Pc) {
           constexpr int p = decltype(Pc)::value;
@@ -240,9 +255,9 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
 #pragma unroll
           for (int j = 0; j < NM; ++j) fold(j);
         });
-        if (s0 + 2 < s1) load_k_tile<HD>(a[0], Ku, tb + (s0 + 2) * kStep, t_last, col, half);
+        load_k_tile<HD>(a[0], Ku, tb + min(s0 + 2, s1 - 1) * kStep, t_last, col, half);
         int s = s0 + 1;
-        if (s < s1) logits_now<HD, 1, 0>(accA, a[1]);
+        logits_now<HD, 1, 0>(accA, a[1]);
         // Tile s: accA holds the logits of (s, pair 0).  Steps 1 - 3 take pairs 1 - 3 of tile s from buffer CB, the
         // last step pair 0 of tile s + 1 from buffer NB; every step folds the pair computed by the step before.  The
         // buffer of tile s is free after step 3 and takes tile s + 2.
@@ -250,22 +265,22 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
         pipelined_step<HD, 1, 1>(accB, a[CB], CCD_FOLD1(accA, 0));                            \
         pipelined_step<HD, 1, 2>(accA, a[CB], CCD_FOLD1(accB, 1));                            \
         pipelined_step<HD, 1, 3>(accB, a[CB], CCD_FOLD1(accA, 2));                            \
-        if (s + 2 < s1) load_k_tile<HD>(a[CB], Ku, tb + (s + 2) * kStep, t_last, col, half);      \
-        if (s + 1 < s1) {                                                                         \
-          pipelined_step<HD, 1, 0>(accA, a[NB], CCD_FOLD1(accB, 3));                          \
-        } else {                                                                                  \
-          mma_results_ready(accB);                                                                \
-          auto fold = CCD_FOLD1(accB, 3);                                                         \
-          _Pragma("unroll") for (int j = 0; j < NM; ++j) fold(j);                                 \
-        }
-        while (true) {
-          if (s >= s1) break;
+        /* (always: a load under a condition would make every wait for K fragments a wait for all loads) */ \
+        load_k_tile<HD>(a[CB], Ku, tb + min(s + 2, s1 - 1) * kStep, t_last, col, half);           \
+        pipelined_step<HD, 1, 0>(accA, a[NB], CCD_FOLD1(accB, 3));
+        // (No branch inside a tile and none between the two tiles of the loop body: with straight-line code the
+        // compiler can tell how many loads are in flight at every wait.  Behind the wave's last tile the last step
+        // computes the logits of that tile's first pair once more; nobody reads them.)
+        while (s + 1 < s1) {
           CCD_P1_TILE(1, 0)
           ++s;
-          if (s >= s1) break;
           CCD_P1_TILE(0, 1)
           ++s;
         }
+        if (s < s1) {
+          CCD_P1_TILE(1, 0)
+        }
+        mma_results_ready(accA);      // the surplus logits are in flight until here
 #undef CCD_P1_TILE
 #undef CCD_FOLD1
         // Did a sum leave the fp32 range (or meet a NaN)?  Then this wave redoes its tokens with a running maximum.
@@ -313,6 +328,7 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
       }
       if (ragged && wave == 3) {
         load_k_tile<HD>(a[0], Ku, tb + full * kStep, t_last, col, half);
+        q_frags_arrived();
         static_for<0, kUPairs>([&](auto Pc) {
           constexpr int p = decltype(Pc)::value;
           logits_now<HD, 1, p>(accA, a[0]);
@@ -369,13 +385,19 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
       __syncthreads();
     }
 
-    // ---------------- pass 2: tiles s1p - 1 down to s0 ----------------
-    if (s0 < s1p) {
+    // ---------------- pass 2: tiles s1p - 1 down to s0, in blocks of kUBlock ----------------
+    // The sums of a block of tiles are collected in LDS and written out behind the block: a store (or, from the second
+    // sweep on, a load and a store) inside the pipelined loop would sit among the K loads in the memory counter, and
+    // every wait for K fragments would become a wait for everything.
+    for (int sb = s1p; sb > s0; sb -= kUBlock) {
+      const int sa = max(s0, sb - kUBlock);        // this block: tiles [sa, sb)
+      float* ub = sm.ubuf[wave];
       float nl[kQB][16];      // normalisers of the pair being folded; each half is reloaded as soon as it is done with
       float us[2];
       uint32_t nl_base = (uint32_t)(uintptr_t)(LdsFloats)sm.neg_lse + 16 * half;
       // chunk j of the fold of a pair: 2^(x c - lse2) of EPC accumulator elements added to the token's sum; behind
-      // the last chunk of a block, the normalisers of that block of pair NP (the pair folded next) are requested
+      // the last chunk of a block of query rows, the normalisers of that block of pair NP (the pair folded next) are
+      // requested
 #define CCD_FOLD2(CUR, NP)                                                                \
       [&](int j) {                                                                        \
         float t[EPC];                                                                     \
@@ -389,44 +411,43 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
         if (j == NM / 2 - 1) load_neg_lse(nl[0], nl_base, (NP) * kQB);                    \
         if (j == NM - 1) load_neg_lse(nl[1], nl_base, (NP) * kQB + 1);                    \
       }
-      int s = s1p - 1;
+      int s = sb - 1;
       load_k_tile<HD>(a[0], Ku, tb + s * kStep, t_last, col, half);
-      if (s - 1 >= s0) load_k_tile<HD>(a[1], Ku, tb + (s - 1) * kStep, t_last, col, half);
+      load_k_tile<HD>(a[1], Ku, tb + max(s - 1, sa) * kStep, t_last, col, half);
       load_neg_lse(nl[0], nl_base, 0);
       load_neg_lse(nl[1], nl_base, 1);
+      q_frags_arrived();
       logits_now<HD, 2, 0>(accA, a[0]);
       // Tile s: accA holds the logits of (s, pair 0) and nl the normalisers of pair 0.  Same step structure as pass 1,
-      // walking down; the token's sum is complete after the fourth step and is stored then.
+      // walking down; the token's sum is complete after the fourth step.
 #define CCD_P2_TILE(CB, NB)                                                                          \
       us[0] = 0.f; us[1] = 0.f;                                                                      \
       asm volatile("" : "+v"(nl_base));                                                              \
       pipelined_step<HD, 2, 1>(accB, a[CB], CCD_FOLD2(accA, 1));                                     \
       pipelined_step<HD, 2, 2>(accA, a[CB], CCD_FOLD2(accB, 2));                                     \
       pipelined_step<HD, 2, 3>(accB, a[CB], CCD_FOLD2(accA, 3));                                     \
-      if (s - 2 >= s0) load_k_tile<HD>(a[CB], Ku, tb + (s - 2) * kStep, t_last, col, half);          \
-      if (s - 1 >= s0) {                                                                             \
-        pipelined_step<HD, 2, 0>(accA, a[NB], CCD_FOLD2(accB, 0));                                   \
-      } else {                                                                                       \
-        mma_results_ready(accB);                                                                     \
-        auto fold = CCD_FOLD2(accB, 0);                                                              \
-        _Pragma("unroll") for (int j = 0; j < NM; ++j) fold(j);                                      \
-      }                                                                                              \
+      load_k_tile<HD>(a[CB], Ku, tb + max(s - 2, sa) * kStep, t_last, col, half);                    \
+      pipelined_step<HD, 2, 0>(accA, a[NB], CCD_FOLD2(accB, 0));                                     \
       {                                                                                              \
         float v = us[0] + us[1];                                                                     \
         v += __shfl_xor(v, 32);                                                                      \
-        const int t = tb + s * kStep + col;                                                          \
-        if (half == 0 && t < D.n) uu[t] = (qc == 0) ? v : uu[t] + v;                                 \
+        ub[(s - sa) * kStep + col] = v;      /* (both lane halves hold the same sum) */              \
       }
-      while (true) {
-        if (s < s0) break;
+      while (s - 1 >= sa) {
         CCD_P2_TILE(0, 1)
         --s;
-        if (s < s0) break;
         CCD_P2_TILE(1, 0)
         --s;
       }
+      if (s >= sa) {
+        CCD_P2_TILE(0, 1)
+      }
+      mma_results_ready(accA);        // the surplus logits are in flight until here
 #undef CCD_P2_TILE
 #undef CCD_FOLD2
+      // the block's sums (this wave wrote them, this wave reads them)
+      const int t_blk = tb + sa * kStep, n_blk = min((sb - sa) * kStep, D.n - t_blk);
+      for (int i = lane; i < n_blk; i += 64) uu[t_blk + i] = (qc == 0) ? ub[i] : uu[t_blk + i] + ub[i];
     }
     __syncthreads();   // the LDS tables are rewritten by the next sweep
   }
