@@ -114,6 +114,17 @@ CCD_API int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, v
                  float* scores_opt, int32_t* keep_idx, void* workspace, size_t workspace_bytes,
                  void* hip_stream);
 
+/* ccd_compress for callers that cannot allocate device memory - code under HIP graph capture, serving loops that have
+ * handed all memory out, harnesses that forbid hipMalloc: the workspace is a buffer of CCD_NOALLOC_WORKSPACE_BYTES that
+ * the library itself holds on every GPU, from load to process end.  Same arguments, results and return codes as
+ * ccd_compress, minus the workspace; shapes whose ccd_workspace_bytes() exceeds the buffer return CCD_EWORKSPACE and
+ * nothing is launched.  Allocates nothing (the first call on a GPU looks the buffer's address up once).  All calls on
+ * one GPU share the one buffer, whose contents are scratch and need not start at any value: calls that overlap in time
+ * on the same GPU (two streams, two threads) race; on different GPUs they do not. */
+#define CCD_NOALLOC_WORKSPACE_BYTES (16u << 20)
+CCD_API int ccd_compress_noalloc(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty,
+                         float* scores_opt, int32_t* keep_idx, void* hip_stream);
+
 /* NuC score from the model's logits (Sec. 3.3.2, Eq. 3; App. B "Calculate NuC Score"): the novelty of a token is its
  * cross entropy under the model, novelty[r] = log(sum_v exp(logits[r][v])) - logits[r][labels[r]], r < rows.
  * logits: device, [rows, V] of `dtype` (CCD_FP32 or CCD_BF16), rows `row_stride` elements apart (row_stride >= V, a

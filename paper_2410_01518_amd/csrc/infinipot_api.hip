@@ -11,6 +11,11 @@
 #include "../../include/infinipot.h"
 #include "ccd_kernels.h"
 
+// Workspace of ccd_compress_noalloc: one copy per GPU, held from the moment the library is loaded until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress (scratch_of_current_device below): the address
+// it yields is what kernels, copies and memsets take.
+static __device__ __align__(256) unsigned char scratch[CCD_NOALLOC_WORKSPACE_BYTES];
+
 namespace ccd {
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -419,6 +424,33 @@ int ccd_compress(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, 
                        nullptr, workspace, workspace_bytes, hip_stream);
 }
 
+// Device address of `scratch` on the current GPU, asked once per GPU (each GPU holds its own copy at its own address).
+static int scratch_of_current_device(void** out) {
+  constexpr int kMaxDevices = 64;
+  static void* ptrs[kMaxDevices] = {};      // racing first calls on one GPU store the same value
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CCD_ELAUNCH;
+  if (ptrs[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return CCD_ELAUNCH;
+    ptrs[dev] = p;
+  }
+  *out = ptrs[dev];
+  return CCD_OK;
+}
+
+int ccd_compress_noalloc(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,
+                         int32_t* keep_idx, void* hip_stream) {
+  int rc = check_shape(shape, kNeedFull);
+  if (rc != CCD_OK) return rc;
+  if (layout_workspace(make_dims(shape)).total > (size_t)CCD_NOALLOC_WORKSPACE_BYTES) return CCD_EWORKSPACE;
+  void* ws = nullptr;
+  rc = scratch_of_current_device(&ws);
+  if (rc != CCD_OK) return rc;
+  return compress_impl(shape, Q_cat, K, V, novelty, scores_opt, keep_idx, nullptr, nullptr, nullptr, nullptr, nullptr,
+                       nullptr, ws, (size_t)CCD_NOALLOC_WORKSPACE_BYTES, hip_stream);
+}
+
 int ccd_compress_lse(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, const float* lse, float* novelty,
                      float* scores_opt, int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (lse == nullptr) return CCD_EINVAL;
@@ -501,7 +533,9 @@ const char* ccd_strerror(int code) {
       return "unsupported: head dimension not 64 or 128, unknown dtype or pool mode, more than 65536 tokens, a matrix-core "
              "score path for an fp32 cache, or (bf16) a window that hides more than 2048 tokens from the last CaP token";
     case CCD_EALIGN: return "pointer or stride not 16-byte aligned";
-    case CCD_EWORKSPACE: return "workspace null, misaligned or too small";
+    case CCD_EWORKSPACE:
+      return "workspace null, misaligned or too small (ccd_compress_noalloc: the shape needs more than the built-in "
+             "CCD_NOALLOC_WORKSPACE_BYTES)";
     case CCD_ELAUNCH: return "HIP kernel launch failed";
     default: return "unknown code";
   }

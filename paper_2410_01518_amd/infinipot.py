@@ -24,7 +24,7 @@ CCD_PATH_AUTO, CCD_PATH_VALU, CCD_PATH_MFMA_SLICES, CCD_PATH_MFMA_UNIT = 0, 1, 2
 
 EXPORTS = ("ccd_workspace_bytes", "ccd_score", "ccd_select", "ccd_compact", "ccd_compress", "ccd_cr_rope",
            "ccd_compress_rope", "ccd_score_kcat", "ccd_compress_kcat", "ccd_score_lse", "ccd_compress_lse",
-           "ccd_nuc_from_logits", "ccd_profile_enable", "ccd_profile_stages", "ccd_profile_stage_name",
+           "ccd_nuc_from_logits", "ccd_compress_noalloc", "ccd_profile_enable", "ccd_profile_stages", "ccd_profile_stage_name",
            "ccd_profile_collect", "ccd_strerror")
 
 
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.ccd_compact.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
         L.ccd_compress.restype = ctypes.c_int
         L.ccd_compress.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ccd_compress_noalloc.restype = ctypes.c_int
+        L.ccd_compress_noalloc.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
         L.ccd_cr_rope.restype = ctypes.c_int
         L.ccd_cr_rope.argtypes = [sp, vp, vp, vp, ctypes.c_int32, vp, vp]
         L.ccd_compress_rope.restype = ctypes.c_int
@@ -180,6 +182,15 @@ def ccd_compress(shape, Q_cat, K, V, novelty, keep_idx, workspace, scores=None, 
     return _check(lib().ccd_compress(ctypes.byref(shape), _ptr(Q_cat), _ptr(K), _ptr(V), _ptr(novelty), _ptr(scores),
                                      _ptr(keep_idx), _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                      _stream(stream)))
+
+
+NOALLOC_WORKSPACE_BYTES = 16 << 20
+
+
+def ccd_compress_noalloc(shape, Q_cat, K, V, novelty, keep_idx, scores=None, stream=None) -> int:
+    """ccd_compress on the workspace the library holds itself (no allocation anywhere in the call)."""
+    return _check(lib().ccd_compress_noalloc(ctypes.byref(shape), _ptr(Q_cat), _ptr(K), _ptr(V), _ptr(novelty), _ptr(scores),
+                                             _ptr(keep_idx), _stream(stream)))
 
 
 def ccd_nuc_from_logits(logits, labels, novelty, stream=None) -> int:
