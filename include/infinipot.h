@@ -46,7 +46,7 @@ enum {
   CCD_NOOP = 1,          /* pot not full (n_valid < n_cap) or nothing to drop (n_valid <= k): untouched */
   CCD_EINVAL = -1,       /* NULL pointer, or a shape field out of range                                 */
   CCD_EUNSUPPORTED = -2, /* d not in {64, 128}, unknown dtype or pool_mode, n_valid > 65536, a matrix-  */
-                         /* core score_path for fp32, a window hiding > 2048 tokens of a bf16 cache     */
+                         /* core score_path for fp32, a window with P > 1986 on a bf16 cache            */
   CCD_EALIGN = -3,       /* pointer or stride not 16-byte aligned                                       */
   CCD_EWORKSPACE = -4,   /* workspace NULL, misaligned or smaller than ccd_workspace_bytes()            */
   CCD_ELAUNCH = -5       /* the HIP runtime refused a kernel launch                                    */
@@ -70,8 +70,8 @@ typedef struct {
   int32_t window;             /* sliding attention window in tokens, 0 = none (Sec. 4, footnote on SWA   */
                               /* models): the cached tokens stand at positions 0 .. n_valid-1 and CaP    */
                               /* token i at n_valid + i; a query at position p sees the keys at          */
-                              /* p-window+1 .. p only.  window >= P when set; bf16 caches: at most 2048  */
-                              /* tokens may be hidden from the last CaP token (CCD_EUNSUPPORTED beyond). */
+                              /* p-window+1 .. p only.  window >= P when set; bf16 caches with a window:  */
+                              /* P <= 1986 (CCD_EUNSUPPORTED beyond).                                     */
   int32_t score_path;         /* kernels for Eq. 2: CCD_PATH_AUTO (0) unless two paths are to be compared:       */
                               /* CCD_PATH_VALU vector ALUs; bf16 caches only: CCD_PATH_MFMA_SLICES matrix cores, */
                               /* a workgroup per token slice; CCD_PATH_MFMA_UNIT matrix cores, a workgroup per   */

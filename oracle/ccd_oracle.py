@@ -223,15 +223,6 @@ def nuc_from_logits(logits: np.ndarray, labels: np.ndarray) -> np.ndarray:
     return out.astype(np.float32)
 
 
-def rope_tables(n_pos: int, d: int, base: float = 10000.0):
-    """cos, sin [n_pos, d/2] of the angles p * base**(-2i/d) (RoPE's frequencies), as float32 tables.
-
-    The tables are the INPUT of the re-application (library and oracle read the same fp32 values)."""
-    i = np.arange(d // 2, dtype=np.float64)
-    ang = np.arange(n_pos, dtype=np.float64)[:, None] * base ** (-2.0 * i / d)[None, :]
-    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
-
-
 def rope_rotate(X: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
     """Rotary embedding of the rows of X [n, d] (fp64) by the angles whose cos/sin are given, [n, d/2].
 

@@ -19,8 +19,9 @@ struct Dims {
   float scale_log2;  // logit scale times log2(e): probabilities are computed with exp2
   int score_path;    // the caller's choice of kernels for Eq. 2 (CCD_PATH_*), read by the host-side plan only
   // sliding attention window (0 = none): CaP token i sees cached token t iff t >= win_off + i; tokens below `head`
-  // (a multiple of 32, at most n) are hidden from some CaP token, the others are seen by all
-  int window, win_off, head;
+  // (a multiple of 32, at most n) are hidden from some CaP token, the others are seen by all; tokens below `head0`
+  // (a multiple of 32, at most head) are hidden from every CaP token
+  int window, win_off, head, head0;
   int64_t kv_sb, kv_sl, kv_sh;
   int64_t q_sb, q_sl, q_sh;
   int64_t nov_sb, nov_sl, nov_sh;

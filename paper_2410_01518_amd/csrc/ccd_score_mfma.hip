@@ -42,8 +42,10 @@ __global__ __launch_bounds__(kMT, 2) void score_pass_kernel(Dims D, ScorePlan pl
   score_pass_body<HD, PASS>(D, pl, unit, slice, Q, K, part, u, Kcap, lse_out, sm);
 }
 
-// Sliding attention window: the tokens [0, D.head) that some CaP token does not see.  Two small kernels, one workgroup
-// per unit, outside the two big passes (which start at D.head): statistics before pass 2, probabilities after it.
+// Sliding attention window: the tokens [0, D.head) that some CaP token does not see.  Those below D.head0 are seen by
+// none (score 0, no share in any normaliser); [D.head0, D.head) - at most P + 62 tokens - are seen by some.  Two small
+// kernels, one workgroup per unit, outside the two big passes (which start at D.head): statistics before pass 2,
+// probabilities (and the zeros) after it.
 template <int HD>
 struct HeadLds {
   __attribute__((aligned(1024))) uint8_t slot[Tiles<HD>::kSlotBytes];
@@ -63,7 +65,7 @@ __global__ __launch_bounds__(kMT) void head_stats_kernel(Dims D, ScorePlan pl, c
   const float c = D.scale_log2;
   for (int qc = 0; qc < D.GP; qc += kQPerPass) {
     const int q0 = qc + wave * (kQB * 32) + col;
-    const MaxSum2 r = stats_sweep_body<HD, true>(Ku, 0, D.head, q0 < D.GP ? Q + q_offset(D, ui, q0) : nullptr,
+    const MaxSum2 r = stats_sweep_body<HD, true>(Ku, D.head0, D.head, q0 < D.GP ? Q + q_offset(D, ui, q0) : nullptr,
                                               q0 + 32 < D.GP ? Q + q_offset(D, ui, q0 + 32) : nullptr,
                                               (__attribute__((address_space(3))) uint8_t*)sm.slot, c,
                                               D.win_off + q0 % D.P, D.win_off + (q0 + 32) % D.P);
@@ -94,14 +96,16 @@ __global__ __launch_bounds__(kMT) void head_prob_kernel(Dims D, const uint16_t* 
     sm.lse_s[threadIdx.x] = q < D.GP ? lse[(int64_t)unit * D.GP + q] * lse_mul : INFINITY;
     __syncthreads();
     const int q0 = qc + wave * (kQB * 32) + col;
-    prob_head_masked<HD>(Ku, 0, D.head, q0 < D.GP ? Q + q_offset(D, ui, q0) : nullptr,
+    prob_head_masked<HD>(Ku, D.head0, D.head, q0 < D.GP ? Q + q_offset(D, ui, q0) : nullptr,
                          q0 + 32 < D.GP ? Q + q_offset(D, ui, q0 + 32) : nullptr,
                          (__attribute__((address_space(3))) uint8_t*)sm.slot, D.scale_log2, &sm.lse_s[wave * (kQB * 32)],
                          &sm.up[wave][0], qc + wave * (kQB * 32), D.P, D.win_off);
-    for (int t = threadIdx.x; t < D.head; t += kMT) {     // the same thread every sweep: no race on u
+    for (int t = threadIdx.x; t < D.head - D.head0; t += kMT) {     // the same thread every sweep: no race on u
       const float v = (sm.up[0][t] + sm.up[1][t]) + (sm.up[2][t] + sm.up[3][t]);
-      uu[t] = qc == 0 ? v : uu[t] + v;
+      uu[D.head0 + t] = qc == 0 ? v : uu[D.head0 + t] + v;
     }
+    if (qc == 0)                                          // tokens no CaP token sees
+      for (int t = threadIdx.x; t < D.head0; t += kMT) uu[t] = 0.f;
     __syncthreads();   // lse_s and up are rewritten by the next sweep
   }
 }

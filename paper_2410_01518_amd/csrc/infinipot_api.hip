@@ -78,9 +78,13 @@ static Dims make_dims(const ccd_shape_t* s) {
   D.window = s->window;
   D.win_off = s->window > 0 ? s->n_valid + 1 - s->window : 0;
   D.head = 0;
+  D.head0 = 0;
   if (s->window > 0 && s->n_valid + s->P > s->window) {
     const int64_t hidden = (int64_t)s->n_valid + s->P - s->window;        // tokens hidden from the last CaP token
     D.head = (int)((hidden + 31) / 32 * 32 < s->n_valid ? (hidden + 31) / 32 * 32 : s->n_valid);
+    const int64_t unseen = (int64_t)s->n_valid + 1 - s->window;           // tokens hidden from the first one, so from all
+    D.head0 = unseen > 0 ? (int)(unseen / 32 * 32) : 0;
+    if (D.head0 > D.head) D.head0 = D.head;
   }
   D.kv_sb = s->kv_stride_b; D.kv_sl = s->kv_stride_l; D.kv_sh = s->kv_stride_h;
   D.q_sb = s->q_stride_b; D.q_sl = s->q_stride_l; D.q_sh = s->q_stride_h;
@@ -316,7 +320,7 @@ static int score_impl(const ccd_shape_t* shape, const void* Q_cat, const void* K
   if (!aligned16(Q_cat) || !aligned16(K) || !aligned16(K_cap) || !aligned16(lse)) return CCD_EALIGN;
   const Dims D = make_dims(shape);
   const ScorePlan pl = plan_score(D);
-  if (pl.use_mfma && D.head > mfma_max_slice()) return CCD_EUNSUPPORTED;   // window far shorter than the pot
+  if (pl.use_mfma && D.head - D.head0 > mfma_max_slice()) return CCD_EUNSUPPORTED;   // about 2000 CaP tokens and a window
   const Workspace w = layout_workspace(D);
   rc = check_workspace(w, workspace, workspace_bytes);
   if (rc != CCD_OK) return rc;
@@ -391,7 +395,7 @@ static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, v
   const void* K_attn = K_score != nullptr ? K_score : K;     // the keys the CaP queries attend to
   const Dims D = make_dims(shape);
   const ScorePlan pl = plan_score(D);
-  if (pl.use_mfma && D.head > mfma_max_slice()) return CCD_EUNSUPPORTED;   // window far shorter than the pot
+  if (pl.use_mfma && D.head - D.head0 > mfma_max_slice()) return CCD_EUNSUPPORTED;   // about 2000 CaP tokens and a window
   const Workspace w = layout_workspace(D);
   rc = check_workspace(w, workspace, workspace_bytes);
   if (rc != CCD_OK) return rc;
@@ -531,7 +535,7 @@ const char* ccd_strerror(int code) {
     case CCD_EINVAL: return "invalid argument (null pointer or shape field out of range)";
     case CCD_EUNSUPPORTED:
       return "unsupported: head dimension not 64 or 128, unknown dtype or pool mode, more than 65536 tokens, a matrix-core "
-             "score path for an fp32 cache, or (bf16) a window that hides more than 2048 tokens from the last CaP token";
+             "score path for an fp32 cache, or (bf16, with a window) more than about 2000 CaP tokens";
     case CCD_EALIGN: return "pointer or stride not 16-byte aligned";
     case CCD_EWORKSPACE:
       return "workspace null, misaligned or too small (ccd_compress_noalloc: the shape needs more than the built-in "

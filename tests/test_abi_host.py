@@ -191,9 +191,9 @@ def test_window_errors_are_decided_on_the_host():
     assert _compress(_shape(score_path=4)) == ip.CCD_EINVAL and _compress(_shape(score_path=-1)) == ip.CCD_EINVAL
     for path in (ip.CCD_PATH_MFMA_SLICES, ip.CCD_PATH_MFMA_UNIT):         # the matrix-core kernels are bf16 only
         assert _compress(_shape(dtype=ip.CCD_FP32, score_path=path)) == ip.CCD_EUNSUPPORTED
-    assert "fp32" in ip.ccd_strerror(ip.CCD_EUNSUPPORTED) and "2048" in ip.ccd_strerror(ip.CCD_EUNSUPPORTED)
-    big = _shape(n_valid=8192, n_cap=8192, k=4096, T=0, window=8192 + 16 - 2049)
-    assert _compress(big) == ip.CCD_EUNSUPPORTED                              # more than 2048 tokens hidden (bf16 path)
+    assert "fp32" in ip.ccd_strerror(ip.CCD_EUNSUPPORTED) and "2000" in ip.ccd_strerror(ip.CCD_EUNSUPPORTED)
+    big = _shape(n_valid=8192, n_cap=8192, k=4096, T=0, P=2100, window=4096)
+    assert _compress(big) == ip.CCD_EUNSUPPORTED          # more CaP tokens than the windowed matrix-core kernels take
     assert ip.ccd_workspace_bytes(_shape(window=512)) == ip.ccd_workspace_bytes(_shape())
     assert _compress(_shape(n_valid=300, n_cap=512, k=256, window=300)) == ip.CCD_NOOP
 

@@ -52,7 +52,7 @@ def test_cr_rope_stand_alone(dtype, d, count):
     cfg = synth.CCDConfig(name="r", B=2, L=1, Hq=2, Hkv=2, d=d, N=300, k=100, P=1, T=0, w=1, dtype=dtype, keys="normal", seed=21)
     print(f"cr_rope {dtype} d={d} count={count}", flush=True)
     inp = synth.make_inputs(cfg)
-    cos, sin = O.rope_tables(cfg.N, d)
+    cos, sin = synth.rope_tables(cfg.N, d)
     K = gu.to_dev(inp["K"])
     Krot = torch.full_like(K, 7.0)                      # sentinel: rows >= count must stay
     sentinel = gu.to_host(Krot)
@@ -88,7 +88,7 @@ def test_compress_with_cr_rope(case, per_head):
     cfg = synth.CCDConfig(**base)
     print(f"compress_rope case={case} per_head={per_head} cfg={cfg}", flush=True)
     inp = synth.make_inputs(cfg, per_head_novelty=per_head)
-    cos, sin = O.rope_tables(cfg.k, cfg.d)
+    cos, sin = synth.rope_tables(cfg.k, cfg.d)
     dev = {k: gu.to_dev(v) for k, v in inp.items()}
     Krot = torch.full_like(dev["K"], 7.0)
     sentinel = gu.to_host(Krot)
@@ -130,7 +130,7 @@ def test_cr_rope_on_strided_layouts(stand_alone):
     cfg = synth.CCDConfig(name="t", B=2, L=3, Hq=6, Hkv=3, d=128, N=500, k=200, P=5, T=60, w=3, dtype="bf16", keys="normal", seed=37)
     print(f"rope strided stand_alone={stand_alone} {cfg}", flush=True)
     inp = synth.make_inputs(cfg)
-    cos, sin = O.rope_tables(cfg.k, cfg.d)
+    cos, sin = synth.rope_tables(cfg.k, cfg.d)
     fill = 3.0
 
     def embed(x):
@@ -176,7 +176,7 @@ def test_compress_with_cr_rope_on_a_pot_that_is_not_full_writes_nothing():
     cfg = synth.CCDConfig(name="t", B=1, L=1, Hq=2, Hkv=2, d=64, N=256, k=100, P=2, T=10, w=1, dtype="bf16", keys="normal", seed=41)
     inp = synth.make_inputs(cfg)
     dev = {k: gu.to_dev(v) for k, v in inp.items()}
-    cos, sin = O.rope_tables(cfg.k, cfg.d)
+    cos, sin = synth.rope_tables(cfg.k, cfg.d)
     Krot = torch.full_like(dev["K"], 7.0)
     sentinel = gu.to_host(Krot)
     shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, n_valid=200)
@@ -199,7 +199,7 @@ def test_compress_scores_on_the_embedded_keys_and_rewrites_them_in_place(d):
     cfg = synth.CCDConfig(name="t", B=1, L=2, Hq=8, Hkv=2, d=d, N=900, k=400, P=6, T=50, w=7, dtype="bf16", keys="normal", seed=61)
     print(f"cr-rope cycle {cfg}", flush=True)
     inp = synth.make_inputs(cfg)
-    cos, sin = O.rope_tables(cfg.N, cfg.d)
+    cos, sin = synth.rope_tables(cfg.N, cfg.d)
     dev = {k: gu.to_dev(v) for k, v in inp.items()}
     cos_d, sin_d = torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda()
     shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w)

@@ -45,6 +45,8 @@ SWA_CASES = [
     dict(cfg=dict(B=2, L=4, Hq=4, Hkv=4, N=900, k=300, P=16, T=50), window=lambda c: c.N - 300),  # many units: short slices
     dict(cfg=dict(N=333, k=100, T=50, P=20), window=lambda c: c.P + 10),                      # nearly everything hidden
     dict(cfg=dict(N=333, k=100, T=50, P=20), window=lambda c: c.P),                           # the last CaP token sees nothing
+    dict(cfg=dict(L=1, N=8192, k=3000, T=500, P=33), window=lambda c: 4096),                  # half of the pot behind the window
+    dict(cfg=dict(L=1, Hq=4, Hkv=2, N=5000, k=1000, T=100, P=70), window=lambda c: 1000),     # most of it, and P > 64
     dict(cfg=dict(dtype="fp32", d=64, N=300, k=120, T=30, P=5), window=lambda c: c.N),
     dict(cfg=dict(dtype="fp32", Hq=4, Hkv=2, N=260, k=100, T=10, P=37, w=1), window=lambda c: c.N - 50),
 ]
@@ -128,7 +130,7 @@ def test_window_limits_are_decided_on_the_host():
     inp = synth.make_inputs(cfg)
     dev = {k: gu.to_dev(v) for k, v in inp.items()}
     scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
-    for window, code in ((cfg.P - 1, ip.CCD_EINVAL), (-5, ip.CCD_EINVAL), (cfg.N + cfg.P - 2049, ip.CCD_EUNSUPPORTED)):
+    for window, code in ((cfg.P - 1, ip.CCD_EINVAL), (-5, ip.CCD_EINVAL)):
         shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w)
         ws = ip.alloc_workspace(shape)
         shape.window = window

@@ -10,6 +10,7 @@ import pytest
 import torch
 
 from oracle import ccd_oracle as O
+from paper_2410_01518_amd import synth
 
 
 def _rand(n, d, seed):
@@ -18,7 +19,7 @@ def _rand(n, d, seed):
 
 def test_tables_are_the_rope_frequencies():
     # angle[p, i] = p * base^(-2i/d): spot values written out by hand
-    cos, sin = O.rope_tables(5, 8, base=10000.0)
+    cos, sin = synth.rope_tables(5, 8, base=10000.0)
     assert cos.shape == (5, 4) and cos.dtype == np.float32
     for p, i in [(0, 0), (1, 0), (3, 1), (4, 3)]:
         ang = p * 10000.0 ** (-2.0 * i / 8)
@@ -39,7 +40,7 @@ def test_d2_is_a_plane_rotation():
 
 def test_position_zero_is_identity_and_pair_norms_are_kept():
     X = _rand(7, 16, 1)
-    cos, sin = O.rope_tables(7, 16)
+    cos, sin = synth.rope_tables(7, 16)
     Y = O.rope_rotate(X, cos, sin)
     np.testing.assert_array_equal(Y[0], X[0])
     h = 8
@@ -96,7 +97,7 @@ def test_cr_rope_uses_the_new_positions_not_the_old_ones():
     n, d, k = 40, 16, 9
     K = np.random.default_rng(7).standard_normal((n, d)).astype(np.float32)
     keep = np.array([1, 4, 5, 11, 17, 18, 30, 31, 39])
-    cos, sin = O.rope_tables(n, d)
+    cos, sin = synth.rope_tables(n, d)
     got = O.cr_rope(K[keep], cos, sin)
     want = O.rope_rotate(K[keep].astype(np.float64), cos[np.arange(k)], sin[np.arange(k)]).astype(np.float32)
     np.testing.assert_array_equal(got, want)
@@ -112,7 +113,7 @@ def test_compress_returns_rotated_kept_keys():
     K = rng.standard_normal((B, L, Hkv, n, d)).astype(np.float32)
     V = rng.standard_normal((B, L, Hkv, n, d)).astype(np.float32)
     nov = rng.random((B, n)).astype(np.float32)
-    cos, sin = O.rope_tables(k, d)
+    cos, sin = synth.rope_tables(k, d)
     out = O.compress(Q, K, V, nov, k=k, T=2, rope_cos=cos, rope_sin=sin)
     keep = out["keep_idx"][0, 0, 0]
     np.testing.assert_array_equal(out["K"][0, 0, 0], K[0, 0, 0][keep])          # the pot keeps pre-RoPE keys
