@@ -27,7 +27,9 @@ VALU_FP32_PEAK_TFLOPS = 157.3
 # HBM bytes per launch on the headline config from the committed rocprofv3 counter runs
 # (profiles/ccd_compress_c3_hbm_traffic.md: FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the factors a plain copy of known
 # size gives; equal to read requests x 128 B + write requests x 64 B)
-MEASURED_TRAFFIC_C3 = {"score_stats": 286_600_000, "score_prob": 290_700_000, "select_compact": 543_300_000}
+MEASURED_TRAFFIC_C3 = {"score_stats": 286_600_000, "score_prob": 290_700_000, "select_compact": 543_300_000,
+                       "score_unit": None}
+TRAFFIC_SOURCE = "profiles/ccd_compress_c3_hbm_traffic.md (a committed counter run, not this run)"
 
 
 def algorithmic_bytes(cfg) -> dict:
@@ -59,11 +61,11 @@ def algorithmic_flops(cfg) -> float:
     return 2.0 * cfg.units * cfg.G * cfg.P * cfg.N * cfg.d
 
 
-def stream_bench(args, dev, torch, ip, synth) -> int:
+def stream_measure(reps, dev, torch, ip, synth):
     """Streaming use of the step (Sec. 3.2): a 131072-token context of a 32-layer, 8-KV-head, d 128 model is fed into a
     pot of 4096 in 2048-token chunks (seeded synthetic K, V, novelty already resident in HBM); whenever the next chunk
-    does not fit, the pot is distilled to 2048 first: 62 calls.  Reports the tokens per second of cache maintenance
-    (appends + distillations; novelty is carried per head)."""
+    does not fit, the pot is distilled to 2048 first: 62 calls.  Returns (best seconds per context, calls, all times,
+    algorithmic bytes per context: the 62 calls plus reading and writing every appended chunk)."""
     from paper_2410_01518_amd.pot import MemoryPot
     cfg = synth.CONFIGS["c3"]
     context, chunk = 131072, 2048
@@ -89,17 +91,74 @@ def stream_bench(args, dev, torch, ip, synth) -> int:
         return time.perf_counter() - t0, pot.calls
 
     run()                                         # warm-up: allocations, first launches
-    reps = max(1, min(args.steps, 5))
     times = [run() for _ in range(reps)]
     dt, calls = min(t for t, _ in times), times[0][1]
+    chunk_bytes = 2 * cfg.units * chunk * cfg.d * 2                  # K and V of a chunk
+    nbytes = calls * algorithmic_bytes(cfg)["call"] + (context // chunk) * 2 * chunk_bytes
+    return dt, calls, [t for t, _ in times], nbytes, context
+
+
+def stream_bench(args, dev, torch, ip, synth) -> int:
+    reps = max(1, min(args.steps, 5))
+    dt, calls, times, nbytes, context = stream_measure(reps, dev, torch, ip, synth)
+    gbps = nbytes / dt / 1e9
     print(json.dumps({"metric": "streaming CCD cache maintenance tokens/s (32L x 8KV x 128d, pot 4096 -> 2048, 2048-token chunks)",
                       "value": context / dt, "unit": "tokens/s", "n_gpus": 1, "steps": reps, "warmup": 1,
                       "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
                       "dtype": "bf16", "data": "synthetic",
                       "config": {"workload": f"131072-token context, {calls} ccd_compress calls, per-head novelty",
-                                 "ms_per_context": dt * 1e3, "all_repetitions_ms": [t * 1e3 for t, _ in times]},
-                      "roofline": None, "cpu_baseline": None}))
+                                 "ms_per_context": dt * 1e3, "all_repetitions_ms": [t * 1e3 for t in times]},
+                      "roofline": {"kernel": "whole context (calls + appends)", "bound": "hbm", "achieved": gbps,
+                                   "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS, "traffic": None},
+                      "cpu_baseline": None}))
     return 0
+
+
+def small_config_latency(cfg, dev, torch, ip, synth, calls=40):
+    """Microseconds per ccd_compress call (HIP events around `calls` back-to-back calls, each on its own copy of the pot)
+    of a configuration that is far too small to fill the chip."""
+    host = synth.make_inputs(cfg)
+
+    def upload(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(dev)
+        return torch.from_numpy(a).to(dev)
+
+    d0 = {k: upload(v) for k, v in host.items()}
+    pots = [(d0["K"].clone(), d0["V"].clone()) for _ in range(calls + 4)]
+    shape = ip.make_shape(d0["Q_cat"], pots[0][0], d0["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=ip.CCD_POOL_MAX)
+    ws = ip.alloc_workspace(shape)
+    keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device=dev)
+    for K, V in pots[calls:]:
+        assert ip.ccd_compress(shape, d0["Q_cat"], K, V, d0["novelty"], keep, ws) == ip.CCD_OK
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for K, V in pots[:calls]:
+        ip.ccd_compress(shape, d0["Q_cat"], K, V, d0["novelty"], keep, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / calls
+
+
+def other_configs(dev, torch, ip, synth) -> list:
+    """The benchmark's other single-GPU configurations next to the headline one, a few seconds in all: the tiny fp32
+    call (c1), the single GQA layer (c2) and the streaming use (c4).  (The large-pot configuration needs 43 GB per pot:
+    `--aux stress`.)"""
+    out = []
+    for name in ("c1", "c2"):
+        cfg = synth.CONFIGS[name]
+        us = small_config_latency(cfg, dev, torch, ip, synth)
+        gbps = algorithmic_bytes(cfg)["call"] / (us * 1e-6) / 1e9
+        out.append({"workload": f"{name}: L{cfg.L} Hq{cfg.Hq} Hkv{cfg.Hkv} d{cfg.d} {cfg.dtype} N{cfg.N}->k{cfg.k} P{cfg.P} pool{cfg.w}",
+                    "value": us, "unit": "us per ccd_compress call", "bound": "launch latency (a few workgroups)",
+                    "achieved_GBps": gbps, "frac_of_hbm_peak": gbps / HBM_PEAK_GBPS})
+    dt, calls, times, nbytes, context = stream_measure(2, dev, torch, ip, synth)
+    gbps = nbytes / dt / 1e9
+    out.append({"workload": f"c4: 131072-token context in 2048-token chunks through a pot of 4096, {calls} ccd_compress calls",
+                "value": context / dt, "unit": "tokens/s", "bound": "hbm", "achieved_GBps": gbps,
+                "frac_of_hbm_peak": gbps / HBM_PEAK_GBPS, "ms_per_context": dt * 1e3})
+    return out
 
 
 def stress_bench(args, dev, torch, ip, synth) -> int:
@@ -272,6 +331,11 @@ def main() -> int:
                          "context streamed through a pot of 4096 in 2048-token chunks (62 distillations), stress = the "
                          "large-pot configuration at full size (2560 units, pot 32768 -> 4096, 43 GB per pot)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="leave the other configurations (tiny call, single layer, streaming) out of the JSON line")
+    ap.add_argument("--clock-warmup-ms", type=float, default=300.0,
+                    help="before the W warm-up steps, keep calling on the warm-up pots for this long, so that the timed "
+                         "steps of a short run do not fall into the clock ramp of an idle GPU (reported in the line)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -391,6 +455,21 @@ def main() -> int:
         assert rc == ip.CCD_OK, rc
 
     torch.cuda.synchronize()                             # the inputs were drawn on the default stream
+    # Clock warm-up (untimed, on the pots behind the timed ones, which it compresses over and over): an idle GPU needs
+    # some hundred milliseconds of load to reach its working clocks; a run of 25 calls is over after 7 ms.
+    cw_calls, cw_t0 = 0, time.perf_counter()
+    while args.warmup > 0 and len(pots) >= args.steps + args.warmup and (time.perf_counter() - cw_t0) * 1e3 < args.clock_warmup_ms:
+        for i in range(args.warmup):
+            step(args.steps + i, i % n_streams)
+        cw_calls += args.warmup
+        torch.cuda.synchronize()
+    cw_seconds = time.perf_counter() - cw_t0
+    if cw_calls:                                         # the W warm-up steps proper get full pots again
+        for K, V in pots[args.steps:args.steps + args.warmup]:
+            fresh(K)
+            fresh(V)
+        prepare_lse()
+        torch.cuda.synchronize()
     for i in range(args.warmup):
         step(args.steps + i, i % n_streams)              # the warm-up calls use the pots behind the timed ones
     torch.cuda.synchronize()
@@ -442,8 +521,9 @@ def main() -> int:
         else:
             r = {"kernel": stage, "bound": "hbm", "achieved": ab[stage] / t / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
         r["frac"] = r["achieved"] / r["peak"]
-        r["traffic"] = MEASURED_TRAFFIC_C3.get(stage) if cfg.name == "c3" and args.score_path == 0 and not args.rope and not args.kcat and not args.window and not args.lse else None
-        r["traffic_source"] = "profiles/ccd_compress_c3_hbm_traffic.md" if r["traffic"] else None
+        plain = cfg.name == "c3" and args.score_path == 0 and not (args.rope or args.kcat or args.window or args.lse)
+        r["traffic"] = MEASURED_TRAFFIC_C3.get(stage) if plain else None
+        r["traffic_source"] = TRAFFIC_SOURCE if r["traffic"] else None
         r["avg_us"] = stage_avg_us[stage]
         return r
 
@@ -467,10 +547,20 @@ def main() -> int:
                                f"P{cfg.P} T{cfg.T} pool{cfg.w}", "ring": [len(pots), len(qsets), len(novs)], "score_path": args.score_path,
                    "cap_keys_in_softmax": bool(args.kcat), "window": args.window,
                    "per_head_novelty": bool(args.per_head_novelty), "lse_given": bool(args.lse), "streams": n_streams},
+        # the figure the target is stated on: the whole call's algorithmic bytes against the HBM peak
+        "roofline_call": {"kernel": "whole call", "bound": "hbm", "achieved": call_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                          "frac": call_gbps / HBM_PEAK_GBPS, "algorithmic_bytes": ab["call"], "target_frac": 0.70},
         "call_hbm": {"algorithmic_bytes": ab["call"], "achieved_GBps": call_gbps, "frac_of_peak": call_gbps / HBM_PEAK_GBPS},
         "stage_avg_us": stage_avg_us, "moved_row_fraction": moved,
+        # the kernel with the largest average duration (HIP events around every kernel, second pass over the same steps)
         "roofline": roof, "roofline_other_kernels": by_kernel,
+        "clock_warmup": {"seconds": cw_seconds, "calls": cw_calls},
     }
+    plain_headline = cfg.name == "c3" and not (args.rope or args.kcat or args.window or args.lse or args.per_head_novelty)
+    if plain_headline and not args.no_other_configs:
+        del pots, lanes                                   # make room: the streaming leg holds 3 GiB of its own
+        torch.cuda.empty_cache()
+        out["other_configs"] = other_configs(dev, torch, ip, synth)
 
     if not args.no_cpu_baseline:
         from oracle import ccd_oracle as O   # CPU baseline leg only
