@@ -28,7 +28,7 @@ VALU_FP32_PEAK_TFLOPS = 157.3
 # (profiles/ccd_compress_c3_hbm_traffic.md: FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the factors a plain copy of known
 # size gives; equal to read requests x 128 B + write requests x 64 B)
 MEASURED_TRAFFIC_C3 = {"score_stats": 286_600_000, "score_prob": 290_700_000, "select_compact": 543_300_000,
-                       "score_unit": None}
+                       "score_unit": 525_400_000}
 TRAFFIC_SOURCE = "profiles/ccd_compress_c3_hbm_traffic.md (a committed counter run, not this run)"
 
 
