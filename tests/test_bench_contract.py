@@ -47,5 +47,11 @@ def test_json_line_has_the_contract_keys():
     assert "workload" in d["config"] and "model" not in d["config"]
     roof = d["roofline"]
     assert roof["bound"] in ("hbm", "mfma", "alu") and abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-12
+    call = d["roofline_call"]                      # the whole call against the HBM peak: the figure the target is stated on
+    assert call["bound"] == "hbm" and call["peak"] == 8000.0 and abs(call["frac"] - call["achieved"] / call["peak"]) < 1e-12
+    assert abs(call["achieved"] - call["algorithmic_bytes"] / (d["ms_per_step"] * 1e-3) / 1e9) < 1e-6 * call["achieved"]
+    assert d["clock_warmup"]["calls"] >= 0
+    other = d["other_configs"]                     # the tiny call, the single layer and the streaming use
+    assert [o["workload"][:2] for o in other] == ["c1", "c2", "c4"] and all(o["value"] > 0 for o in other)
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and "units" in cb["sample"]

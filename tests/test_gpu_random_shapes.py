@@ -73,7 +73,10 @@ def test_random_shape_long_rows_or_many_units(seed):
 
 
 def _run(seed, cfg, pool_mode, per_head, with_cap, window):
-    print(f"random shape {seed}: {cfg} pool_mode={pool_mode} per_head={per_head} with_cap={with_cap} window={window}", flush=True)
+    # bf16 caches: the automatic choice of score kernels, or one of the two matrix-core kernels by force
+    path = [ip.CCD_PATH_AUTO, ip.CCD_PATH_MFMA_SLICES, ip.CCD_PATH_MFMA_UNIT][seed % 3] if cfg.dtype == "bf16" else ip.CCD_PATH_AUTO
+    print(f"random shape {seed}: {cfg} pool_mode={pool_mode} per_head={per_head} with_cap={with_cap} window={window} "
+          f"path={path}", flush=True)
     inp = synth.make_inputs(cfg, per_head_novelty=per_head)
     if seed % 5 == 0:                                    # ties and tokens that may not take a NuC slot
         inp["novelty"] = np.round(inp["novelty"], 1)
@@ -82,7 +85,7 @@ def _run(seed, cfg, pool_mode, per_head, with_cap, window):
     K_cap = synth.cap_keys(cfg) if with_cap else None
     dev = {k: gu.to_dev(v) for k, v in inp.items()}
     shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=pool_mode,
-                          window=window)
+                          window=window, score_path=path)
     ws = ip.alloc_workspace(shape)
     keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device="cuda")
     scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
