@@ -437,9 +437,11 @@ def main() -> int:
     k_cap_h = synth.cap_keys(cfg) if args.kcat else None
     k_cap = upload(k_cap_h) if args.kcat else None
 
-    def step(i, lane=0):
+    def step(i, lane=0, keep_out=None):
         K, V = pots[i % len(pots)]
         stream, ws, keep = lanes[lane]
+        if keep_out is not None:
+            keep = keep_out
         if args.rope:
             p = i % len(pots)
             rc = ip.ccd_compress_rope(shape, qsets[p % len(qsets) if args.lse else i % len(qsets)], K, V, novs[i % len(novs)],
@@ -455,24 +457,31 @@ def main() -> int:
         assert rc == ip.CCD_OK, rc
 
     torch.cuda.synchronize()                             # the inputs were drawn on the default stream
-    # Clock warm-up (untimed, on the pots behind the timed ones, which it compresses over and over): an idle GPU needs
-    # some hundred milliseconds of load to reach its working clocks; a run of 25 calls is over after 7 ms.
-    cw_calls, cw_t0 = 0, time.perf_counter()
-    while args.warmup > 0 and len(pots) >= args.steps + args.warmup and (time.perf_counter() - cw_t0) * 1e3 < args.clock_warmup_ms:
+
+    def warm_up():
+        """Clock warm-up (untimed, on the pots behind the timed ones, which it compresses over and over): an idle GPU
+        needs some hundred milliseconds of load to reach its working clocks, and a run of 25 calls is over after 7 ms.
+        Then the W warm-up steps proper, on full pots again.  Returns (calls, seconds) of the clock warm-up."""
+        calls, t_start = 0, time.perf_counter()
+        while (args.warmup > 0 and len(pots) >= args.steps + args.warmup
+               and (time.perf_counter() - t_start) * 1e3 < args.clock_warmup_ms):
+            for i in range(args.warmup):
+                step(args.steps + i, i % n_streams)
+            calls += args.warmup
+            torch.cuda.synchronize()
+        seconds = time.perf_counter() - t_start
+        if calls:
+            for K, V in pots[args.steps:args.steps + args.warmup]:
+                fresh(K)
+                fresh(V)
+            prepare_lse()
+            torch.cuda.synchronize()
         for i in range(args.warmup):
-            step(args.steps + i, i % n_streams)
-        cw_calls += args.warmup
+            step(args.steps + i, i % n_streams)          # the warm-up calls use the pots behind the timed ones
         torch.cuda.synchronize()
-    cw_seconds = time.perf_counter() - cw_t0
-    if cw_calls:                                         # the W warm-up steps proper get full pots again
-        for K, V in pots[args.steps:args.steps + args.warmup]:
-            fresh(K)
-            fresh(V)
-        prepare_lse()
-        torch.cuda.synchronize()
-    for i in range(args.warmup):
-        step(args.steps + i, i % n_streams)              # the warm-up calls use the pots behind the timed ones
-    torch.cuda.synchronize()
+        return calls, seconds
+
+    cw_calls, cw_seconds = warm_up()
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(i, i % n_streams)
@@ -480,23 +489,26 @@ def main() -> int:
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
-    # the same K steps again with an event after every kernel: per-kernel average durations
-    # (between the bracketed kernels of that pass: which fraction of the kept rows each call really moved)
+    # The same K steps again, back to back as in the timed region, every kernel launched with a pair of events that take
+    # its own begin and end time stamps: per-kernel average durations.  (Kept out of the timed region: the completion
+    # signal that every kernel then carries costs 3 - 4 us per kernel between launches.)  Each call writes its keep_idx
+    # to a buffer of its own, from which the fraction of kept rows that really moved is taken afterwards.
     refill()
     prepare_lse()
-    torch.cuda.synchronize()
-    ar = torch.arange(cfg.k, device=dev)
-    moved_acc = torch.zeros((), device=dev)
+    keeps = [torch.empty_like(keep) for _ in range(args.steps)]
+    warm_up()                                            # as before the timed region
     ip.ccd_profile_enable(True)
     for i in range(args.steps):
-        step(i)
-        moved_acc += (keep.to(torch.int64) != ar).float().mean()
+        step(i, keep_out=keeps[i])
+    torch.cuda.synchronize()
     stage_ms, calls = ip.ccd_profile_collect()
     ip.ccd_profile_enable(False)
     stage_avg_us = {k: 1e3 * v / max(calls, 1) for k, v in stage_ms.items()}
 
     # how much of the cache a call actually moves (rows with keep_idx[j] != j), mean over the profiled calls
-    moved = float(moved_acc.item()) / max(args.steps, 1)
+    ar = torch.arange(cfg.k, device=dev)
+    moved = float(sum((kp.to(torch.int64) != ar).float().mean().item() for kp in keeps)) / max(args.steps, 1)
+    del keeps
 
     ab = algorithmic_bytes(cfg)
     keep_bytes = cfg.units * cfg.k * 4

@@ -187,8 +187,9 @@ CCD_API int ccd_compress_lse(const ccd_shape_t* shape, const void* Q_cat, void* 
 
 /* Per-kernel timing of ccd_compress for benchmarks: a host-side aid, off by default, and the only state the library
  * keeps between calls (process-wide: enable it from one thread, for calls on one stream).  While enabled, each
- * kernel of ccd_compress is bracketed by two HIP events on the stream it runs on (events are created on demand
- * and reused; nothing else changes).  ccd_profile_collect waits for the recorded
+ * kernel of ccd_compress is launched with two HIP events attached that take the kernel's own begin and end time
+ * stamps (hipExtLaunchKernel; events are created on demand and reused; nothing is put into the stream between the
+ * kernels and nothing else changes).  ccd_profile_collect waits for those
  * events, adds up the elapsed milliseconds per stage into stage_ms[ccd_profile_stages()] (host array) and stores
  * the number of calls covered in *calls (host), then forgets them.  Stage i is named ccd_profile_stage_name(i).
  * Not thread safe; meant for one stream. */

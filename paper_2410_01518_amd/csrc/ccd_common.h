@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "ccd_kernels.h"
+#include "ccd_launch.h"
 
 namespace ccd {
 

@@ -274,7 +274,7 @@ void launch_select_compact(const Dims& D, const float* u, float* novelty, bool c
   const bool split = parts > 1;
   const dim3 grid((unsigned)D.units_run * parts), block(kCpThreads);
 #define CCD_LAUNCH(KPT, RB, ROPE, BF, SPLIT)                                                                           \
-  hipLaunchKernelGGL((select_compact_kernel<KPT, RB, ROPE, BF, SPLIT>), grid, block, 0, s, D, u, novelty,                \
+  launch((select_compact_kernel<KPT, RB, ROPE, BF, SPLIT>), grid, block, s, D, u, novelty,                \
                      (carry_novelty && !SPLIT) ? 1 : 0, scores, keep_idx, (char*)K, (char*)V, rope_cos, rope_sin,        \
                      (char*)Krot, parts)
 #define CCD_LAUNCH_RB(KPT, ROPE, SPLIT)                                           \
@@ -294,7 +294,7 @@ void launch_select_compact(const Dims& D, const float* u, float* novelty, bool c
 #undef CCD_LAUNCH_RB
 #undef CCD_LAUNCH
   if (split && carry_novelty)
-    hipLaunchKernelGGL(compact_novelty_kernel, dim3(D.units_run), block, 0, s, D, keep_idx, novelty);
+    launch(compact_novelty_kernel, dim3(D.units_run), block, s, D, keep_idx, novelty);
 }
 
 void launch_rope_rows(const Dims& D, const void* K, const float* rope_cos, const float* rope_sin, int count, void* Krot,
@@ -303,7 +303,7 @@ void launch_rope_rows(const Dims& D, const void* K, const float* rope_cos, const
   const int rows_per_block = 256 / (rowb / 16) * kRopeUnroll;
   const dim3 grid((unsigned)((count + rows_per_block - 1) / rows_per_block) * (unsigned)D.units_run), block(256);
 #define CCD_LAUNCH(RB, BF) \
-  hipLaunchKernelGGL((rope_rows_kernel<RB, BF>), grid, block, 0, s, D, (const char*)K, rope_cos, rope_sin, count, (char*)Krot)
+  launch((rope_rows_kernel<RB, BF>), grid, block, s, D, (const char*)K, rope_cos, rope_sin, count, (char*)Krot)
   if (rowb == 128) CCD_LAUNCH(128, true);
   else if (rowb == 256 && D.dtype == 1) CCD_LAUNCH(256, true);
   else if (rowb == 256) CCD_LAUNCH(256, false);
@@ -316,14 +316,14 @@ void launch_compact(const Dims& D, const void* Ksrc, const void* Vsrc, const int
   const int rowb = D.d * (D.dtype == 0 ? 4 : 2);
   dim3 grid(2u * D.units_run), block(kCpThreads);
 #define CCD_LAUNCH(RB)                                                                                             \
-  hipLaunchKernelGGL((compact_rows_kernel<RB>), grid, block, 0, s, D, (const char*)Ksrc, (const char*)Vsrc, keep_idx, \
+  launch((compact_rows_kernel<RB>), grid, block, s, D, (const char*)Ksrc, (const char*)Vsrc, keep_idx, \
                      (char*)Kdst, (char*)Vdst)
   if (rowb == 128) CCD_LAUNCH(128);
   else if (rowb == 256) CCD_LAUNCH(256);
   else CCD_LAUNCH(512);
 #undef CCD_LAUNCH
   if (novelty != nullptr)
-    hipLaunchKernelGGL(compact_novelty_kernel, dim3(D.units_run), block, 0, s, D, keep_idx, novelty);
+    launch(compact_novelty_kernel, dim3(D.units_run), block, s, D, keep_idx, novelty);
 }
 
 }  // namespace ccd

@@ -108,10 +108,10 @@ void launch_nuc_from_logits(const void* logits, const int32_t* labels, float* no
                             int64_t row_stride_elems, int dtype, hipStream_t s) {
   const dim3 grid((unsigned)rows), block(kNucThreads);
   if (dtype == 1)
-    hipLaunchKernelGGL((nuc_from_logits_kernel<true>), grid, block, 0, s, (const char*)logits, labels, novelty, V,
+    launch((nuc_from_logits_kernel<true>), grid, block, s, (const char*)logits, labels, novelty, V,
                        row_stride_elems * 2);
   else
-    hipLaunchKernelGGL((nuc_from_logits_kernel<false>), grid, block, 0, s, (const char*)logits, labels, novelty, V,
+    launch((nuc_from_logits_kernel<false>), grid, block, s, (const char*)logits, labels, novelty, V,
                        row_stride_elems * 4);
 }
 

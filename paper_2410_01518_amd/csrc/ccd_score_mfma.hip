@@ -119,19 +119,19 @@ int mfma_max_slice() { return kMaxSlice; }
 void launch_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s) {
   dim3 grid(stats_grid(D, pl)), block(kMT);
   if (D.d == 64)
-    hipLaunchKernelGGL((score_pass_kernel<64, 1>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
+    launch((score_pass_kernel<64, 1>), grid, block, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
                        (float*)nullptr, (const uint16_t*)nullptr, (float*)nullptr);
   else
-    hipLaunchKernelGGL((score_pass_kernel<128, 1>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
+    launch((score_pass_kernel<128, 1>), grid, block, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part,
                        (float*)nullptr, (const uint16_t*)nullptr, (float*)nullptr);
 }
 
 void launch_head_stats_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s) {
   dim3 grid((unsigned)D.units_run), block(kMT);
   if (D.d == 64)
-    hipLaunchKernelGGL((head_stats_kernel<64>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part);
+    launch((head_stats_kernel<64>), grid, block, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part);
   else
-    hipLaunchKernelGGL((head_stats_kernel<128>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part);
+    launch((head_stats_kernel<128>), grid, block, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part);
 }
 
 void launch_head_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float* lse, float* u,
@@ -139,9 +139,9 @@ void launch_head_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, co
   const float lse_mul = pl.lse_given ? 1.44269504088896340736f : 1.0f;
   dim3 grid((unsigned)D.units_run), block(kMT);
   if (D.d == 64)
-    hipLaunchKernelGGL((head_prob_kernel<64>), grid, block, 0, s, D, (const uint16_t*)Q, (const uint16_t*)K, lse, lse_mul, u);
+    launch((head_prob_kernel<64>), grid, block, s, D, (const uint16_t*)Q, (const uint16_t*)K, lse, lse_mul, u);
   else
-    hipLaunchKernelGGL((head_prob_kernel<128>), grid, block, 0, s, D, (const uint16_t*)Q, (const uint16_t*)K, lse, lse_mul, u);
+    launch((head_prob_kernel<128>), grid, block, s, D, (const uint16_t*)Q, (const uint16_t*)K, lse, lse_mul, u);
 }
 
 // K_cap (nullable; [units, P, d] bf16): the CaP tokens' own keys join the softmax, causally
@@ -149,10 +149,10 @@ void launch_prob_mfma(const Dims& D, const ScorePlan& pl, const void* Q, const v
                       const float2* part, float* u, float* lse_io, hipStream_t s) {
   dim3 grid((unsigned)((D.units_run + 7) / 8 * 8) * pl.n_slices2), block(kMT);
   if (D.d == 64)
-    hipLaunchKernelGGL((score_pass_kernel<64, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
+    launch((score_pass_kernel<64, 2>), grid, block, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
                        const_cast<float2*>(part), u, (const uint16_t*)K_cap, lse_io);
   else
-    hipLaunchKernelGGL((score_pass_kernel<128, 2>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
+    launch((score_pass_kernel<128, 2>), grid, block, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K,
                        const_cast<float2*>(part), u, (const uint16_t*)K_cap, lse_io);
 }
 

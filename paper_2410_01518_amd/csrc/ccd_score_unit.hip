@@ -462,10 +462,10 @@ void launch_score_unit(const Dims& D, const ScorePlan& pl, const void* Q, const 
                        const float2* part, float* u, float* lse_io, hipStream_t s) {
   dim3 grid((unsigned)D.units_run), block(kMT);
   if (D.d == 64)
-    hipLaunchKernelGGL((score_unit_kernel<64>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part, u,
+    launch((score_unit_kernel<64>), grid, block, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part, u,
                        (const uint16_t*)K_cap, lse_io);
   else
-    hipLaunchKernelGGL((score_unit_kernel<128>), grid, block, 0, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part, u,
+    launch((score_unit_kernel<128>), grid, block, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part, u,
                        (const uint16_t*)K_cap, lse_io);
 }
 

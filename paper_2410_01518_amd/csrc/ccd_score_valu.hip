@@ -226,7 +226,7 @@ __global__ __launch_bounds__(kThreads) void prob_valu_kernel(Dims D, ScorePlan p
 void launch_stats_valu(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s) {
   dim3 grid((unsigned)pl.n_slices1 * D.units_run), block(kThreads);
 #define CCD_LAUNCH(T, HD) \
-  hipLaunchKernelGGL((stats_valu_kernel<T, HD>), grid, block, 0, s, D, pl, (const T*)Q, (const T*)K, part)
+  launch((stats_valu_kernel<T, HD>), grid, block, s, D, pl, (const T*)Q, (const T*)K, part)
   if (D.dtype == 0) { if (D.d == 64) CCD_LAUNCH(float, 64); else CCD_LAUNCH(float, 128); }
   else              { if (D.d == 64) CCD_LAUNCH(uint16_t, 64); else CCD_LAUNCH(uint16_t, 128); }
 #undef CCD_LAUNCH
@@ -236,7 +236,7 @@ void launch_cap_block_stats_valu(const Dims& D, const ScorePlan& pl, const void*
                                  hipStream_t s) {
   dim3 grid((unsigned)D.units_run), block(kThreads);
 #define CCD_LAUNCH(T, HD) \
-  hipLaunchKernelGGL((cap_block_stats_valu_kernel<T, HD>), grid, block, 0, s, D, pl, (const T*)Q, (const T*)K_cap, part)
+  launch((cap_block_stats_valu_kernel<T, HD>), grid, block, s, D, pl, (const T*)Q, (const T*)K_cap, part)
   if (D.dtype == 0) { if (D.d == 64) CCD_LAUNCH(float, 64); else CCD_LAUNCH(float, 128); }
   else              { if (D.d == 64) CCD_LAUNCH(uint16_t, 64); else CCD_LAUNCH(uint16_t, 128); }
 #undef CCD_LAUNCH
@@ -244,7 +244,7 @@ void launch_cap_block_stats_valu(const Dims& D, const ScorePlan& pl, const void*
 
 void launch_merge(const Dims& D, const ScorePlan& pl, const float2* part, float* lse2, hipStream_t s) {
   dim3 grid((unsigned)((D.GP + kThreads - 1) / kThreads) * D.units_run), block(kThreads);
-  hipLaunchKernelGGL(merge_kernel, grid, block, 0, s, D, pl, part, lse2);
+  launch(merge_kernel, grid, block, s, D, pl, part, lse2);
 }
 
 void launch_prob_valu(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const float* lse2, float* u,
@@ -252,7 +252,7 @@ void launch_prob_valu(const Dims& D, const ScorePlan& pl, const void* Q, const v
   dim3 grid((unsigned)pl.n_slices2 * D.units_run), block(kThreads);
   const float lse_mul = pl.lse_given ? 1.44269504088896340736f : 1.0f;
 #define CCD_LAUNCH(T, HD) \
-  hipLaunchKernelGGL((prob_valu_kernel<T, HD>), grid, block, 0, s, D, pl, (const T*)Q, (const T*)K, lse2, lse_mul, u)
+  launch((prob_valu_kernel<T, HD>), grid, block, s, D, pl, (const T*)Q, (const T*)K, lse2, lse_mul, u)
   if (D.dtype == 0) { if (D.d == 64) CCD_LAUNCH(float, 64); else CCD_LAUNCH(float, 128); }
   else              { if (D.d == 64) CCD_LAUNCH(uint16_t, 64); else CCD_LAUNCH(uint16_t, 128); }
 #undef CCD_LAUNCH

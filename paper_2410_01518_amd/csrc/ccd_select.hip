@@ -33,7 +33,7 @@ void launch_finalize_select(const Dims& D, const float* u, const float* novelty,
                             hipStream_t s) {
   const dim3 grid(D.units_run), block(kSelThreads);
   const int kpt = (D.n + kSelThreads - 1) / kSelThreads;
-#define CCD_LAUNCH(KPT) hipLaunchKernelGGL((finalize_select_kernel<KPT>), grid, block, 0, s, D, u, novelty, scores, keep_idx)
+#define CCD_LAUNCH(KPT) launch((finalize_select_kernel<KPT>), grid, block, s, D, u, novelty, scores, keep_idx)
   if (kpt <= 4) CCD_LAUNCH(4);
   else if (kpt <= 16) CCD_LAUNCH(16);
   else if (kpt <= 32) CCD_LAUNCH(32);

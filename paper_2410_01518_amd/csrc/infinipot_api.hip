@@ -10,6 +10,7 @@
 
 #include "../../include/infinipot.h"
 #include "ccd_kernels.h"
+#include "ccd_launch.h"
 
 // Workspace of ccd_compress_noalloc: one copy per GPU, held from the moment the library is loaded until the process
 // ends.  In host code this name is only a handle for hipGetSymbolAddress (scratch_of_current_device below): the address
@@ -185,32 +186,35 @@ enum Stage { kStStats = 0, kStMerge, kStProb, kStSelect, kStCompact, kStSelCompa
 static const char* const kStageNames[kNumStages] = {"score_stats", "score_merge",    "score_prob", "select",     "compact",
                                                     "select_compact", "cap_block",   "window_head", "score_unit"};
 
-// Every profiled launch is bracketed by two events on the stream it runs on.
+// A timed stage owns two events; the kernels launched while it is open take them along (ccd_launch.h): the first
+// kernel's begin stamp and the last kernel's end stamp are what the stage reports.
+StageTimer* g_stage_timer = nullptr;
 struct Profiler {
   bool on = false;
   std::vector<hipEvent_t> pool;       // every event ever created
   size_t used = 0;                    // events handed out since the last collect
   std::vector<int> stage_of;          // stage of the span that starts at event 2*i
   int64_t calls = 0;
+  StageTimer timer{nullptr, nullptr, false};
   hipEvent_t next() {
     if (used == pool.size()) {
       hipEvent_t e;
-      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+      // (no system-scope fence with these events: cache write-backs and invalidations at every kernel boundary would
+      // change the very durations being measured)
+      if (hipEventCreateWithFlags(&e, hipEventDisableSystemFence) != hipSuccess) return nullptr;
       pool.push_back(e);
     }
     return pool[used++];
   }
-  void begin(int stage, hipStream_t st) {
+  void begin(int stage, hipStream_t) {
     if (!on) return;
-    hipEvent_t e = next();
-    if (e) (void)hipEventRecord(e, st);
+    timer.start = next();
+    timer.stop = next();
+    timer.first = true;
     stage_of.push_back(stage);
+    if (timer.start && timer.stop) g_stage_timer = &timer;
   }
-  void end(hipStream_t st) {
-    if (!on) return;
-    hipEvent_t e = next();
-    if (e) (void)hipEventRecord(e, st);
-  }
+  void end(hipStream_t) { g_stage_timer = nullptr; }
 };
 static Profiler g_prof;
 
@@ -522,6 +526,7 @@ int ccd_profile_collect(double* stage_ms, int64_t* calls) {
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, g_prof.pool[i], g_prof.pool[i + 1]) == hipSuccess) stage_ms[g_prof.stage_of[i / 2]] += ms;
   }
+  (void)hipGetLastError();    // a stage that launched nothing leaves two unused events and an error of the query
   g_prof.used = 0;
   g_prof.stage_of.clear();
   g_prof.calls = 0;

@@ -469,3 +469,58 @@ def test_compress_in_a_captured_graph_replays_exactly():
         got = (gu.to_host(scores).view(np.uint32), gu.to_host(keep), gu.to_host(dev["K"]), gu.to_host(dev["V"]))
         for a, b in zip(want, got):
             np.testing.assert_array_equal(a, b)
+
+
+def test_interleaved_calls_with_different_score_paths_do_not_affect_each_other():
+    """The score path is an argument of the call (shape.score_path), not a setting of the library: calls that ask for
+    different paths, issued alternately from two host threads on two streams, each give the bits the same call gives
+    when it runs alone."""
+    import threading
+    cfgs = [_cfg(L=3, N=1300, k=600, T=150, seed=61), _cfg(L=2, N=900, k=400, T=90, seed=62),
+            _cfg(L=2, N=1100, k=512, T=128, seed=63)]
+    paths = [ip.CCD_PATH_VALU, ip.CCD_PATH_MFMA_SLICES, ip.CCD_PATH_MFMA_UNIT]
+    inps = [synth.make_inputs(c) for c in cfgs]
+    alone = []
+    for cfg, inp, path in zip(cfgs, inps, paths):
+        rc, dev, scores, keep = _run_fused(cfg, inp, score_path=path)
+        assert rc == ip.CCD_OK
+        alone.append((gu.to_host(scores).view(np.uint32), gu.to_host(keep), gu.to_host(dev["K"]), gu.to_host(dev["V"])))
+    # two paths on the same inputs differ in rounding order, so the check below can tell them apart
+    rc, _, s_other, _ = _run_fused(cfgs[0], inps[0], score_path=paths[2])
+    assert rc == ip.CCD_OK and not np.array_equal(gu.to_host(s_other).view(np.uint32), alone[0][0])
+
+    reps, errors = 4, []
+    results = [[None] * reps for _ in cfgs]
+
+    def worker(i):
+        try:
+            cfg, inp, path = cfgs[i], inps[i], paths[i]
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for rep in range(reps):
+                    dev = _upload(inp)
+                    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w,
+                                          pool_mode=O.POOL_MAX, score_path=path)
+                    ws = ip.alloc_workspace(shape)
+                    scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
+                    keep = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.k), dtype=torch.int32, device="cuda")
+                    rc = ip.ccd_compress(shape, dev["Q_cat"], dev["K"], dev["V"], dev["novelty"], keep, ws, scores=scores,
+                                         stream=stream)
+                    assert rc == ip.CCD_OK
+                    stream.synchronize()
+                    results[i][rep] = (gu.to_host(scores).view(np.uint32), gu.to_host(keep), gu.to_host(dev["K"]),
+                                       gu.to_host(dev["V"]))
+        except Exception as e:                                # pragma: no cover - reported by the assert below
+            errors.append((i, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(len(cfgs))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for i in range(len(cfgs)):
+        for rep in range(reps):
+            for a, b in zip(alone[i], results[i][rep]):
+                np.testing.assert_array_equal(a, b)
