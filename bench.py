@@ -388,6 +388,9 @@ def main() -> int:
         for K, V in pots[1:]:
             fresh(K)
             fresh(V)
+        if args.per_head_novelty:
+            for nv in novs:
+                nv.uniform_(generator=g)
 
     pots = [(dev0["K"], dev0["V"])] + [(fresh(torch.empty_like(dev0["K"])), fresh(torch.empty_like(dev0["V"])))
                                        for _ in range(1, n_pots)]
@@ -395,7 +398,8 @@ def main() -> int:
     nov_shape = (cfg.B, cfg.L, cfg.Hkv, cfg.N) if args.per_head_novelty else (cfg.B, cfg.N)
     novs = [dev0["novelty"]] + [torch.rand(nov_shape, generator=g, device=dev, dtype=torch.float32) for _ in range(4)]
     if args.per_head_novelty:
-        novs = novs[1:]
+        # carried novelty is compacted with the pot it belongs to: one array per pot, redrawn whenever the pot is
+        novs = [torch.rand(nov_shape, generator=g, device=dev, dtype=torch.float32) for _ in range(n_pots)]
     shape = ip.make_shape(qsets[0], pots[0][0], novs[0], k=cfg.k, T=cfg.T, pool_w=cfg.w, pool_mode=ip.CCD_POOL_MAX,
                           window=args.window, score_path=args.score_path)
     ws = ip.alloc_workspace(shape)
@@ -474,6 +478,9 @@ def main() -> int:
             for K, V in pots[args.steps:args.steps + args.warmup]:
                 fresh(K)
                 fresh(V)
+            if args.per_head_novelty:
+                for nv in novs[args.steps:args.steps + args.warmup]:
+                    nv.uniform_(generator=g)
             prepare_lse()
             torch.cuda.synchronize()
         for i in range(args.warmup):
