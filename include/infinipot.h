@@ -46,7 +46,8 @@ enum {
   CCD_NOOP = 1,          /* pot not full (n_valid < n_cap) or nothing to drop (n_valid <= k): untouched */
   CCD_EINVAL = -1,       /* NULL pointer, or a shape field out of range                                 */
   CCD_EUNSUPPORTED = -2, /* d not in {64, 128}, unknown dtype or pool_mode, n_valid > 65536, a matrix-  */
-                         /* core score_path for fp32, a window with P > 1986 on a bf16 cache            */
+                         /* core score_path that an fp32 cache cannot take (see score_path), a window  */
+                         /* with P > 1986 on a bf16 cache                                               */
   CCD_EALIGN = -3,       /* pointer or stride not 16-byte aligned                                       */
   CCD_EWORKSPACE = -4,   /* workspace NULL, misaligned or smaller than ccd_workspace_bytes()            */
   CCD_ELAUNCH = -5       /* the HIP runtime refused a kernel launch                                    */
@@ -73,9 +74,13 @@ typedef struct {
                               /* p-window+1 .. p only.  window >= P when set; bf16 caches with a window:  */
                               /* P <= 1986 (CCD_EUNSUPPORTED beyond).                                     */
   int32_t score_path;         /* kernels for Eq. 2: CCD_PATH_AUTO (0) unless two paths are to be compared:       */
-                              /* CCD_PATH_VALU vector ALUs; bf16 caches only: CCD_PATH_MFMA_SLICES matrix cores, */
-                              /* a workgroup per token slice; CCD_PATH_MFMA_UNIT matrix cores, a workgroup per   */
-                              /* unit.  All give the same scores up to fp32 rounding order.                      */
+                              /* CCD_PATH_VALU vector ALUs; CCD_PATH_MFMA_SLICES (bf16 caches only) matrix       */
+                              /* cores, a workgroup per token slice; CCD_PATH_MFMA_UNIT matrix cores, a          */
+                              /* workgroup per unit.  All give the same scores up to fp32 rounding order.        */
+                              /* fp32 caches on CCD_PATH_MFMA_UNIT: every fp32 value enters as the sum of two    */
+                              /* bf16 values and a product as three bf16 products (logits good to about 2^-16    */
+                              /* of sum |q k|); d = 64 only, no window, no K_cap (CCD_EUNSUPPORTED otherwise;    */
+                              /* CCD_PATH_AUTO then takes the vector ALUs).                                      */
   int64_t kv_stride_b, kv_stride_l, kv_stride_h;    /* K, V: [B, L, Hkv, n_cap, d], strides in elements */
   int64_t q_stride_b, q_stride_l, q_stride_h;       /* Q_cat: [B, L, Hq, P, d]                          */
   int64_t nov_stride_b, nov_stride_l, nov_stride_h; /* novelty fp32: [B, n] shared by layers and heads  */

@@ -39,7 +39,7 @@ struct ScorePlan {
   int unit_kernel;  // 1 (matrix-core path): both passes in one kernel, one workgroup per unit (launch_score_unit)
 };
 
-ScorePlan plan_score(const Dims& D);
+ScorePlan plan_score(const Dims& D, bool cap_keys);
 
 // pass 1: per (unit, slice, query) running maximum and sum of exp2 of the log2-domain logits
 void launch_stats_valu(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, float2* part, hipStream_t s);

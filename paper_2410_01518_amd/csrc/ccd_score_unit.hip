@@ -1,4 +1,5 @@
-// Representative score of Eq. 2 for bf16 caches, one workgroup per unit: both passes in one kernel.
+// Representative score of Eq. 2 on the matrix cores, one workgroup per unit: both passes in one kernel.  bf16 caches
+// (head dimension 64 or 128), and fp32 caches of head dimension 64 as sums of bf16 products (see "fp32 caches" below).
 //
 // The slice kernels of ccd_score_mfma.hip share every K tile among the four waves of a workgroup through LDS (each
 // wave owns 64 query rows), and the traffic that goes with it - DMA into the ring, eight fragment reads per wave and
@@ -26,6 +27,14 @@
 // instructions that consume the accumulators of the step before.  Compiled with the VGPR form of the matrix
 // instructions (results land in vector registers, where the ALU reads them; the query fragments are pinned to the
 // accumulation registers).
+//
+// fp32 caches: an fp32 value x is split into hi = bf16(x) and lo = bf16(x - hi) (x - hi is exact in fp32; what is left
+// is below 2^-17 |x|), and a product q k is taken as qh kh + ql kh + qh kl on the bf16 matrix instructions - three of
+// them per product, accumulated in fp32 in that order, the dropped ql kl term being 2^-18 of the product.  The logit
+// then carries a relative error of about 2^-16 of sum |q k| instead of fp32's 2^-24: two orders below what the
+// scores are asked to keep.  A row of d fp32 values becomes 2 d bf16 values [hi | lo], so d = 64 has the fragment
+// counts of a bf16 row of 128 and fits the same registers; K tiles are split in registers as they arrive (no copy of
+// the cache in memory), query rows once per sweep.
 #include <type_traits>
 
 #include "ccd_score_mfma.h"
@@ -46,6 +55,23 @@ struct UnitLds {
   float ubuf[4][kUBlock * kStep];   // per wave: the token sums of the block of tiles it is working on (pass 2)
 };
 
+// Shape of the work per head dimension HD and cache type (F32: fp32 values as [hi | lo] bf16 pairs)
+template <int HD, bool F32>
+struct UnitShape {
+  static constexpr int KQ = HD / 16;                    // 16-wide steps along the head dimension
+  static constexpr int KF = F32 ? 2 * KQ : KQ;          // fragments of a K tile, and of a 32-row block of query rows
+  static constexpr int NMQ = F32 ? 3 * KQ : KQ;         // matrix instructions per 32 x 32 block of logits
+  static constexpr int NM = kQB * NMQ;                  // ... per step (a pair of blocks)
+  static constexpr int NCH = NM < 16 ? NM : 16;         // chunks the ALU work of a step is cut into
+  static constexpr int EPC = 32 / NCH;                  // accumulator elements per chunk
+  static_assert(kUPairs * kQB * KF * 4 <= 256, "the query fragments of a sweep fill the accumulation registers");
+  // matrix instruction j (0 .. NMQ - 1) of a block: which K fragment meets which query fragment
+  static constexpr int kfrag(int j) { return !F32 ? j : (j < 2 * KQ ? j % KQ : KQ + j % KQ); }
+  static constexpr int qfrag(int j) { return !F32 ? j : (j < KQ ? j : (j < 2 * KQ ? j : j - 2 * KQ)); }
+  // chunks of ALU work done once matrix instruction i of a step is issued: none behind the first, all behind the last
+  static constexpr int chunks_by(int i) { return i < 0 ? 0 : (i == NM - 1 ? NCH : (i * NCH) / NM); }
+};
+
 // fragments of one 32-token tile, straight from global memory: lane (col, half) holds elements 16 ks + 8 half .. + 7
 // of token row t_tile + col (rows past t_last re-read row t_last: masked in pass 1, never stored in pass 2)
 template <int HD>
@@ -54,6 +80,52 @@ __device__ __forceinline__ void load_k_tile(bf16x8 (&a)[HD / 16], const uint16_t
   const uint16_t* p = Ku + (int64_t)min(t_tile + col, t_last) * HD + half * 8;
 #pragma unroll
   for (int ks = 0; ks < HD / 16; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(p + ks * 16);
+}
+
+// fp32 caches: the same elements as 8 floats per k-step (two 16-byte loads), split into hi and lo fragments later
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+template <int HD>
+struct RawTile {
+  f32x4 v[HD / 16][2];
+};
+template <int HD>
+__device__ __forceinline__ void load_k_raw(RawTile<HD>& r, const float* __restrict__ Ku, int t_tile, int t_last, int col,
+                                           int half) {
+  const float* p = Ku + (int64_t)min(t_tile + col, t_last) * HD + half * 8;
+#pragma unroll
+  for (int ks = 0; ks < HD / 16; ++ks) {
+    r.v[ks][0] = *reinterpret_cast<const f32x4*>(p + ks * 16);
+    r.v[ks][1] = *reinterpret_cast<const f32x4*>(p + ks * 16 + 4);
+  }
+}
+// x0, x1 -> (bf16(x0), bf16(x1)) packed, and the same of what the rounding left over: 3 ALU instructions per value
+__device__ __forceinline__ void split2(float x0, float x1, uint32_t& hi, uint32_t& lo) {
+  hi = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){x0, x1}, bf16x2));
+  const float h0 = __uint_as_float(hi << 16), h1 = __uint_as_float(hi & 0xFFFF0000u);
+  lo = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){x0 - h0, x1 - h1}, bf16x2));
+}
+__device__ __forceinline__ void split8(const f32x4 (&x)[2], bf16x8& hi, bf16x8& lo) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  uint32_t h[4], l[4];
+  split2(x[0].x, x[0].y, h[0], l[0]);
+  split2(x[0].z, x[0].w, h[1], l[1]);
+  split2(x[1].x, x[1].y, h[2], l[2]);
+  split2(x[1].z, x[1].w, h[3], l[3]);
+  hi = __builtin_bit_cast(bf16x8, (u32x4){h[0], h[1], h[2], h[3]});
+  lo = __builtin_bit_cast(bf16x8, (u32x4){l[0], l[1], l[2], l[3]});
+}
+// (A matrix instruction must not read a register that an ALU instruction wrote less than two issue slots before.  The
+// compiler keeps that distance for instructions it knows; the matrix instructions here are assembly text to it, and it
+// moves the conversions freely between them.  Every fragment therefore passes through two idle slots of its own,
+// after its last conversion and before any matrix instruction that reads it.)
+template <int HD>
+__device__ __forceinline__ void split_k_tile(bf16x8 (&a)[HD / 8], const RawTile<HD>& r) {
+#pragma unroll
+  for (int ks = 0; ks < HD / 16; ++ks) split8(r.v[ks], a[ks], a[HD / 16 + ks]);
+#pragma unroll
+  for (int f = 0; f < HD / 8; ++f) asm volatile("s_nop 1" : "+v"(a[f]));
 }
 
 // The matrix instructions are written out, with the query fragments at fixed places in the accumulation registers:
@@ -81,8 +153,19 @@ __device__ __forceinline__ void load_q_frag_at(const uint16_t* row) {
 template <int F>
 __device__ __forceinline__ void zero_q_frag() {
   asm volatile("v_accvgpr_write_b32 a[%0], 0\n\tv_accvgpr_write_b32 a[%1], 0\n\t"
-               "v_accvgpr_write_b32 a[%2], 0\n\tv_accvgpr_write_b32 a[%3], 0"
+               "v_accvgpr_write_b32 a[%2], 0\n\tv_accvgpr_write_b32 a[%3], 0\n\ts_nop 3"
                :: "n"(4 * F), "n"(4 * F + 1), "n"(4 * F + 2), "n"(4 * F + 3)
+               : CCD_ALL_ACC_REGISTERS);
+}
+// fragment F from four words in vector registers (fp32 caches: the split query rows)
+template <int F>
+__device__ __forceinline__ void put_q_frag(const bf16x8& f) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 w = __builtin_bit_cast(u32x4, f);
+  // (four idle slots behind the writes: more than a matrix instruction needs before it may read these registers)
+  asm volatile("v_accvgpr_write_b32 a[%0], %4\n\tv_accvgpr_write_b32 a[%1], %5\n\t"
+               "v_accvgpr_write_b32 a[%2], %6\n\tv_accvgpr_write_b32 a[%3], %7\n\ts_nop 3"
+               :: "n"(4 * F), "n"(4 * F + 1), "n"(4 * F + 2), "n"(4 * F + 3), "v"(w.x), "v"(w.y), "v"(w.z), "v"(w.w)
                : CCD_ALL_ACC_REGISTERS);
 }
 __device__ __forceinline__ void q_frags_arrived() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -113,31 +196,28 @@ __device__ __forceinline__ void static_for(F&& f) {
 }
 
 // logits of one tile against block pair P, not overlapped with anything (first tile, ragged tile, careful redo)
-template <int HD, int PASS, int P>
-__device__ __forceinline__ void logits_now(floatx16 (&acc)[kQB], const bf16x8 (&ak)[HD / 16]) {
-  constexpr int KS = HD / 16;
-  static_for<0, 2 * KS>([&](auto I) {
-    constexpr int i = decltype(I)::value, ks = i / 2, qb = i % 2, F = (P * kQB + qb) * KS + ks;
-    if constexpr (ks == 0) mma_first<PASS, F>(acc[qb], ak[0]);
-    else                   mma_next<PASS, F>(acc[qb], ak[ks]);
+template <class SH, int PASS, int P>
+__device__ __forceinline__ void logits_now(floatx16 (&acc)[kQB], const bf16x8 (&ak)[SH::KF]) {
+  static_for<0, SH::NM>([&](auto I) {
+    constexpr int i = decltype(I)::value, j = i / 2, qb = i % 2, F = (P * kQB + qb) * SH::KF + SH::qfrag(j);
+    if constexpr (j == 0) mma_first<PASS, F>(acc[qb], ak[SH::kfrag(0)]);
+    else                  mma_next<PASS, F>(acc[qb], ak[SH::kfrag(j)]);
   });
   mma_results_ready(acc);
 }
 
-// One pipelined step: the 2 KS matrix instructions of (tile, block pair P) into `nxt`, and between them the ALU work
-// on the accumulators of the step before, cut into 2 KS chunks.  chunk(j) runs behind matrix instruction j + 1 (the
-// last two behind the last one): the results it reads - block 0 in the first half of the chunks, block 1 in the
-// second - were produced at least three matrix instructions earlier.
-template <int HD, int PASS, int P, class Chunk>
-__device__ __forceinline__ void pipelined_step(floatx16 (&nxt)[kQB], const bf16x8 (&ak)[HD / 16], Chunk&& chunk) {
-  constexpr int KS = HD / 16, NM = 2 * KS;
+// One pipelined step: the NM matrix instructions of (tile, block pair P) into `nxt`, and between them the ALU work
+// on the accumulators of the step before, cut into NCH chunks.  The first chunk runs behind the second matrix
+// instruction at the earliest, the rest spread evenly, the last behind the last one: the results a chunk reads - block 0
+// in the first half of the chunks, block 1 in the second - were produced at least three matrix instructions earlier.
+template <class SH, int PASS, int P, class Chunk>
+__device__ __forceinline__ void pipelined_step(floatx16 (&nxt)[kQB], const bf16x8 (&ak)[SH::KF], Chunk&& chunk) {
   __builtin_amdgcn_sched_barrier(0);
-  static_for<0, NM>([&](auto I) {
-    constexpr int i = decltype(I)::value, ks = i / 2, qb = i % 2, F = (P * kQB + qb) * KS + ks;
-    if constexpr (ks == 0) mma_first<PASS, F>(nxt[qb], ak[0]);
-    else                   mma_next<PASS, F>(nxt[qb], ak[ks]);
-    if constexpr (i >= 1) chunk(i - 1);
-    if constexpr (i == NM - 1) chunk(NM - 1);
+  static_for<0, SH::NM>([&](auto I) {
+    constexpr int i = decltype(I)::value, j = i / 2, qb = i % 2, F = (P * kQB + qb) * SH::KF + SH::qfrag(j);
+    if constexpr (j == 0) mma_first<PASS, F>(nxt[qb], ak[SH::kfrag(0)]);
+    else                  mma_next<PASS, F>(nxt[qb], ak[SH::kfrag(j)]);
+    static_for<SH::chunks_by(i - 1), SH::chunks_by(i)>([&](auto C) { chunk(decltype(C)::value); });
     __builtin_amdgcn_sched_barrier(0);
   });
 }
@@ -164,19 +244,22 @@ __device__ __forceinline__ void load_neg_lse(float (&nl)[16], uint32_t lane_base
   }
 }
 
-template <int HD>
-__global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl, const uint16_t* __restrict__ Q,
-                                                            const uint16_t* __restrict__ K,
+// ET: element type of the caches in memory (uint16_t: bf16 bits; float: fp32, split on the fly)
+template <int HD, class ET>
+__global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl, const ET* __restrict__ Q,
+                                                            const ET* __restrict__ K,
                                                             const float2* __restrict__ part, float* __restrict__ u,
-                                                            const uint16_t* __restrict__ Kcap,
+                                                            const ET* __restrict__ Kcap,
                                                             float* __restrict__ lse_io) {
-  constexpr int KS = HD / 16;
-  constexpr int NM = 2 * KS;           // matrix instructions and ALU chunks per step
-  constexpr int EPC = 32 / NM;         // accumulator elements per chunk
+  constexpr bool F32 = std::is_same<ET, float>::value;
+  using SH = UnitShape<HD, F32>;
+  constexpr int KF = SH::KF;           // fragments of a K tile / of a block of query rows
+  constexpr int NCH = SH::NCH;         // ALU chunks per step
+  constexpr int EPC = SH::EPC;         // accumulator elements per chunk
   __shared__ UnitLds<HD> sm;
   const int unit = D.unit0 + blockIdx.x;
   const UnitIdx ui = decode_unit(D, unit);
-  const uint16_t* Ku = K + kv_offset(D, ui);
+  const ET* Ku = K + kv_offset(D, ui);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63, col = lane & 31, half = lane >> 5;
   const float c = D.scale_log2;
@@ -199,21 +282,49 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
     // Fragments of the sweep's query rows into the accumulation registers: all 8 KS loads of a lane are in flight at
     // once, together with the first K tiles requested further down.  Rows past G * P (last sweep only) stay zero.
     if (qc + kUQ > D.GP) {
-      static_for<0, kUPairs * kQB * KS>([&](auto Fc) { zero_q_frag<decltype(Fc)::value>(); });
+      static_for<0, kUPairs * kQB * KF>([&](auto Fc) { zero_q_frag<decltype(Fc)::value>(); });
     }
     static_for<0, kUPairs * kQB>([&](auto Bc) {
       constexpr int blk = decltype(Bc)::value;
       const int q = qc + blk * 32 + col;
       if (q < D.GP) {
-        const uint16_t* row = Q + q_offset(D, ui, q) + half * 8;
-        static_for<0, KS>([&](auto Kc) {
+        const ET* row = Q + q_offset(D, ui, q) + half * 8;
+        static_for<0, SH::KQ>([&](auto Kc) {
           constexpr int ks = decltype(Kc)::value;
-          load_q_frag_at<blk * KS + ks, ks * 32>(row);
+          if constexpr (F32) {
+            const f32x4 x[2] = {*reinterpret_cast<const f32x4*>(row + ks * 16),
+                                *reinterpret_cast<const f32x4*>(row + ks * 16 + 4)};
+            bf16x8 hi, lo;
+            split8(x, hi, lo);
+            put_q_frag<blk * KF + ks>(hi);
+            put_q_frag<blk * KF + SH::KQ + ks>(lo);
+          } else {
+            load_q_frag_at<blk * KF + ks, ks * 32>(row);
+          }
         });
       }
     });
-    bf16x8 a[2][KS];
+    bf16x8 a[2][KF];
     floatx16 accA[kQB], accB[kQB];
+    // fp32 caches: the tile requested last waits here, as it came from memory, until its turn to be split
+    RawTile<F32 ? HD : 16> raw;
+    // a[BUF] <- tile T of the wave, two tiles ahead of its use.  bf16: requested here.  fp32: tile T was requested one
+    // tile earlier and is split into a[BUF] now; the request that goes out here is for tile T2, the one after it.
+#define CCD_NEXT_TILE(BUF, T, T2)                                                        \
+    if constexpr (F32) {                                                                 \
+      split_k_tile<HD>(a[BUF], raw);                                                     \
+      load_k_raw<HD>(raw, Ku, tb + (T2) * kStep, t_last, col, half);                     \
+    } else {                                                                             \
+      load_k_tile<HD>(a[BUF], Ku, tb + (T) * kStep, t_last, col, half);                  \
+    }
+    // a[BUF] <- tile T, needed at once (prologues, ragged tile, careful redo)
+#define CCD_TILE_NOW(BUF, T)                                                             \
+    if constexpr (F32) {                                                                 \
+      load_k_raw<HD>(raw, Ku, tb + (T) * kStep, t_last, col, half);                      \
+      split_k_tile<HD>(a[BUF], raw);                                                     \
+    } else {                                                                             \
+      load_k_tile<HD>(a[BUF], Ku, tb + (T) * kStep, t_last, col, half);                  \
+    }
 
     if (!pl.lse_given) {
       // ---------------- pass 1 ----------------
@@ -242,32 +353,42 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
         asm volatile("" : "+v"(Z[P][(j * EPC) / 16][0]), "+v"(Z[P][(j * EPC) / 16][1]));    \
       }
       if (s0 < s1) {
-        load_k_tile<HD>(a[0], Ku, tb + s0 * kStep, t_last, col, half);
-        load_k_tile<HD>(a[1], Ku, tb + min(s0 + 1, s1 - 1) * kStep, t_last, col, half);
+        if constexpr (F32) {
+          load_k_raw<HD>(raw, Ku, tb + s0 * kStep, t_last, col, half);
+          split_k_tile<HD>(a[0], raw);
+          load_k_raw<HD>(raw, Ku, tb + min(s0 + 1, s1 - 1) * kStep, t_last, col, half);
+        } else {
+          load_k_tile<HD>(a[0], Ku, tb + s0 * kStep, t_last, col, half);
+          load_k_tile<HD>(a[1], Ku, tb + min(s0 + 1, s1 - 1) * kStep, t_last, col, half);
+        }
         q_frags_arrived();
         // the wave's first tile fixes the references and is folded without overlap
         static_for<0, kUPairs>([&](auto Pc) {
           constexpr int p = decltype(Pc)::value;
-          logits_now<HD, 1, p>(accA, a[0]);
+          logits_now<SH, 1, p>(accA, a[0]);
 #pragma unroll
           for (int qb = 0; qb < kQB; ++qb) nm[p][qb] = -max16(accA[qb]) * c;
           auto fold = CCD_FOLD1(accA, p);
 #pragma unroll
-          for (int j = 0; j < NM; ++j) fold(j);
+          for (int j = 0; j < NCH; ++j) fold(j);
         });
-        load_k_tile<HD>(a[0], Ku, tb + min(s0 + 2, s1 - 1) * kStep, t_last, col, half);
+        if constexpr (F32) {      // a[1] <- tile s0 + 1 (waiting in raw), a[0] <- tile s0 + 2, tile s0 + 3 requested
+          split_k_tile<HD>(a[1], raw);
+          load_k_raw<HD>(raw, Ku, tb + min(s0 + 2, s1 - 1) * kStep, t_last, col, half);
+        }
+        CCD_NEXT_TILE(0, min(s0 + 2, s1 - 1), min(s0 + 3, s1 - 1))
         int s = s0 + 1;
-        logits_now<HD, 1, 0>(accA, a[1]);
+        logits_now<SH, 1, 0>(accA, a[1]);
         // Tile s: accA holds the logits of (s, pair 0).  Steps 1 - 3 take pairs 1 - 3 of tile s from buffer CB, the
         // last step pair 0 of tile s + 1 from buffer NB; every step folds the pair computed by the step before.  The
         // buffer of tile s is free after step 3 and takes tile s + 2.
 #define CCD_P1_TILE(CB, NB)                                                                       \
-        pipelined_step<HD, 1, 1>(accB, a[CB], CCD_FOLD1(accA, 0));                            \
-        pipelined_step<HD, 1, 2>(accA, a[CB], CCD_FOLD1(accB, 1));                            \
-        pipelined_step<HD, 1, 3>(accB, a[CB], CCD_FOLD1(accA, 2));                            \
+        pipelined_step<SH, 1, 1>(accB, a[CB], CCD_FOLD1(accA, 0));                            \
+        pipelined_step<SH, 1, 2>(accA, a[CB], CCD_FOLD1(accB, 1));                            \
+        pipelined_step<SH, 1, 3>(accB, a[CB], CCD_FOLD1(accA, 2));                            \
         /* (always: a load under a condition would make every wait for K fragments a wait for all loads) */ \
-        load_k_tile<HD>(a[CB], Ku, tb + min(s + 2, s1 - 1) * kStep, t_last, col, half);           \
-        pipelined_step<HD, 1, 0>(accA, a[NB], CCD_FOLD1(accB, 3));
+        CCD_NEXT_TILE(CB, min(s + 2, s1 - 1), min(s + 3, s1 - 1))                                 \
+        pipelined_step<SH, 1, 0>(accA, a[NB], CCD_FOLD1(accB, 3));
         // (No branch inside a tile and none between the two tiles of the loop body: with straight-line code the
         // compiler can tell how many loads are in flight at every wait.  Behind the wave's last tile the last step
         // computes the logits of that tile's first pair once more; nobody reads them.)
@@ -294,16 +415,19 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
             m_ref[p][qb] = -nm[p][qb] * inv_c;
             bad |= !(Zs[p][qb] < INFINITY);
           }
+#ifdef CCD_DEBUG_FORCE_REDO
+        bad = true;
+#endif
         if (__any(bad)) {
 #pragma unroll
           for (int p = 0; p < kUPairs; ++p)
 #pragma unroll
             for (int qb = 0; qb < kQB; ++qb) { m_ref[p][qb] = kNegHuge; Zs[p][qb] = 0.f; }
           for (int t = s0; t < s1; ++t) {
-            load_k_tile<HD>(a[0], Ku, tb + t * kStep, t_last, col, half);
+            CCD_TILE_NOW(0, t)
             static_for<0, kUPairs>([&](auto Pc) {
               constexpr int p = decltype(Pc)::value;
-              logits_now<HD, 1, p>(accA, a[0]);
+              logits_now<SH, 1, p>(accA, a[0]);
               fold_stats<false>(accA, m_ref[p], Zs[p], c, half, kStep);
             });
           }
@@ -327,11 +451,11 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
           for (int qb = 0; qb < kQB; ++qb) { m_ref[p][qb] = kNegHuge; Zs[p][qb] = 0.f; }
       }
       if (ragged && wave == 3) {
-        load_k_tile<HD>(a[0], Ku, tb + full * kStep, t_last, col, half);
+        CCD_TILE_NOW(0, full)
         q_frags_arrived();
         static_for<0, kUPairs>([&](auto Pc) {
           constexpr int p = decltype(Pc)::value;
-          logits_now<HD, 1, p>(accA, a[0]);
+          logits_now<SH, 1, p>(accA, a[0]);
           fold_stats<true>(accA, m_ref[p], Zs[p], c, half, n_main - full * kStep);
         });
       }
@@ -350,13 +474,15 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
     // ---------------- merge: one log2-sum-exp per query row (thread = row of the sweep) ----------------
     {
       float2 cap = make_float2(kNegHuge, 0.f);     // the block of the CaP keys (causal variant), else nothing
-      if (Kcap != nullptr) {
-        const uint16_t* Kc = Kcap + (int64_t)unit * D.P * HD;
-        // the thread's own query row is one of the 2 x 32 rows of block pair `wave`: their fragments once more, in
-        // vector registers this time (the registers of pass 1 are free here)
-        bf16x8 bw[kQB][KS];
-        load_q_frags<HD>(bw, D, ui, Q, qc + wave * (kQB * 32), col, half);
-        cap = cap_block_stats<HD>(D, Kc, bw, qc + wave * (kQB * 32), col, half, c);
+      if constexpr (!F32) {          // (fp32 caches with CaP keys take the vector-ALU kernels: the host sees to that)
+        if (Kcap != nullptr) {
+          const uint16_t* Kc = Kcap + (int64_t)unit * D.P * HD;
+          // the thread's own query row is one of the 2 x 32 rows of block pair `wave`: their fragments once more, in
+          // vector registers this time (the registers of pass 1 are free here)
+          bf16x8 bw[kQB][KF];
+          load_q_frags<HD>(bw, D, ui, Q, qc + wave * (kQB * 32), col, half);
+          cap = cap_block_stats<HD>(D, Kc, bw, qc + wave * (kQB * 32), col, half, c);
+        }
       }
       __syncthreads();
       const int q = qc + threadIdx.x;
@@ -408,26 +534,34 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
         _Pragma("unroll") for (int i = 0; i < EPC; ++i) t[i] = fast_exp2(t[i]);           \
         _Pragma("unroll") for (int i = 0; i < EPC; ++i) us[i & 1] += t[i];                \
         asm volatile("" : "+v"(us[0]), "+v"(us[1]));     /* as in pass 1 */               \
-        if (j == NM / 2 - 1) load_neg_lse(nl[0], nl_base, (NP) * kQB);                    \
-        if (j == NM - 1) load_neg_lse(nl[1], nl_base, (NP) * kQB + 1);                    \
+        if (j == NCH / 2 - 1) load_neg_lse(nl[0], nl_base, (NP) * kQB);                   \
+        if (j == NCH - 1) load_neg_lse(nl[1], nl_base, (NP) * kQB + 1);                   \
       }
       int s = sb - 1;
-      load_k_tile<HD>(a[0], Ku, tb + s * kStep, t_last, col, half);
-      load_k_tile<HD>(a[1], Ku, tb + max(s - 1, sa) * kStep, t_last, col, half);
+      if constexpr (F32) {        // a[0] <- tile s, a[1] <- tile s - 1, tile s - 2 requested
+        load_k_raw<HD>(raw, Ku, tb + s * kStep, t_last, col, half);
+        split_k_tile<HD>(a[0], raw);
+        load_k_raw<HD>(raw, Ku, tb + max(s - 1, sa) * kStep, t_last, col, half);
+        split_k_tile<HD>(a[1], raw);
+        load_k_raw<HD>(raw, Ku, tb + max(s - 2, sa) * kStep, t_last, col, half);
+      } else {
+        load_k_tile<HD>(a[0], Ku, tb + s * kStep, t_last, col, half);
+        load_k_tile<HD>(a[1], Ku, tb + max(s - 1, sa) * kStep, t_last, col, half);
+      }
       load_neg_lse(nl[0], nl_base, 0);
       load_neg_lse(nl[1], nl_base, 1);
       q_frags_arrived();
-      logits_now<HD, 2, 0>(accA, a[0]);
+      logits_now<SH, 2, 0>(accA, a[0]);
       // Tile s: accA holds the logits of (s, pair 0) and nl the normalisers of pair 0.  Same step structure as pass 1,
       // walking down; the token's sum is complete after the fourth step.
 #define CCD_P2_TILE(CB, NB)                                                                          \
       us[0] = 0.f; us[1] = 0.f;                                                                      \
       asm volatile("" : "+v"(nl_base));                                                              \
-      pipelined_step<HD, 2, 1>(accB, a[CB], CCD_FOLD2(accA, 1));                                     \
-      pipelined_step<HD, 2, 2>(accA, a[CB], CCD_FOLD2(accB, 2));                                     \
-      pipelined_step<HD, 2, 3>(accB, a[CB], CCD_FOLD2(accA, 3));                                     \
-      load_k_tile<HD>(a[CB], Ku, tb + max(s - 2, sa) * kStep, t_last, col, half);                    \
-      pipelined_step<HD, 2, 0>(accA, a[NB], CCD_FOLD2(accB, 0));                                     \
+      pipelined_step<SH, 2, 1>(accB, a[CB], CCD_FOLD2(accA, 1));                                     \
+      pipelined_step<SH, 2, 2>(accA, a[CB], CCD_FOLD2(accB, 2));                                     \
+      pipelined_step<SH, 2, 3>(accB, a[CB], CCD_FOLD2(accA, 3));                                     \
+      CCD_NEXT_TILE(CB, max(s - 2, sa), max(s - 3, sa))                                              \
+      pipelined_step<SH, 2, 0>(accA, a[NB], CCD_FOLD2(accB, 0));                                     \
       {                                                                                              \
         float v = us[0] + us[1];                                                                     \
         v += __shfl_xor(v, 32);                                                                      \
@@ -450,23 +584,30 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
       for (int i = lane; i < n_blk; i += 64) uu[t_blk + i] = (qc == 0) ? ub[i] : uu[t_blk + i] + ub[i];
     }
     __syncthreads();   // the LDS tables are rewritten by the next sweep
+#undef CCD_NEXT_TILE
+#undef CCD_TILE_NOW
   }
 }
 
 }  // namespace
 
 // One workgroup per unit pays when the units fill the chip round by round.
-bool score_unit_supported(const Dims& D) { return D.dtype == 1 && (D.d == 64 || D.d == 128); }
+// (fp32 caches: head dimension 64 only - the split rows of 128 would need twice the fragment registers - and neither
+// CaP keys in the softmax nor a sliding window, whose side kernels exist for bf16 only: the caller checks those)
+bool score_unit_supported(const Dims& D) { return D.dtype == 1 ? (D.d == 64 || D.d == 128) : D.d == 64; }
 
 void launch_score_unit(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const void* K_cap,
                        const float2* part, float* u, float* lse_io, hipStream_t s) {
   dim3 grid((unsigned)D.units_run), block(kMT);
-  if (D.d == 64)
-    launch((score_unit_kernel<64>), grid, block, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part, u,
-                       (const uint16_t*)K_cap, lse_io);
+  if (D.dtype == 0)
+    launch((score_unit_kernel<64, float>), grid, block, s, D, pl, (const float*)Q, (const float*)K, part, u,
+           (const float*)nullptr, lse_io);
+  else if (D.d == 64)
+    launch((score_unit_kernel<64, uint16_t>), grid, block, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part, u,
+           (const uint16_t*)K_cap, lse_io);
   else
-    launch((score_unit_kernel<128>), grid, block, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part, u,
-                       (const uint16_t*)K_cap, lse_io);
+    launch((score_unit_kernel<128, uint16_t>), grid, block, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part, u,
+           (const uint16_t*)K_cap, lse_io);
 }
 
 }  // namespace ccd

@@ -51,7 +51,9 @@ static int check_shape(const ccd_shape_t* s, int need) {
     if (s->pool_w < 1 || s->pool_w % 2 == 0) return CCD_EINVAL;
     if (s->window < 0 || (s->window > 0 && s->window < s->P)) return CCD_EINVAL;
     if (s->score_path < CCD_PATH_AUTO || s->score_path > CCD_PATH_MFMA_UNIT) return CCD_EINVAL;
-    if (s->dtype != CCD_BF16 && s->score_path >= CCD_PATH_MFMA_SLICES) return CCD_EUNSUPPORTED;
+    if (s->dtype != CCD_BF16 && s->score_path == CCD_PATH_MFMA_SLICES) return CCD_EUNSUPPORTED;
+    // fp32 caches on the matrix cores: head dimension 64, no sliding window (and no CaP keys: checked with the call)
+    if (s->dtype != CCD_BF16 && s->score_path == CCD_PATH_MFMA_UNIT && (s->d != 64 || s->window > 0)) return CCD_EUNSUPPORTED;
   }
   if (need & kNeedNov) {
     if (s->T < 0 || s->T > s->k) return CCD_EINVAL;
@@ -142,7 +144,8 @@ static ScorePlan plan_mfma(const Dims& D) {
   return pl;
 }
 
-ScorePlan plan_score(const Dims& D) {
+// cap_keys: the call puts the CaP tokens' own keys into the softmax
+ScorePlan plan_score(const Dims& D, bool cap_keys) {
   ScorePlan pl{};
   pl.use_mfma = (D.dtype == CCD_BF16 && D.score_path != CCD_PATH_VALU) ? 1 : 0;
   if (pl.use_mfma) {
@@ -156,7 +159,23 @@ ScorePlan plan_score(const Dims& D) {
   pl.cap_block = 0;
   pl.head_block = 0;
   pl.lse_given = 0;
+  // fp32 caches: the unit kernel (fp32 values as sums of bf16 products on the matrix cores) where it exists - head
+  // dimension 64, plain softmax over the cached tokens - when asked for, or by itself when the units fill the chip
+  // and a sweep of 256 query rows is not mostly padding (the vector-ALU kernels cost in proportion to G * P)
+  if (D.dtype == CCD_FP32 && score_unit_supported(D) && !cap_keys && D.window == 0) {
+    if (D.score_path == CCD_PATH_MFMA_UNIT) {
+      pl.unit_kernel = 1;
+    } else if (D.score_path == CCD_PATH_AUTO) {
+      const int cus = compute_units();
+      const int rounds = (D.units_run + cus - 1) / cus;
+      pl.unit_kernel = (D.GP >= 32 && 4 * D.units_run >= 3 * rounds * cus) ? 1 : 0;
+    }
+  }
   return pl;
+}
+// a path the caller named that this call cannot take
+static bool path_refused(const Dims& D, const ScorePlan& pl) {
+  return D.dtype == CCD_FP32 && D.score_path == CCD_PATH_MFMA_UNIT && !pl.unit_kernel;
 }
 
 struct Workspace {
@@ -323,7 +342,8 @@ static int score_impl(const ccd_shape_t* shape, const void* Q_cat, const void* K
   if (novelty == nullptr && shape->T > 0) return CCD_EINVAL;
   if (!aligned16(Q_cat) || !aligned16(K) || !aligned16(K_cap) || !aligned16(lse)) return CCD_EALIGN;
   const Dims D = make_dims(shape);
-  const ScorePlan pl = plan_score(D);
+  const ScorePlan pl = plan_score(D, K_cap != nullptr);
+  if (path_refused(D, pl)) return CCD_EUNSUPPORTED;
   if (pl.use_mfma && D.head - D.head0 > mfma_max_slice()) return CCD_EUNSUPPORTED;   // about 2000 CaP tokens and a window
   const Workspace w = layout_workspace(D);
   rc = check_workspace(w, workspace, workspace_bytes);
@@ -398,7 +418,8 @@ static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, v
   if (!aligned16(lse)) return CCD_EALIGN;
   const void* K_attn = K_score != nullptr ? K_score : K;     // the keys the CaP queries attend to
   const Dims D = make_dims(shape);
-  const ScorePlan pl = plan_score(D);
+  const ScorePlan pl = plan_score(D, K_cap != nullptr);
+  if (path_refused(D, pl)) return CCD_EUNSUPPORTED;
   if (pl.use_mfma && D.head - D.head0 > mfma_max_slice()) return CCD_EUNSUPPORTED;   // about 2000 CaP tokens and a window
   const Workspace w = layout_workspace(D);
   rc = check_workspace(w, workspace, workspace_bytes);
@@ -540,7 +561,8 @@ const char* ccd_strerror(int code) {
     case CCD_EINVAL: return "invalid argument (null pointer or shape field out of range)";
     case CCD_EUNSUPPORTED:
       return "unsupported: head dimension not 64 or 128, unknown dtype or pool mode, more than 65536 tokens, a matrix-core "
-             "score path for an fp32 cache, or (bf16, with a window) more than about 2000 CaP tokens";
+             "score path that an fp32 cache cannot take (token slices; units with a head dimension other than 64, a window "
+             "or CaP keys), or (bf16, with a window) more than about 2000 CaP tokens";
     case CCD_EALIGN: return "pointer or stride not 16-byte aligned";
     case CCD_EWORKSPACE:
       return "workspace null, misaligned or too small (ccd_compress_noalloc: the shape needs more than the built-in "

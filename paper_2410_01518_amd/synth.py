@@ -48,6 +48,8 @@ CONFIGS = {
     "c4": CCDConfig("c4", 1, 32, 32, 8, 128, 4096, 2048, 64, 1024, 7, "bf16", "normal", 4),
     # large pot, heavy compression, Zipf-skewed key norms, batch of 4
     "c5": CCDConfig("c5", 4, 80, 64, 8, 128, 32768, 4096, 128, 2048, 7, "bf16", "zipf", 5),
+    # not a benchmark configuration: the headline's layer / head / pot shape with an fp32 cache of head dimension 64
+    "c3f": CCDConfig("c3f", 1, 32, 32, 8, 64, 4096, 2048, 64, 1024, 7, "fp32", "normal", 6),
 }
 
 

@@ -183,14 +183,22 @@ def test_kcat_argument_errors_are_decided_on_the_host():
     assert score(scores=None) == ip.CCD_EINVAL and score(ws=None) == ip.CCD_EWORKSPACE
     assert compress(Kcap=P) == ip.CCD_EINVAL and compress(Kcap=P + 0x200000) == ip.CCD_EINVAL   # aliases K / V
     assert compress(shape=_shape(n_valid=300, n_cap=512, k=256)) == ip.CCD_NOOP
+    # an fp32 cache with CaP keys cannot take the matrix-core unit kernel: refused when named, not replaced silently
+    f32 = _shape(dtype=ip.CCD_FP32, d=64, score_path=ip.CCD_PATH_MFMA_UNIT)
+    assert L.ccd_compress_kcat(ctypes.byref(f32), P, P, P + 0x200000, P2, P, None, P, 0x10000, ip.ccd_workspace_bytes(f32),
+                               None) == ip.CCD_EUNSUPPORTED
 
 
 def test_window_errors_are_decided_on_the_host():
     assert _compress(_shape(window=-1)) == ip.CCD_EINVAL
     assert _compress(_shape(window=15)) == ip.CCD_EINVAL                      # shorter than the P = 16 CaP tokens
     assert _compress(_shape(score_path=4)) == ip.CCD_EINVAL and _compress(_shape(score_path=-1)) == ip.CCD_EINVAL
-    for path in (ip.CCD_PATH_MFMA_SLICES, ip.CCD_PATH_MFMA_UNIT):         # the matrix-core kernels are bf16 only
-        assert _compress(_shape(dtype=ip.CCD_FP32, score_path=path)) == ip.CCD_EUNSUPPORTED
+    # fp32 caches on the matrix cores: the unit kernel only, head dimension 64, no window (no CaP keys: next test)
+    for path in (ip.CCD_PATH_MFMA_SLICES, ip.CCD_PATH_MFMA_UNIT):
+        assert _compress(_shape(dtype=ip.CCD_FP32, score_path=path)) == ip.CCD_EUNSUPPORTED            # d = 128
+    assert _compress(_shape(dtype=ip.CCD_FP32, d=64, score_path=ip.CCD_PATH_MFMA_SLICES)) == ip.CCD_EUNSUPPORTED
+    assert _compress(_shape(dtype=ip.CCD_FP32, d=64, score_path=ip.CCD_PATH_MFMA_UNIT, window=400)) == ip.CCD_EUNSUPPORTED
+    assert _compress(_shape(dtype=ip.CCD_FP32, d=64, score_path=ip.CCD_PATH_MFMA_UNIT, n_valid=300)) == ip.CCD_NOOP
     assert "fp32" in ip.ccd_strerror(ip.CCD_EUNSUPPORTED) and "2000" in ip.ccd_strerror(ip.CCD_EUNSUPPORTED)
     big = _shape(n_valid=8192, n_cap=8192, k=4096, T=0, P=2100, window=4096)
     assert _compress(big) == ip.CCD_EUNSUPPORTED          # more CaP tokens than the windowed matrix-core kernels take

@@ -104,6 +104,8 @@ SCORE_CASES = [
     dict(keys="outlier1pct", Hq=8, Hkv=2, N=2048, k=1024, P=32, T=512),           # config-2 shape, fewer heads
     dict(B=2, L=1, Hq=16, Hkv=2, N=1111, k=10, P=40, T=3, w=5),                   # G*P = 320 > one workgroup of queries
     dict(keys="zipf", B=2, L=1, N=900, k=128, P=16, T=64),
+    dict(dtype="fp32", d=64, B=2, L=1, Hq=16, Hkv=2, N=1111, k=10, P=40, T=3, w=5),   # fp32, two query sweeps, ragged
+    dict(dtype="fp32", d=64, keys="zipf", N=2600, k=900, T=100),                   # fp32, many tiles per wave
 ]
 
 
@@ -112,11 +114,13 @@ SCORE_PATHS = [ip.CCD_PATH_VALU, ip.CCD_PATH_MFMA_SLICES, ip.CCD_PATH_MFMA_UNIT]
 
 
 def _path_for(cfg, score_path):
-    """fp32 caches have the vector-ALU path only: they run once, under the automatic choice."""
+    """fp32 caches: the vector ALUs (under the automatic choice), and the matrix-core unit kernel for head dimension 64."""
     if cfg.dtype == "fp32":
-        if score_path != ip.CCD_PATH_VALU:
-            pytest.skip("fp32 caches have one path")
-        return ip.CCD_PATH_AUTO
+        if score_path == ip.CCD_PATH_VALU:
+            return ip.CCD_PATH_AUTO
+        if score_path == ip.CCD_PATH_MFMA_UNIT and cfg.d == 64:
+            return score_path
+        pytest.skip("fp32 caches: no such path")
     return score_path
 
 
@@ -238,6 +242,36 @@ def test_fused_compress_small(per_head, want_scores, score_path):
     rc, dev, scores, keep = _run_fused(cfg, inp, per_head=per_head, want_scores=want_scores, score_path=score_path)
     assert rc == ip.CCD_OK
     _check_fused(cfg, inp, ref, dev, scores, keep, per_head)
+
+
+@pytest.mark.parametrize("per_head", [False, True])
+def test_fused_compress_fp32_cache_on_the_matrix_cores(per_head):
+    """An fp32 cache of head dimension 64 on the unit kernel (every value as hi + lo bf16, three products each)."""
+    cfg = _cfg(dtype="fp32", d=64, B=2, L=2, Hq=8, Hkv=2, P=20, N=1300, k=500, T=120, seed=37)
+    print(f"fused fp32 on the matrix cores per_head={per_head} {cfg}", flush=True)
+    inp = synth.make_inputs(cfg, per_head_novelty=per_head)
+    ref = _oracle(cfg, inp)
+    rc, dev, scores, keep = _run_fused(cfg, inp, per_head=per_head, score_path=ip.CCD_PATH_MFMA_UNIT)
+    assert rc == ip.CCD_OK
+    _check_fused(cfg, inp, ref, dev, scores, keep, per_head)
+
+
+def test_fp32_cache_that_fills_the_chip_takes_the_matrix_cores_by_itself():
+    """192 units of an fp32 cache (d = 64, 32 query rows per unit): the automatic choice is the unit kernel (seen in
+    the per-kernel timing), and the result is the oracle's."""
+    cfg = _cfg(dtype="fp32", d=64, B=1, L=24, Hq=32, Hkv=8, P=8, N=420, k=200, T=50, w=5, seed=41)
+    print(f"fp32 automatic path {cfg}", flush=True)
+    inp = synth.make_inputs(cfg)
+    ref = _oracle(cfg, inp)
+    ip.ccd_profile_enable(True)
+    try:
+        rc, dev, scores, keep = _run_fused(cfg, inp)
+        stage_ms, calls = ip.ccd_profile_collect()
+    finally:
+        ip.ccd_profile_enable(False)
+    assert rc == ip.CCD_OK and calls == 1
+    assert stage_ms["score_unit"] > 0 and stage_ms["score_stats"] == 0 and stage_ms["score_prob"] == 0
+    _check_fused(cfg, inp, ref, dev, scores, keep, False)
 
 
 @pytest.mark.parametrize("per_head", [False, True])
@@ -394,6 +428,37 @@ def test_logits_far_above_those_of_the_first_tile(where):
     assert ip.ccd_score(shape, dev["Q_cat"], dev["K"], dev["novelty"], scores, ws) == ip.CCD_OK
     torch.cuda.synchronize()
     gu.assert_scores_close(gu.to_host(scores), ref["scores"], cfg.G * cfg.P)
+
+
+@pytest.mark.parametrize("where", ["late_tokens", "tail_tile"])
+def test_logits_far_above_those_of_the_first_tile_fp32_on_the_matrix_cores(where):
+    """The same redo of a wave's tokens on the fp32 form of the unit kernel.  Logits that overflow a sum are more than 127
+    binary orders above the reference, and at that size the hi/lo split of the fp32 values (logits good to about 2^-16
+    of sum |q k|) no longer resolves a probability to 1e-3: the bound here is 5e-2, the point is the redo itself."""
+    cfg = _cfg(dtype="fp32", d=64, B=1, L=1, Hq=16, Hkv=2, P=40, N=1000, k=300, T=50, w=3, seed=73)
+    print(f"far logits fp32 {where} {cfg}", flush=True)
+    inp = synth.make_inputs(cfg)
+    K, Q = inp["K"].copy(), inp["Q_cat"].copy()
+    K[..., :64, :] *= 0.01
+    if where == "late_tokens":
+        K[..., 300:, :] *= 40.0
+    else:
+        K[..., 992:, :] *= 60.0
+    Q *= 4.0
+    inp["K"], inp["Q_cat"] = K, Q
+    ref = _oracle(cfg, inp)
+    dev = _upload(inp)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w,
+                          score_path=ip.CCD_PATH_MFMA_UNIT)
+    ws = ip.alloc_workspace(shape)
+    scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
+    assert ip.ccd_score(shape, dev["Q_cat"], dev["K"], dev["novelty"], scores, ws) == ip.CCD_OK
+    torch.cuda.synchronize()
+    got, want = gu.to_host(scores), ref["scores"]
+    fin = np.isfinite(want)
+    assert np.array_equal(np.isposinf(got), np.isposinf(want)) and not np.isnan(got).any()
+    np.testing.assert_allclose(got[fin], want[fin], rtol=5e-2, atol=2 * cfg.G * cfg.P * np.finfo(np.float32).tiny)
+    assert (want[fin] > 0).sum() > 100          # not a row of zeros
 
 
 @pytest.mark.parametrize("score_path", SCORE_PATHS)
