@@ -46,8 +46,8 @@ enum {
   CCD_NOOP = 1,          /* pot not full (n_valid < n_cap) or nothing to drop (n_valid <= k): untouched */
   CCD_EINVAL = -1,       /* NULL pointer, or a shape field out of range                                 */
   CCD_EUNSUPPORTED = -2, /* d not in {64, 128}, unknown dtype or pool_mode, n_valid > 65536, a matrix-  */
-                         /* core score_path that an fp32 cache cannot take (see score_path), a window  */
-                         /* with P > 1986 on a bf16 cache                                               */
+                         /* core score_path that an fp32 cache cannot take (see score_path), or one     */
+                         /* named for a window with P > 1986                                            */
   CCD_EALIGN = -3,       /* pointer or stride not 16-byte aligned                                       */
   CCD_EWORKSPACE = -4,   /* workspace NULL, misaligned or smaller than ccd_workspace_bytes()            */
   CCD_ELAUNCH = -5       /* the HIP runtime refused a kernel launch                                    */
@@ -71,8 +71,9 @@ typedef struct {
   int32_t window;             /* sliding attention window in tokens, 0 = none (Sec. 4, footnote on SWA   */
                               /* models): the cached tokens stand at positions 0 .. n_valid-1 and CaP    */
                               /* token i at n_valid + i; a query at position p sees the keys at          */
-                              /* p-window+1 .. p only.  window >= P when set; bf16 caches with a window:  */
-                              /* P <= 1986 (CCD_EUNSUPPORTED beyond).                                     */
+                              /* p-window+1 .. p only.  window >= P when set.  (The matrix-core score     */
+                              /* paths take P <= 1986 under a window; beyond that CCD_PATH_AUTO scores on */
+                              /* the vector ALUs and a matrix-core path that was named is refused.)       */
   int32_t score_path;         /* kernels for Eq. 2: CCD_PATH_AUTO (0) unless two paths are to be compared:       */
                               /* CCD_PATH_VALU vector ALUs; CCD_PATH_MFMA_SLICES (bf16 caches only) matrix       */
                               /* cores, a workgroup per token slice; CCD_PATH_MFMA_UNIT matrix cores, a          */

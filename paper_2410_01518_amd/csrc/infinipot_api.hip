@@ -148,6 +148,9 @@ static ScorePlan plan_mfma(const Dims& D) {
 ScorePlan plan_score(const Dims& D, bool cap_keys) {
   ScorePlan pl{};
   pl.use_mfma = (D.dtype == CCD_BF16 && D.score_path != CCD_PATH_VALU) ? 1 : 0;
+  // a windowed head longer than the head kernels of the matrix-core paths take (about 2000 CaP tokens under a window):
+  // the vector-ALU kernels mask inside their loops and take any, so the automatic choice goes there
+  if (pl.use_mfma && D.score_path == CCD_PATH_AUTO && D.head - D.head0 > mfma_max_slice()) pl.use_mfma = 0;
   if (pl.use_mfma) {
     return plan_mfma(D);
   } else {
@@ -344,7 +347,7 @@ static int score_impl(const ccd_shape_t* shape, const void* Q_cat, const void* K
   const Dims D = make_dims(shape);
   const ScorePlan pl = plan_score(D, K_cap != nullptr);
   if (path_refused(D, pl)) return CCD_EUNSUPPORTED;
-  if (pl.use_mfma && D.head - D.head0 > mfma_max_slice()) return CCD_EUNSUPPORTED;   // about 2000 CaP tokens and a window
+  if (pl.use_mfma && D.head - D.head0 > mfma_max_slice()) return CCD_EUNSUPPORTED;   // (a matrix-core path was named)
   const Workspace w = layout_workspace(D);
   rc = check_workspace(w, workspace, workspace_bytes);
   if (rc != CCD_OK) return rc;
@@ -420,7 +423,7 @@ static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, v
   const Dims D = make_dims(shape);
   const ScorePlan pl = plan_score(D, K_cap != nullptr);
   if (path_refused(D, pl)) return CCD_EUNSUPPORTED;
-  if (pl.use_mfma && D.head - D.head0 > mfma_max_slice()) return CCD_EUNSUPPORTED;   // about 2000 CaP tokens and a window
+  if (pl.use_mfma && D.head - D.head0 > mfma_max_slice()) return CCD_EUNSUPPORTED;   // (a matrix-core path was named)
   const Workspace w = layout_workspace(D);
   rc = check_workspace(w, workspace, workspace_bytes);
   if (rc != CCD_OK) return rc;
@@ -562,7 +565,7 @@ const char* ccd_strerror(int code) {
     case CCD_EUNSUPPORTED:
       return "unsupported: head dimension not 64 or 128, unknown dtype or pool mode, more than 65536 tokens, a matrix-core "
              "score path that an fp32 cache cannot take (token slices; units with a head dimension other than 64, a window "
-             "or CaP keys), or (bf16, with a window) more than about 2000 CaP tokens";
+             "or CaP keys), or a matrix-core score path named for a window with more than about 2000 CaP tokens";
     case CCD_EALIGN: return "pointer or stride not 16-byte aligned";
     case CCD_EWORKSPACE:
       return "workspace null, misaligned or too small (ccd_compress_noalloc: the shape needs more than the built-in "

@@ -200,8 +200,11 @@ def test_window_errors_are_decided_on_the_host():
     assert _compress(_shape(dtype=ip.CCD_FP32, d=64, score_path=ip.CCD_PATH_MFMA_UNIT, window=400)) == ip.CCD_EUNSUPPORTED
     assert _compress(_shape(dtype=ip.CCD_FP32, d=64, score_path=ip.CCD_PATH_MFMA_UNIT, n_valid=300)) == ip.CCD_NOOP
     assert "fp32" in ip.ccd_strerror(ip.CCD_EUNSUPPORTED) and "2000" in ip.ccd_strerror(ip.CCD_EUNSUPPORTED)
-    big = _shape(n_valid=8192, n_cap=8192, k=4096, T=0, P=2100, window=4096)
-    assert _compress(big) == ip.CCD_EUNSUPPORTED          # more CaP tokens than the windowed matrix-core kernels take
+    # more CaP tokens than the windowed matrix-core kernels take: refused when such a path is named (the automatic
+    # choice scores on the vector ALUs then: tests/test_gpu_swa.py)
+    for path in (ip.CCD_PATH_MFMA_SLICES, ip.CCD_PATH_MFMA_UNIT):
+        big = _shape(n_valid=8192, n_cap=8192, k=4096, T=0, P=2100, window=4096, score_path=path)
+        assert _compress(big) == ip.CCD_EUNSUPPORTED
     assert ip.ccd_workspace_bytes(_shape(window=512)) == ip.ccd_workspace_bytes(_shape())
     assert _compress(_shape(n_valid=300, n_cap=512, k=256, window=300)) == ip.CCD_NOOP
 

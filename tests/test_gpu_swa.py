@@ -137,3 +137,22 @@ def test_window_limits_are_decided_on_the_host():
         rc = ip.lib().ccd_score(__import__("ctypes").byref(shape), dev["Q_cat"].data_ptr(), dev["K"].data_ptr(),
                                 dev["novelty"].data_ptr(), scores.data_ptr(), ws.data_ptr(), ws.numel(), None)
         assert rc == code, (window, rc)
+
+
+def test_more_cap_tokens_under_a_window_than_the_matrix_core_kernels_take():
+    """2100 CaP tokens under a window: the hidden head is longer than the matrix-core head kernels take, so the automatic
+    choice scores on the vector ALUs (which mask inside their loops); naming a matrix-core path is refused."""
+    cfg = _cfg(L=1, Hq=1, Hkv=1, d=64, N=2600, k=900, T=100, P=2100)
+    window = 2300
+    print(f"swa with {cfg.P} CaP tokens {cfg} window={window}", flush=True)
+    got, ref = _score(cfg, window)
+    gu.assert_scores_close(got, ref["scores"], cfg.G * cfg.P)
+    inp = synth.make_inputs(cfg)
+    dev = {k: gu.to_dev(v) for k, v in inp.items()}
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, window=window,
+                          score_path=ip.CCD_PATH_MFMA_UNIT)
+    ws = ip.alloc_workspace(shape)
+    scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
+    rc = ip.lib().ccd_score(__import__("ctypes").byref(shape), dev["Q_cat"].data_ptr(), dev["K"].data_ptr(),
+                            dev["novelty"].data_ptr(), scores.data_ptr(), ws.data_ptr(), ws.numel(), None)
+    assert rc == ip.CCD_EUNSUPPORTED
