@@ -149,6 +149,31 @@ def test_scores_and_staged_calls(case, pool_mode, score_path):
     np.testing.assert_array_equal(kh, gu.replay_select(sh, cfg.k))                # (C) replay on the GPU's scores
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("score_path", SCORE_PATHS)
+@pytest.mark.parametrize("N", [1, 2, 31, 32, 33, 97, 128, 129])
+def test_rows_of_a_few_tokens(N, score_path, dtype):
+    """Rows shorter than, equal to and just beyond one 32-token tile and one tile per wave: waves without tokens, a
+    ragged tile only, one full tile and a ragged one."""
+    cfg = _cfg(dtype=dtype, d=64, L=1, N=N, k=max(1, N // 2), T=N // 4, P=5, w=3, seed=91 + N)
+    score_path = _path_for(cfg, score_path)
+    print(f"short rows {cfg} path={score_path}", flush=True)
+    inp = synth.make_inputs(cfg)
+    ref = _oracle(cfg, inp)
+    rc, dev, scores, keep = _run_fused(cfg, inp, score_path=score_path) if N > cfg.k else (None, None, None, None)
+    if rc is None:                                   # k = n (N = 1): nothing to drop, the fused call is a no-op; score only
+        dev = _upload(inp)
+        shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, score_path=score_path)
+        ws = ip.alloc_workspace(shape)
+        scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
+        assert ip.ccd_score(shape, dev["Q_cat"], dev["K"], dev["novelty"], scores, ws) == ip.CCD_OK
+        torch.cuda.synchronize()
+        gu.assert_scores_close(gu.to_host(scores), ref["scores"], cfg.G * cfg.P)
+        return
+    assert rc == ip.CCD_OK
+    _check_fused(cfg, inp, ref, dev, scores, keep, False)
+
+
 @pytest.mark.parametrize("per_head", [False, True])
 @pytest.mark.parametrize("score_path", SCORE_PATHS)
 @pytest.mark.parametrize("T", [1, 37, 200, 699])
