@@ -51,6 +51,54 @@ def check_acc_registers_untouched(asm_path: str) -> None:
         raise RuntimeError(f"{asm_path}: the compiler uses accumulation registers that the kernel reserves:\n" + "\n".join(bad[:10]))
 
 
+_VGPR_RANGE = re.compile(r"v\[(\d+):(\d+)\]")
+_VGPR_ONE = re.compile(r"v(\d+)")
+
+
+def _vgprs(token: str) -> set:
+    token = token.strip()
+    m = _VGPR_RANGE.fullmatch(token)
+    if m:
+        return set(range(int(m.group(1)), int(m.group(2)) + 1))
+    m = _VGPR_ONE.fullmatch(token)
+    return {int(m.group(1))} if m else set()
+
+
+def check_matrix_operand_distance(asm_path: str) -> None:
+    """A matrix instruction must not read, as its first or second operand, a vector register that an ALU instruction
+    wrote in the two issue slots before it.  The compiler keeps that distance for matrix instructions it generates; the
+    ones in ccd_score_unit.hip are inline assembly, which it schedules around without knowing what they are.  Checked on
+    straight-line code (history is dropped at every label)."""
+    bad, hist = [], []
+    with open(asm_path) as f:
+        for n, line in enumerate(f, 1):
+            text = line.split(";")[0].strip()
+            if not text or text.startswith("."):
+                continue
+            if text.endswith(":"):
+                hist = []
+                continue
+            parts = text.split(None, 1)
+            op = parts[0]
+            args = [a.strip() for a in parts[1].split(",")] if len(parts) > 1 else []
+            if op.startswith("v_mfma"):
+                src = set()
+                for a in args[1:3]:
+                    src |= _vgprs(a)
+                for ln, tx, wr in hist[-2:]:
+                    if wr & src:
+                        bad.append(f"{n}: {text}   <- {ln}: {tx}")
+                hist.append((n, text, set()))
+            elif op == "s_nop":
+                hist.extend([(n, text, set())] * (int(args[0], 0) + 1))
+            else:
+                wr = _vgprs(args[0]) if (op.startswith("v_") and not op.startswith("v_cmp") and args) else set()
+                hist.append((n, text, wr))
+            hist = hist[-4:]
+    if bad:
+        raise RuntimeError(f"{asm_path}: an ALU write directly before the matrix instruction that reads it:\n" + "\n".join(bad[:10]))
+
+
 def build_library(verbose: bool = True, extra_flags=()) -> str:
     """Compiles every kernel source and links the shared library; returns its path."""
     hipcc = _hipcc()
@@ -67,6 +115,7 @@ def build_library(verbose: bool = True, extra_flags=()) -> str:
             if r.returncode != 0:
                 raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")
             check_acc_registers_untouched(asm)
+            check_matrix_operand_distance(asm)
         cmd = [hipcc, *flags, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
