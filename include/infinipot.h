@@ -99,6 +99,17 @@ CCD_API size_t ccd_workspace_bytes(const ccd_shape_t* shape);
 CCD_API int ccd_score(const ccd_shape_t* shape, const void* Q_cat, const void* K, const float* novelty,
               float* scores, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Filling the pot (Sec. 3.2: new context is cached until the pot is full): rows n_valid .. n_valid + count - 1 of
+ * every unit of K and V (layout and strides of the shape) take the rows of a chunk of new context, K_new and V_new
+ * [B, L, Hkv, count, d], dense, cache dtype; requires n_valid + count <= n_cap (CCD_EINVAL otherwise; n_valid may
+ * be 0, count may be 0).  novelty / novelty_new (both or neither): entries n_valid .. n_valid + count - 1 of
+ * novelty (strides of the shape: shared [B, n], or carried per head [B, L, Hkv, n_cap], then every head gets them)
+ * take novelty_new [B, count] fp32.  The caller raises n_valid by count afterwards.  Only B, L, Hkv, d, dtype,
+ * n_valid, n_cap and the K/V and novelty strides of the shape are read.  (A model that writes its new keys and
+ * values straight into the pot's free rows needs no such copy.) */
+CCD_API int ccd_append(const ccd_shape_t* shape, void* K, void* V, float* novelty, const void* K_new, const void* V_new,
+                       const float* novelty_new, int32_t count, void* hip_stream);
+
 /* The select step (Sec. 3.3.3 step 2): keep_idx[B, L, Hkv, k] int32 = the k indices of largest score per unit,
  * ascending.  Equal scores: lower index first; NaN ranks with -inf; -0 equals +0.  Only B, L, Hkv,
  * n_valid and k of the shape are read. */

@@ -40,6 +40,9 @@ Steps, per unit (sequence b, layer l, KV head h), in the paper's order:
                 top-k per head; ties go to the lower index; the kept indices
                 are emitted in ascending (temporal) order.
   compact       App. B: K' = K[keep], V' = V[keep] (bit copies).
+  append        Sec. 3.2: between two distillations the pot is filled - the keys, values and novelty of the next
+                chunk of context go behind the cached tokens (bit copies; the novelty of a token is the same
+                for every head).
   nuc_from_logits  Sec. 3.3.2, Eq. 3 / App. B "Calculate NuC Score": the novelty of a token is its cross
                 entropy under the model, n_t = -log P(x_t | context), read off the logits row that
                 predicts x_t.  (Which context the model saw - the compressed one of Eq. 4 - is the
@@ -204,6 +207,22 @@ def select(scores: np.ndarray, k: int) -> np.ndarray:
 def compact(X: np.ndarray, keep: np.ndarray) -> np.ndarray:
     """Rows of X at the kept indices, in that order (a copy of the stored bits)."""
     return X[np.asarray(keep, dtype=np.int64)].copy()
+
+
+def append(pot: np.ndarray, n_valid: int, chunk: np.ndarray) -> np.ndarray:
+    """Sec. 3.2, filling the pot: a copy of `pot` [..., n_cap(, d)] whose token rows n_valid .. n_valid + m - 1 hold the
+    m rows of `chunk` [..., m(, d)] (leading dimensions of the chunk broadcast over the pot's: one novelty value per
+    token goes to every head); the other rows are untouched.  The token axis is axis 3 for K and V [B, L, Hkv, n, d]
+    and the last axis for novelty."""
+    out = pot.copy()
+    m = chunk.shape[3] if pot.ndim == 5 else chunk.shape[-1]
+    if n_valid < 0 or n_valid + m > (pot.shape[3] if pot.ndim == 5 else pot.shape[-1]):
+        raise ValueError("the chunk does not fit behind the cached tokens")
+    if pot.ndim == 5:
+        out[:, :, :, n_valid:n_valid + m, :] = chunk
+    else:
+        out[..., n_valid:n_valid + m] = chunk
+    return out
 
 
 def nuc_from_logits(logits: np.ndarray, labels: np.ndarray) -> np.ndarray:

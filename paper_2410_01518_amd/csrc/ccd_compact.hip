@@ -32,6 +32,48 @@ __device__ __forceinline__ uint4 load_streaming(const char* p) {
 constexpr int kCpThreads = 1024;
 constexpr int kCpUnroll = 4;
 
+// Appending a chunk of new context behind the cached tokens (Sec. 3.2: the pot is filled until it is full): rows
+// [n, n + count) of every unit of K and V take the chunk's rows, dense [units, count, d] on the source side.  A unit's
+// share is one contiguous run on both sides; the grid is (unit, tensor, segment of 64 KiB), 16 bytes per lane and
+// four of them in flight.  Carried novelty follows: entry n + j of every head takes the chunk's novelty of token j.
+constexpr int kApThreads = 256;
+constexpr int kApSegBytes = kApThreads * 16 * 16;     // bytes one workgroup moves: 64 KiB
+__global__ __launch_bounds__(kApThreads) void append_rows_kernel(Dims D, int esz, int count, int segs, char* K, char* V,
+                                                                 const char* Knew, const char* Vnew, float* novelty,
+                                                                 const float* nov_new, int nov_per_head) {
+  const int seg = blockIdx.x % segs;
+  const int ut = blockIdx.x / segs;
+  const int unit = ut >> 1;
+  const bool isV = ut & 1;
+  const UnitIdx ui = decode_unit(D, unit);
+  const int64_t run = (int64_t)count * D.d * esz;                         // bytes of a unit's share
+  char* dst = (isV ? V : K) + (kv_offset(D, ui) + (int64_t)D.n * D.d) * esz;
+  const char* src = (isV ? Vnew : Knew) + (int64_t)unit * run;
+  const int64_t b0 = (int64_t)seg * kApSegBytes + threadIdx.x * 16;
+#pragma unroll
+  for (int r = 0; r < 16; r += 4) {
+    uint4 v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t b = b0 + (int64_t)(r + i) * (kApThreads * 16);
+      if (b < run) v[i] = load_streaming(src + b);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t b = b0 + (int64_t)(r + i) * (kApThreads * 16);
+      if (b < run) {          // the keys are read again by the next score pass, the values not before the compaction
+        if (isV) store_streaming(dst + b, v[i]);
+        else     *reinterpret_cast<uint4*>(dst + b) = v[i];
+      }
+    }
+  }
+  if (novelty != nullptr && !isV && seg == 0 && (nov_per_head || (ui.l == 0 && ui.h == 0))) {
+    float* nd = novelty + nov_offset(D, ui) + D.n;
+    const float* ns = nov_new + (int64_t)ui.b * count;
+    for (int j = threadIdx.x; j < count; j += kApThreads) nd[j] = ns[j];
+  }
+}
+
 template <int ROWB>
 __global__ __launch_bounds__(kCpThreads) void compact_rows_kernel(Dims D, const char* Ksrc, const char* Vsrc,
                                                                   const int32_t* __restrict__ keep_idx, char* Kdst,
@@ -309,6 +351,16 @@ void launch_rope_rows(const Dims& D, const void* K, const float* rope_cos, const
   else if (rowb == 256) CCD_LAUNCH(256, false);
   else CCD_LAUNCH(512, false);
 #undef CCD_LAUNCH
+}
+
+void launch_append(const Dims& D, int count, void* K, void* V, const void* K_new, const void* V_new, float* novelty,
+                   const float* novelty_new, bool nov_per_head, hipStream_t s) {
+  const int esz = D.dtype == 0 ? 4 : 2;
+  const int64_t run = (int64_t)count * D.d * esz;
+  const int segs = (int)((run + kApSegBytes - 1) / kApSegBytes);
+  dim3 grid((unsigned)(D.units * 2 * segs)), block(kApThreads);
+  launch(append_rows_kernel, grid, block, s, D, esz, count, segs, (char*)K, (char*)V, (const char*)K_new,
+         (const char*)V_new, novelty, novelty_new, nov_per_head ? 1 : 0);
 }
 
 void launch_compact(const Dims& D, const void* Ksrc, const void* Vsrc, const int32_t* keep_idx, void* Kdst, void* Vdst,

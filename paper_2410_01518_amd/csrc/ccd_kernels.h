@@ -100,6 +100,10 @@ void launch_nuc_from_logits(const void* logits, const int32_t* labels, float* no
                             int64_t row_stride_elems, int dtype, hipStream_t s);
 int select_max_tokens();   // largest n the selection kernel handles
 
+// rows [D.n, D.n + count) of every unit of K and V <- the chunk's rows (K_new, V_new dense [units, count, d]); novelty
+// (nullable) likewise from novelty_new [B, count], into every head when it is carried per head
+void launch_append(const Dims& D, int count, void* K, void* V, const void* K_new, const void* V_new, float* novelty,
+                   const float* novelty_new, bool nov_per_head, hipStream_t s);
 void launch_compact(const Dims& D, const void* Ksrc, const void* Vsrc, const int32_t* keep_idx,
                     void* Kdst, void* Vdst, float* novelty, hipStream_t s);
 

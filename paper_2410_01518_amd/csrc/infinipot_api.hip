@@ -399,6 +399,33 @@ int ccd_compact(const ccd_shape_t* shape, const void* K_src, const void* V_src, 
   return launch_status();
 }
 
+int ccd_append(const ccd_shape_t* shape, void* K, void* V, float* novelty, const void* K_new, const void* V_new,
+               const float* novelty_new, int32_t count, void* hip_stream) {
+  if (shape == nullptr) return CCD_EINVAL;
+  if (shape->B < 1 || shape->L < 1 || shape->Hkv < 1) return CCD_EINVAL;
+  if ((int64_t)shape->B * shape->L * shape->Hkv > (int64_t)1 << 24) return CCD_EINVAL;
+  if (shape->n_valid < 0 || shape->n_cap < 1 || count < 0 || (int64_t)shape->n_valid + count > shape->n_cap) return CCD_EINVAL;
+  if (shape->dtype != CCD_FP32 && shape->dtype != CCD_BF16) return CCD_EUNSUPPORTED;
+  if (shape->d != 64 && shape->d != 128) return CCD_EUNSUPPORTED;
+  const int64_t esz = shape->dtype == CCD_FP32 ? 4 : 2;
+  if (shape->kv_stride_h < (int64_t)shape->n_cap * shape->d || shape->kv_stride_l < 0 || shape->kv_stride_b < 0) return CCD_EINVAL;
+  if ((shape->kv_stride_b * esz) % 16 || (shape->kv_stride_l * esz) % 16 || (shape->kv_stride_h * esz) % 16) return CCD_EALIGN;
+  if (K == nullptr || V == nullptr) return CCD_EINVAL;
+  if (count == 0) return CCD_OK;                      // an empty chunk (its pointers may be null): nothing to do
+  if (K_new == nullptr || V_new == nullptr) return CCD_EINVAL;
+  if ((novelty == nullptr) != (novelty_new == nullptr)) return CCD_EINVAL;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(K_new) || !aligned16(V_new)) return CCD_EALIGN;
+  const bool per_head = shape->nov_stride_l != 0 || shape->nov_stride_h != 0;
+  if (novelty != nullptr) {
+    if (shape->nov_stride_b < 0 || shape->nov_stride_l < 0 || shape->nov_stride_h < 0) return CCD_EINVAL;
+    if (per_head && shape->nov_stride_h < shape->n_cap) return CCD_EINVAL;
+    if (!per_head && shape->B > 1 && shape->nov_stride_b < (int64_t)shape->n_valid + count) return CCD_EINVAL;
+  }
+  const Dims D = make_dims(shape);
+  launch_append(D, count, K, V, K_new, V_new, novelty, novelty_new, per_head, static_cast<hipStream_t>(hip_stream));
+  return launch_status();
+}
+
 // ccd_compress, optionally with CR-RoPE of the kept keys on the side (K_rot != nullptr), other keys to attend to
 // (K_score != nullptr) and the CaP tokens' own keys in the softmax (K_cap != nullptr)
 static int compress_impl(const ccd_shape_t* shape, const void* Q_cat, void* K, void* V, float* novelty, float* scores_opt,

@@ -22,7 +22,7 @@ CCD_FP32, CCD_BF16 = 0, 1
 CCD_POOL_NONE, CCD_POOL_MAX, CCD_POOL_AVG = 0, 1, 2
 CCD_PATH_AUTO, CCD_PATH_VALU, CCD_PATH_MFMA_SLICES, CCD_PATH_MFMA_UNIT = 0, 1, 2, 3
 
-EXPORTS = ("ccd_workspace_bytes", "ccd_score", "ccd_select", "ccd_compact", "ccd_compress", "ccd_cr_rope",
+EXPORTS = ("ccd_workspace_bytes", "ccd_score", "ccd_select", "ccd_compact", "ccd_compress", "ccd_append", "ccd_cr_rope",
            "ccd_compress_rope", "ccd_score_kcat", "ccd_compress_kcat", "ccd_score_lse", "ccd_compress_lse",
            "ccd_nuc_from_logits", "ccd_compress_noalloc", "ccd_profile_enable", "ccd_profile_stages", "ccd_profile_stage_name",
            "ccd_profile_collect", "ccd_strerror")
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.ccd_compact.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
         L.ccd_compress.restype = ctypes.c_int
         L.ccd_compress.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.ccd_append.restype = ctypes.c_int
+        L.ccd_append.argtypes = [sp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp]
         L.ccd_compress_noalloc.restype = ctypes.c_int
         L.ccd_compress_noalloc.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
         L.ccd_cr_rope.restype = ctypes.c_int
@@ -171,6 +173,14 @@ def ccd_score(shape, Q_cat, K, novelty, scores, workspace, stream=None) -> int:
 
 def ccd_select(shape, scores, keep_idx, stream=None) -> int:
     return _check(lib().ccd_select(ctypes.byref(shape), _ptr(scores), _ptr(keep_idx), _stream(stream)))
+
+
+def ccd_append(shape, K, V, novelty, K_new, V_new, novelty_new, stream=None) -> int:
+    """Rows shape.n_valid .. + count - 1 of every unit of K, V (and novelty) <- the chunk K_new, V_new [B,L,Hkv,count,d]
+    (dense) and novelty_new [B,count]; the caller raises n_valid afterwards."""
+    assert K_new.is_contiguous() and V_new.is_contiguous() and (novelty_new is None or novelty_new.is_contiguous())
+    return _check(lib().ccd_append(ctypes.byref(shape), _ptr(K), _ptr(V), _ptr(novelty), _ptr(K_new), _ptr(V_new),
+                                   _ptr(novelty_new), int(K_new.shape[3]), _stream(stream)))
 
 
 def ccd_compact(shape, K_src, V_src, keep_idx, K_dst, V_dst, novelty_inout=None, stream=None) -> int:

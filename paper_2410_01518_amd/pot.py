@@ -5,8 +5,8 @@ full; then the catalyst-prompt queries of that moment score the cache and ccd_co
 head in place, after which appending continues behind them.  Novelty is carried per head, because after
 the first distillation heads no longer hold the same tokens in the same slots (Sec. 3.3.1).
 
-Only buffer bookkeeping happens here; scoring, selection and compaction all run in the library's kernels.
-Appending is a plain device copy, standing in for the model forward that would write new keys and values.
+Only buffer bookkeeping happens here; appending, scoring, selection and compaction all run in the library's kernels
+(the append stands in for the model forward that would write new keys and values).
 """
 from __future__ import annotations
 
@@ -36,10 +36,9 @@ class MemoryPot:
         """K_new, V_new [B, L, Hkv, m, d]; novelty_new [B, m] (one value per token, copied to every head)."""
         m = K_new.shape[3]
         assert m <= self.room, "pot overflow: distill first"
-        s = slice(self.n_valid, self.n_valid + m)
-        self.K[:, :, :, s].copy_(K_new)
-        self.V[:, :, :, s].copy_(V_new)
-        self.novelty[:, :, :, s].copy_(novelty_new[:, None, None, :].expand(self.B, self.L, self.Hkv, m))
+        shape = ip.make_shape(None, self.K, self.novelty, k=1, n_valid=self.n_valid)
+        rc = ip.ccd_append(shape, self.K, self.V, self.novelty, K_new, V_new, novelty_new)
+        assert rc == ip.CCD_OK, rc
         self.n_valid += m
 
     def distill(self, Q_cat, scores=None) -> int:

@@ -233,3 +233,26 @@ def test_nuc_from_logits_argument_errors_are_decided_on_the_host():
     assert nuc(dtype=5) == ip.CCD_EUNSUPPORTED
     assert nuc(logits=P + 2) == ip.CCD_EALIGN and nuc(V=1001, stride=1001) == ip.CCD_EALIGN     # rows 2002 bytes apart
     assert nuc(rows=0) == ip.CCD_OK                                                             # nothing launched
+
+
+def test_append_argument_errors_are_decided_on_the_host():
+    L = ip.lib()
+    P2, P3, P4 = P + 0x100000, P + 0x200000, P + 0x300000
+
+    def append(s, K=P, V=P2, nov=None, Kn=P3, Vn=P4, nn=None, count=10):
+        return L.ccd_append(None if s is None else ctypes.byref(s), K, V, nov, Kn, Vn, nn, count, None)
+
+    s = _shape(n_valid=100, n_cap=512)
+    assert append(None) == ip.CCD_EINVAL
+    assert append(s, K=None) == ip.CCD_EINVAL and append(s, Vn=None) == ip.CCD_EINVAL
+    assert append(s, count=-1) == ip.CCD_EINVAL
+    assert append(s, count=413) == ip.CCD_EINVAL                      # 100 + 413 > 512: the chunk does not fit
+    assert append(s, count=0) == ip.CCD_OK and append(s, Kn=None, Vn=None, count=0) == ip.CCD_OK   # nothing to do, nothing launched
+    assert append(s, nov=P, nn=None) == ip.CCD_EINVAL and append(s, nov=None, nn=P) == ip.CCD_EINVAL   # both or neither
+    assert append(s, K=P + 2) == ip.CCD_EALIGN and append(s, Kn=P3 + 4) == ip.CCD_EALIGN
+    assert append(_shape(n_valid=100, n_cap=512, d=96)) == ip.CCD_EUNSUPPORTED
+    assert append(_shape(n_valid=100, n_cap=512, dtype=5)) == ip.CCD_EUNSUPPORTED
+    assert append(_shape(n_valid=100, n_cap=512, kv_stride_h=100)) == ip.CCD_EINVAL
+    assert append(_shape(n_valid=-1, n_cap=512)) == ip.CCD_EINVAL
+    per_head = _shape(n_valid=100, n_cap=512, nov_stride_b=2 * 2 * 512, nov_stride_l=2 * 512, nov_stride_h=100)
+    assert append(per_head, nov=P, nn=P2 + 64) == ip.CCD_EINVAL        # a head's novelty row shorter than the pot

@@ -155,6 +155,27 @@ def test_compact_matches_index_select():
 
 # ---------------------------------------------------------------- selection rules and ties
 
+def test_append_puts_the_chunk_behind_the_cached_tokens():
+    """Hand example: a pot of 5 slots with 2 cached tokens takes a chunk of 2; torch's slice assignment as witness;
+    novelty of a token goes to every head; a chunk that does not fit is refused."""
+    pot = np.arange(2 * 1 * 2 * 5 * 3, dtype=np.float32).reshape(2, 1, 2, 5, 3)
+    chunk = -np.arange(2 * 1 * 2 * 2 * 3, dtype=np.float32).reshape(2, 1, 2, 2, 3) - 1.0
+    got = O.append(pot, 2, chunk)
+    assert got[1, 0, 1, 2].tolist() == chunk[1, 0, 1, 0].tolist() == [-19.0, -20.0, -21.0]      # first new row of the last unit
+    assert got[1, 0, 1, 3].tolist() == [-22.0, -23.0, -24.0]
+    assert np.array_equal(got[..., :2, :], pot[..., :2, :]) and np.array_equal(got[..., 4:, :], pot[..., 4:, :])
+    want = torch.from_numpy(pot.copy())
+    want[:, :, :, 2:4] = torch.from_numpy(chunk)
+    assert np.array_equal(got, want.numpy())
+    assert np.array_equal(pot, np.arange(60, dtype=np.float32).reshape(2, 1, 2, 5, 3))         # the input is not modified
+    nov = np.zeros((2, 1, 2, 5), dtype=np.float32)
+    got_n = O.append(nov, 3, np.array([[1.0, 2.0], [3.0, 4.0]], dtype=np.float32)[:, None, None, :])
+    assert got_n[0, 0, 0].tolist() == got_n[0, 0, 1].tolist() == [0, 0, 0, 1, 2] and got_n[1, 0, 1].tolist() == [0, 0, 0, 3, 4]
+    assert np.array_equal(O.append(nov[:, 0, 0], 0, np.ones((2, 5), np.float32)), np.ones((2, 5), np.float32))   # shared [B, n]
+    with pytest.raises(ValueError):
+        O.append(pot, 4, chunk)
+
+
 def test_select_tie_break_and_order():
     s = np.array([1, 3, 3, 2, 3, 1, 3], dtype=np.float32)
     assert O.select(s, 1).tolist() == [1]
