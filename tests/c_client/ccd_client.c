@@ -1,7 +1,8 @@
 /* A client of libinfinipot written against the C header alone: no Python, no torch.  It fills a small pot with
  * pseudo-random bf16 data, calls ccd_compress through the C ABI and checks on the host what can be checked without
  * an oracle: the return codes, k strictly ascending indices per unit, every NuC slot kept, and K', V' being bit copies
- * of the rows the indices name.  Prints "ccd_client ok" and exits 0 on success. */
+ * of the rows the indices name; then it fills the pot up again with ccd_append and checks the rows.  Prints
+ * "ccd_client ok" and exits 0 on success. */
 #include <hip/hip_runtime_api.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -113,6 +114,42 @@ int main(void) {
     }
     if (nuc_kept != T) { fprintf(stderr, "unit %d keeps %d of the %d NuC slots\n", u, nuc_kept, T); return 1; }
   }
-  printf("ccd_client ok: %d units, %d -> %d tokens\n", B * L * HKV, N, K_KEEP);
+  /* the pot is filled up again behind the kept tokens (Sec. 3.2): N - K_KEEP new rows per unit */
+  enum { M = N - K_KEEP };
+  const size_t chunk_elems = (size_t)B * L * HKV * M * D;
+  uint16_t* cK = malloc(chunk_elems * 2);
+  uint16_t* cV = malloc(chunk_elems * 2);
+  if (!cK || !cV) return 2;
+  for (size_t i = 0; i < chunk_elems; ++i) { cK[i] = next_bf16(); cV[i] = next_bf16(); }
+  void *dcK, *dcV;
+  CHECK_HIP(hipMalloc(&dcK, chunk_elems * 2));
+  CHECK_HIP(hipMalloc(&dcV, chunk_elems * 2));
+  CHECK_HIP(hipMemcpy(dcK, cK, chunk_elems * 2, hipMemcpyHostToDevice));
+  CHECK_HIP(hipMemcpy(dcV, cV, chunk_elems * 2, hipMemcpyHostToDevice));
+  ccd_shape_t after = s;
+  after.n_valid = K_KEEP;
+  rc = ccd_append(&after, dK, dV, NULL, dcK, dcV, NULL, M + 1, NULL);
+  if (rc != CCD_EINVAL) { fprintf(stderr, "a chunk that does not fit: expected CCD_EINVAL, got %d\n", rc); return 1; }
+  rc = ccd_append(&after, dK, dV, NULL, dcK, dcV, NULL, M, NULL);
+  if (rc != CCD_OK) { fprintf(stderr, "ccd_append: %d (%s)\n", rc, ccd_strerror(rc)); return 1; }
+  CHECK_HIP(hipDeviceSynchronize());
+  uint16_t* aK = malloc(kv_elems * 2);
+  uint16_t* aV = malloc(kv_elems * 2);
+  if (!aK || !aV) return 2;
+  CHECK_HIP(hipMemcpy(aK, dK, kv_elems * 2, hipMemcpyDeviceToHost));
+  CHECK_HIP(hipMemcpy(aV, dV, kv_elems * 2, hipMemcpyDeviceToHost));
+  for (int u = 0; u < B * L * HKV; ++u) {
+    const size_t head = (size_t)u * N * D, kept = (size_t)K_KEEP * D, fresh = (size_t)M * D;
+    if (memcmp(aK + head, oK + head, kept * 2) != 0 || memcmp(aV + head, oV + head, kept * 2) != 0) {
+      fprintf(stderr, "unit %d: the append touched the kept rows\n", u);
+      return 1;
+    }
+    if (memcmp(aK + head + kept, cK + (size_t)u * fresh, fresh * 2) != 0 ||
+        memcmp(aV + head + kept, cV + (size_t)u * fresh, fresh * 2) != 0) {
+      fprintf(stderr, "unit %d: the appended rows are not bit copies of the chunk\n", u);
+      return 1;
+    }
+  }
+  printf("ccd_client ok: %d units, %d -> %d tokens, %d appended\n", B * L * HKV, N, K_KEEP, M);
   return 0;
 }
