@@ -163,15 +163,16 @@ ScorePlan plan_score(const Dims& D, bool cap_keys) {
   pl.head_block = 0;
   pl.lse_given = 0;
   // fp32 caches: the unit kernel (fp32 values as sums of bf16 products on the matrix cores) where it exists - head
-  // dimension 64, plain softmax over the cached tokens - when asked for, or by itself when the units fill the chip
-  // and a sweep of 256 query rows is not mostly padding (the vector-ALU kernels cost in proportion to G * P)
+  // dimension 64, plain softmax over the cached tokens - when asked for, and by itself unless a few units with long
+  // rows would leave most of the chip idle under it (a workgroup takes about 27 us per 1000 tokens and sweep of 256
+  // query rows; measured faster than the vector-ALU kernels from 4 units of 512 tokens to 256 units of 4096)
   if (D.dtype == CCD_FP32 && score_unit_supported(D) && !cap_keys && D.window == 0) {
     if (D.score_path == CCD_PATH_MFMA_UNIT) {
       pl.unit_kernel = 1;
     } else if (D.score_path == CCD_PATH_AUTO) {
       const int cus = compute_units();
-      const int rounds = (D.units_run + cus - 1) / cus;
-      pl.unit_kernel = (D.GP >= 32 && 4 * D.units_run >= 3 * rounds * cus) ? 1 : 0;
+      const int64_t rounds = (D.units_run + cus - 1) / cus, sweeps = (D.GP + 255) / 256;
+      pl.unit_kernel = (2 * D.units_run >= cus || rounds * sweeps * D.n <= 6000) ? 1 : 0;
     }
   }
   return pl;

@@ -114,11 +114,9 @@ SCORE_PATHS = [ip.CCD_PATH_VALU, ip.CCD_PATH_MFMA_SLICES, ip.CCD_PATH_MFMA_UNIT]
 
 
 def _path_for(cfg, score_path):
-    """fp32 caches: the vector ALUs (under the automatic choice), and the matrix-core unit kernel for head dimension 64."""
+    """fp32 caches: the vector ALUs, and the matrix-core unit kernel for head dimension 64."""
     if cfg.dtype == "fp32":
-        if score_path == ip.CCD_PATH_VALU:
-            return ip.CCD_PATH_AUTO
-        if score_path == ip.CCD_PATH_MFMA_UNIT and cfg.d == 64:
+        if score_path == ip.CCD_PATH_VALU or (score_path == ip.CCD_PATH_MFMA_UNIT and cfg.d == 64):
             return score_path
         pytest.skip("fp32 caches: no such path")
     return score_path
