@@ -132,14 +132,16 @@ static ScorePlan plan_mfma(const Dims& D) {
   pl.cap_block = 0;
   pl.head_block = 0;
   pl.lse_given = 0;
-  // One workgroup per unit (both passes in one kernel) when the units fill the chip round by round and a sweep of 256
-  // query rows is mostly real rows; the slice kernels otherwise (few units: they cut a unit into token slices).
+  // One workgroup per unit (both passes in one kernel) when the units fill at least three fifths of the chip round by
+  // round; the slice kernels otherwise (few units: they cut a unit into token slices).  Measured on the headline shape
+  // with 128 / 192 / 256 / 320 units: 180 / 223 / 220 / 393 us per call against 147 / 246 / 233 / 412 us, and with
+  // 8 to 32 query rows per unit (both kernels pad a sweep to 256 rows) the unit kernel is 3 - 7 % ahead as well.
   if (D.score_path == CCD_PATH_MFMA_UNIT) {
     pl.unit_kernel = 1;
   } else if (D.score_path == CCD_PATH_AUTO && score_unit_supported(D)) {
     const int cus = compute_units();
     const int rounds = (D.units_run + cus - 1) / cus;
-    pl.unit_kernel = (D.GP > 128 && 4 * D.units_run >= 3 * rounds * cus) ? 1 : 0;
+    pl.unit_kernel = (5 * (int64_t)D.units_run >= 3 * (int64_t)rounds * cus) ? 1 : 0;
   }
   return pl;
 }
