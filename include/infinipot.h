@@ -79,9 +79,9 @@ typedef struct {
                               /* cores, a workgroup per token slice; CCD_PATH_MFMA_UNIT matrix cores, a          */
                               /* workgroup per unit.  All give the same scores up to fp32 rounding order.        */
                               /* fp32 caches on CCD_PATH_MFMA_UNIT: every fp32 value enters as the sum of two    */
-                              /* bf16 values and a product as three bf16 products (logits good to about 2^-16    */
-                              /* of sum |q k|); d = 64 only, no window, no K_cap (CCD_EUNSUPPORTED otherwise;    */
-                              /* CCD_PATH_AUTO then takes the vector ALUs).                                      */
+                              /* bf16 values and a product as three bf16 products (scores within 1e-3 for        */
+                              /* logits up to about 140, measured; 4e-4 at 65); d = 64 only, no window, no K_cap  */
+                              /* (CCD_EUNSUPPORTED otherwise; CCD_PATH_AUTO then takes the vector ALUs).          */
   int64_t kv_stride_b, kv_stride_l, kv_stride_h;    /* K, V: [B, L, Hkv, n_cap, d], strides in elements */
   int64_t q_stride_b, q_stride_l, q_stride_h;       /* Q_cat: [B, L, Hq, P, d]                          */
   int64_t nov_stride_b, nov_stride_l, nov_stride_h; /* novelty fp32: [B, n] shared by layers and heads  */

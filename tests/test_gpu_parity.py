@@ -453,6 +453,20 @@ def test_logits_far_above_those_of_the_first_tile(where):
     gu.assert_scores_close(gu.to_host(scores), ref["scores"], cfg.G * cfg.P)
 
 
+@pytest.mark.parametrize("gain", [2.0, 4.0])
+def test_fp32_cache_on_the_matrix_cores_keeps_the_bound_as_logits_grow(gain):
+    """Q and K of N(0,1) scaled by `gain`: the largest log2-domain logits reach about 23 and 93; the scores of the
+    hi/lo form stay within the 1e-3 bound (measured: 6e-5 and 4e-4)."""
+    cfg = _cfg(dtype="fp32", d=64, B=1, L=2, Hq=8, Hkv=2, N=1500, k=500, P=16, T=0, w=1, seed=5)
+    print(f"fp32 on the matrix cores, gain {gain} {cfg}", flush=True)
+    inp = synth.make_inputs(cfg)
+    inp["Q_cat"], inp["K"] = inp["Q_cat"] * np.float32(gain), inp["K"] * np.float32(gain)
+    ref = _oracle(cfg, inp)
+    rc, dev, scores, keep = _run_fused(cfg, inp, score_path=ip.CCD_PATH_MFMA_UNIT)
+    assert rc == ip.CCD_OK
+    _check_fused(cfg, inp, ref, dev, scores, keep, False)
+
+
 @pytest.mark.parametrize("where", ["late_tokens", "tail_tile"])
 def test_logits_far_above_those_of_the_first_tile_fp32_on_the_matrix_cores(where):
     """The same redo of a wave's tokens on the fp32 form of the unit kernel.  Logits that overflow a sum are more than 127
