@@ -43,8 +43,8 @@ namespace ccd {
 
 namespace {
 
-constexpr int kUPairs = 4;                    // pairs of 32-query blocks per sweep
-constexpr int kUQ = kUPairs * kQB * 32;       // query rows per sweep: 256
+constexpr int kUPairs = 4;                    // pairs of 32-query blocks per sweep, at most (a kernel is built for 1, 2 and 4)
+constexpr int kUQ = kUPairs * kQB * 32;       // query rows per sweep, at most: 256
 constexpr int kUBlock = 128;                  // tiles of a wave between two write-outs of its token sums (pass 2)
 static_assert(kQB == 2, "a step covers two query blocks");
 
@@ -64,7 +64,7 @@ struct UnitShape {
   static constexpr int NM = kQB * NMQ;                  // ... per step (a pair of blocks)
   static constexpr int NCH = NM < 16 ? NM : 16;         // chunks the ALU work of a step is cut into
   static constexpr int EPC = 32 / NCH;                  // accumulator elements per chunk
-  static_assert(kUPairs * kQB * KF * 4 <= 256, "the query fragments of a sweep fill the accumulation registers");
+  static_assert(kUPairs * kQB * KF * 4 <= 256, "the query fragments of the widest sweep fill the accumulation registers");
   // matrix instruction j (0 .. NMQ - 1) of a block: which K fragment meets which query fragment
   static constexpr int kfrag(int j) { return !F32 ? j : (j < 2 * KQ ? j % KQ : KQ + j % KQ); }
   static constexpr int qfrag(int j) { return !F32 ? j : (j < KQ ? j : (j < 2 * KQ ? j : j - 2 * KQ)); }
@@ -246,7 +246,9 @@ __device__ __forceinline__ void load_neg_lse(float (&nl)[16], uint32_t lane_base
 }
 
 // ET: element type of the caches in memory (uint16_t: bf16 bits; float: fp32, split on the fly)
-template <int HD, class ET>
+// NP: pairs of 32-query blocks per sweep (1, 2 or 4: sweeps of 64, 128 or 256 query rows; units with few query rows
+//     take the narrowest that holds them and spend one or two steps per tile instead of four)
+template <int HD, class ET, int NP>
 __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl, const ET* __restrict__ Q,
                                                             const ET* __restrict__ K,
                                                             const float2* __restrict__ part, float* __restrict__ u,
@@ -257,6 +259,8 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
   constexpr int KF = SH::KF;           // fragments of a K tile / of a block of query rows
   constexpr int NCH = SH::NCH;         // ALU chunks per step
   constexpr int EPC = SH::EPC;         // accumulator elements per chunk
+  constexpr int UQ = NP * kQB * 32;    // query rows per sweep
+  static_assert(NP == 1 || NP == 2 || NP == 4, "steps per tile");
   __shared__ UnitLds<HD> sm;
   const int unit = D.unit0 + blockIdx.x;
   const UnitIdx ui = decode_unit(D, unit);
@@ -279,13 +283,13 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
   float* uu = u + (int64_t)unit * D.n;
   claim_acc_registers();
 
-  for (int qc = 0; qc < D.GP; qc += kUQ) {
+  for (int qc = 0; qc < D.GP; qc += UQ) {
     // Fragments of the sweep's query rows into the accumulation registers: all 8 KS loads of a lane are in flight at
     // once, together with the first K tiles requested further down.  Rows past G * P (last sweep only) stay zero.
-    if (qc + kUQ > D.GP) {
-      static_for<0, kUPairs * kQB * KF>([&](auto Fc) { zero_q_frag<decltype(Fc)::value>(); });
+    if (qc + UQ > D.GP) {
+      static_for<0, NP * kQB * KF>([&](auto Fc) { zero_q_frag<decltype(Fc)::value>(); });
     }
-    static_for<0, kUPairs * kQB>([&](auto Bc) {
+    static_for<0, NP * kQB>([&](auto Bc) {
       constexpr int blk = decltype(Bc)::value;
       const int q = qc + blk * 32 + col;
       if (q < D.GP) {
@@ -330,12 +334,12 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
     if (!pl.lse_given) {
       // ---------------- pass 1 ----------------
       // per (pair, block): -reference * c and the sum in two partial chains
-      float nm[kUPairs][kQB], Z[kUPairs][kQB][2];
+      float nm[NP][kQB], Z[NP][kQB][2];
 #pragma unroll
-      for (int p = 0; p < kUPairs; ++p)
+      for (int p = 0; p < NP; ++p)
 #pragma unroll
         for (int qb = 0; qb < kQB; ++qb) { nm[p][qb] = -kNegHuge * c; Z[p][qb][0] = 0.f; Z[p][qb][1] = 0.f; }
-      float m_ref[kUPairs][kQB], Zs[kUPairs][kQB];       // (reference, sum) pairs once the sweep is done
+      float m_ref[NP][kQB], Zs[NP][kQB];       // (reference, sum) pairs once the sweep is done
       // chunk j of the fold of pair P: elements j EPC .. + EPC - 1 of the 32 accumulator registers
 #define CCD_FOLD1(CUR, P)                                                                 \
       [&](int j) {                                                                        \
@@ -364,7 +368,7 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
         }
         q_frags_arrived();
         // the wave's first tile fixes the references and is folded without overlap
-        static_for<0, kUPairs>([&](auto Pc) {
+        static_for<0, NP>([&](auto Pc) {
           constexpr int p = decltype(Pc)::value;
           logits_now<SH, 1, p>(accA, a[0]);
 #pragma unroll
@@ -380,36 +384,50 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
         CCD_NEXT_TILE(0, min(s0 + 2, s1 - 1), min(s0 + 3, s1 - 1))
         int s = s0 + 1;
         logits_now<SH, 1, 0>(accA, a[1]);
-        // Tile s: accA holds the logits of (s, pair 0).  Steps 1 - 3 take pairs 1 - 3 of tile s from buffer CB, the
-        // last step pair 0 of tile s + 1 from buffer NB; every step folds the pair computed by the step before.  The
-        // buffer of tile s is free after step 3 and takes tile s + 2.
-#define CCD_P1_TILE(CB, NB)                                                                       \
-        pipelined_step<SH, 1, 1>(accB, a[CB], CCD_FOLD1(accA, 0));                            \
-        pipelined_step<SH, 1, 2>(accA, a[CB], CCD_FOLD1(accB, 1));                            \
-        pipelined_step<SH, 1, 3>(accB, a[CB], CCD_FOLD1(accA, 2));                            \
+        // Tile s: X holds the logits of (s, pair 0).  The steps take the other pairs of tile s from buffer CB and, last,
+        // pair 0 of tile s + 1 from buffer NB; every step folds the pair computed by the step before.  The buffer of
+        // tile s is free before the last step and takes tile s + 2.  With four or two pairs the logits of the next
+        // tile end up in X again, with one pair in Y: there the two tiles of the loop body swap the accumulators.
+#define CCD_P1_TILE(CB, NB, X, Y)                                                                 \
+        if constexpr (NP == 4) {                                                                  \
+          pipelined_step<SH, 1, 1>(Y, a[CB], CCD_FOLD1(X, 0));                                    \
+          pipelined_step<SH, 1, 2>(X, a[CB], CCD_FOLD1(Y, 1));                                    \
+          pipelined_step<SH, 1, 3>(Y, a[CB], CCD_FOLD1(X, 2));                                    \
+        } else if constexpr (NP == 2) {                                                           \
+          pipelined_step<SH, 1, 1>(Y, a[CB], CCD_FOLD1(X, 0));                                    \
+        }                                                                                         \
         /* (always: a load under a condition would make every wait for K fragments a wait for all loads) */ \
         CCD_NEXT_TILE(CB, min(s + 2, s1 - 1), min(s + 3, s1 - 1))                                 \
-        pipelined_step<SH, 1, 0>(accA, a[NB], CCD_FOLD1(accB, 3));
+        if constexpr (NP == 1) {                                                                  \
+          pipelined_step<SH, 1, 0>(Y, a[NB], CCD_FOLD1(X, 0));                                    \
+        } else {                                                                                  \
+          pipelined_step<SH, 1, 0>(X, a[NB], CCD_FOLD1(Y, NP - 1));                               \
+        }
         // (No branch inside a tile and none between the two tiles of the loop body: with straight-line code the
         // compiler can tell how many loads are in flight at every wait.  Behind the wave's last tile the last step
         // computes the logits of that tile's first pair once more; nobody reads them.)
         while (s + 1 < s1) {
-          CCD_P1_TILE(1, 0)
+          CCD_P1_TILE(1, 0, accA, accB)
           ++s;
-          CCD_P1_TILE(0, 1)
+          if constexpr (NP == 1) {
+            CCD_P1_TILE(0, 1, accB, accA)
+          } else {
+            CCD_P1_TILE(0, 1, accA, accB)
+          }
           ++s;
         }
         if (s < s1) {
-          CCD_P1_TILE(1, 0)
+          CCD_P1_TILE(1, 0, accA, accB)
         }
         mma_results_ready(accA);      // the surplus logits are in flight until here
+        mma_results_ready(accB);
 #undef CCD_P1_TILE
 #undef CCD_FOLD1
         // Did a sum leave the fp32 range (or meet a NaN)?  Then this wave redoes its tokens with a running maximum.
         bool bad = false;
         const float inv_c = 1.0f / c;
 #pragma unroll
-        for (int p = 0; p < kUPairs; ++p)
+        for (int p = 0; p < NP; ++p)
 #pragma unroll
           for (int qb = 0; qb < kQB; ++qb) {
             Zs[p][qb] = Z[p][qb][0] + Z[p][qb][1];
@@ -418,12 +436,12 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
           }
         if (__any(bad)) {
 #pragma unroll
-          for (int p = 0; p < kUPairs; ++p)
+          for (int p = 0; p < NP; ++p)
 #pragma unroll
             for (int qb = 0; qb < kQB; ++qb) { m_ref[p][qb] = kNegHuge; Zs[p][qb] = 0.f; }
           for (int t = s0; t < s1; ++t) {
             CCD_TILE_NOW(0, t)
-            static_for<0, kUPairs>([&](auto Pc) {
+            static_for<0, NP>([&](auto Pc) {
               constexpr int p = decltype(Pc)::value;
               logits_now<SH, 1, p>(accA, a[0]);
               fold_stats<false>(accA, m_ref[p], Zs[p], c, half, kStep);
@@ -433,7 +451,7 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
           // move each reference to where its sum is of order one (Z = mant * 2^e -> reference + e / c): the ragged
           // tile and the merges expect the magnitudes of a (maximum, sum) pair
 #pragma unroll
-          for (int p = 0; p < kUPairs; ++p)
+          for (int p = 0; p < NP; ++p)
 #pragma unroll
             for (int qb = 0; qb < kQB; ++qb) {
               const int e = __builtin_amdgcn_frexp_expf(Zs[p][qb]);
@@ -444,14 +462,14 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
         }
       } else {
 #pragma unroll
-        for (int p = 0; p < kUPairs; ++p)
+        for (int p = 0; p < NP; ++p)
 #pragma unroll
           for (int qb = 0; qb < kQB; ++qb) { m_ref[p][qb] = kNegHuge; Zs[p][qb] = 0.f; }
       }
       if (ragged && wave == 3) {
         CCD_TILE_NOW(0, full)
         q_frags_arrived();
-        static_for<0, kUPairs>([&](auto Pc) {
+        static_for<0, NP>([&](auto Pc) {
           constexpr int p = decltype(Pc)::value;
           logits_now<SH, 1, p>(accA, a[0]);
           fold_stats<true>(accA, m_ref[p], Zs[p], c, half, n_main - full * kStep);
@@ -459,7 +477,7 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
       }
       // the two lane halves hold different token rows of the same query row: merge, lower half writes
 #pragma unroll
-      for (int p = 0; p < kUPairs; ++p)
+      for (int p = 0; p < NP; ++p)
 #pragma unroll
         for (int qb = 0; qb < kQB; ++qb) {
           const float m_o = __shfl_xor(m_ref[p][qb], 32), z_o = __shfl_xor(Zs[p][qb], 32);
@@ -473,7 +491,7 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
     {
       float2 cap = make_float2(kNegHuge, 0.f);     // the block of the CaP keys (causal variant), else nothing
       if constexpr (!F32) {          // (fp32 caches with CaP keys take the vector-ALU kernels: the host sees to that)
-        if (Kcap != nullptr) {
+        if (Kcap != nullptr && wave < NP) {
           const uint16_t* Kc = Kcap + (int64_t)unit * D.P * HD;
           // the thread's own query row is one of the 2 x 32 rows of block pair `wave`: their fragments once more, in
           // vector registers this time (the registers of pass 1 are free here)
@@ -484,10 +502,11 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
       }
       __syncthreads();
       const int q = qc + threadIdx.x;
+      const bool my_row = (int)threadIdx.x < UQ && q < D.GP;     // (threads past the sweep's rows have none)
       float lse = INFINITY;
       if (pl.lse_given) {            // the caller's normalisers (natural log): nothing to merge
-        if (q < D.GP) lse = lse_io[(int64_t)unit * D.GP + q] * 1.44269504088896340736f;
-      } else if (q < D.GP) {
+        if (my_row) lse = lse_io[(int64_t)unit * D.GP + q] * 1.44269504088896340736f;
+      } else if (my_row) {
         if (pl.head_block) {         // statistics of the windowed head, left there by its own kernel
           const float2 hd = part[extra_block_index(D, pl, unit, q)];
           const float Mh = fmaxf(cap.x, hd.x);
@@ -520,9 +539,9 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
       float us[2];
       uint32_t nl_base = (uint32_t)(uintptr_t)(LdsFloats)sm.neg_lse + 16 * half;
       // chunk j of the fold of a pair: 2^(x c - lse2) of EPC accumulator elements added to the token's sum; behind
-      // the last chunk of a block of query rows, the normalisers of that block of pair NP (the pair folded next) are
-      // requested
-#define CCD_FOLD2(CUR, NP)                                                                \
+      // the last chunk of a block of query rows, the normalisers of that block of pair NEXTP (the pair folded next) are
+      // requested (with a single pair they never change)
+#define CCD_FOLD2(CUR, NEXTP)                                                             \
       [&](int j) {                                                                        \
         float t[EPC];                                                                     \
         _Pragma("unroll") for (int i = 0; i < EPC; ++i) {                                 \
@@ -532,8 +551,8 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
         _Pragma("unroll") for (int i = 0; i < EPC; ++i) t[i] = fast_exp2(t[i]);           \
         _Pragma("unroll") for (int i = 0; i < EPC; ++i) us[i & 1] += t[i];                \
         asm volatile("" : "+v"(us[0]), "+v"(us[1]));     /* as in pass 1 */               \
-        if (j == NCH / 2 - 1) load_neg_lse(nl[0], nl_base, (NP) * kQB);                   \
-        if (j == NCH - 1) load_neg_lse(nl[1], nl_base, (NP) * kQB + 1);                   \
+        if (NP > 1 && j == NCH / 2 - 1) load_neg_lse(nl[0], nl_base, (NEXTP) * kQB);      \
+        if (NP > 1 && j == NCH - 1) load_neg_lse(nl[1], nl_base, (NEXTP) * kQB + 1);      \
       }
       int s = sb - 1;
       if constexpr (F32) {        // a[0] <- tile s, a[1] <- tile s - 1, tile s - 2 requested
@@ -550,31 +569,44 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
       load_neg_lse(nl[1], nl_base, 1);
       q_frags_arrived();
       logits_now<SH, 2, 0>(accA, a[0]);
-      // Tile s: accA holds the logits of (s, pair 0) and nl the normalisers of pair 0.  Same step structure as pass 1,
-      // walking down; the token's sum is complete after the fourth step.
-#define CCD_P2_TILE(CB, NB)                                                                          \
+      // Tile s: X holds the logits of (s, pair 0) and nl the normalisers of pair 0.  Same step structure as pass 1,
+      // walking down; the token's sum is complete after the last step.
+#define CCD_P2_TILE(CB, NB, X, Y)                                                                    \
       us[0] = 0.f; us[1] = 0.f;                                                                      \
       asm volatile("" : "+v"(nl_base));                                                              \
-      pipelined_step<SH, 2, 1>(accB, a[CB], CCD_FOLD2(accA, 1));                                     \
-      pipelined_step<SH, 2, 2>(accA, a[CB], CCD_FOLD2(accB, 2));                                     \
-      pipelined_step<SH, 2, 3>(accB, a[CB], CCD_FOLD2(accA, 3));                                     \
+      if constexpr (NP == 4) {                                                                       \
+        pipelined_step<SH, 2, 1>(Y, a[CB], CCD_FOLD2(X, 1));                                         \
+        pipelined_step<SH, 2, 2>(X, a[CB], CCD_FOLD2(Y, 2));                                         \
+        pipelined_step<SH, 2, 3>(Y, a[CB], CCD_FOLD2(X, 3));                                         \
+      } else if constexpr (NP == 2) {                                                                \
+        pipelined_step<SH, 2, 1>(Y, a[CB], CCD_FOLD2(X, 1));                                         \
+      }                                                                                              \
       CCD_NEXT_TILE(CB, max(s - 2, sa), max(s - 3, sa))                                              \
-      pipelined_step<SH, 2, 0>(accA, a[NB], CCD_FOLD2(accB, 0));                                     \
+      if constexpr (NP == 1) {                                                                       \
+        pipelined_step<SH, 2, 0>(Y, a[NB], CCD_FOLD2(X, 0));                                         \
+      } else {                                                                                       \
+        pipelined_step<SH, 2, 0>(X, a[NB], CCD_FOLD2(Y, 0));                                         \
+      }                                                                                              \
       {                                                                                              \
         float v = us[0] + us[1];                                                                     \
         v += __shfl_xor(v, 32);                                                                      \
         ub[(s - sa) * kStep + col] = v;      /* (both lane halves hold the same sum) */              \
       }
       while (s - 1 >= sa) {
-        CCD_P2_TILE(0, 1)
+        CCD_P2_TILE(0, 1, accA, accB)
         --s;
-        CCD_P2_TILE(1, 0)
+        if constexpr (NP == 1) {
+          CCD_P2_TILE(1, 0, accB, accA)
+        } else {
+          CCD_P2_TILE(1, 0, accA, accB)
+        }
         --s;
       }
       if (s >= sa) {
-        CCD_P2_TILE(0, 1)
+        CCD_P2_TILE(0, 1, accA, accB)
       }
       mma_results_ready(accA);        // the surplus logits are in flight until here
+      mma_results_ready(accB);
 #undef CCD_P2_TILE
 #undef CCD_FOLD2
       // the block's sums (this wave wrote them, this wave reads them)
@@ -594,18 +626,22 @@ __global__ __launch_bounds__(kMT, 1) void score_unit_kernel(Dims D, ScorePlan pl
 // CaP keys in the softmax nor a sliding window, whose side kernels exist for bf16 only: the caller checks those)
 bool score_unit_supported(const Dims& D) { return D.dtype == 1 ? (D.d == 64 || D.d == 128) : D.d == 64; }
 
+// the kernel for (head dimension, cache type, pairs of query blocks per sweep)
+template <int HD, class ET>
+static void launch_score_unit_as(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const void* K_cap,
+                                 const float2* part, float* u, float* lse_io, hipStream_t s) {
+  dim3 grid((unsigned)D.units_run), block(kMT);
+  const ET *q = (const ET*)Q, *k = (const ET*)K, *kc = (const ET*)K_cap;
+  if (D.GP <= 64)       launch((score_unit_kernel<HD, ET, 1>), grid, block, s, D, pl, q, k, part, u, kc, lse_io);
+  else if (D.GP <= 128) launch((score_unit_kernel<HD, ET, 2>), grid, block, s, D, pl, q, k, part, u, kc, lse_io);
+  else                  launch((score_unit_kernel<HD, ET, 4>), grid, block, s, D, pl, q, k, part, u, kc, lse_io);
+}
+
 void launch_score_unit(const Dims& D, const ScorePlan& pl, const void* Q, const void* K, const void* K_cap,
                        const float2* part, float* u, float* lse_io, hipStream_t s) {
-  dim3 grid((unsigned)D.units_run), block(kMT);
-  if (D.dtype == 0)
-    launch((score_unit_kernel<64, float>), grid, block, s, D, pl, (const float*)Q, (const float*)K, part, u,
-           (const float*)nullptr, lse_io);
-  else if (D.d == 64)
-    launch((score_unit_kernel<64, uint16_t>), grid, block, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part, u,
-           (const uint16_t*)K_cap, lse_io);
-  else
-    launch((score_unit_kernel<128, uint16_t>), grid, block, s, D, pl, (const uint16_t*)Q, (const uint16_t*)K, part, u,
-           (const uint16_t*)K_cap, lse_io);
+  if (D.dtype == 0)    launch_score_unit_as<64, float>(D, pl, Q, K, nullptr, part, u, lse_io, s);
+  else if (D.d == 64)  launch_score_unit_as<64, uint16_t>(D, pl, Q, K, K_cap, part, u, lse_io, s);
+  else                 launch_score_unit_as<128, uint16_t>(D, pl, Q, K, K_cap, part, u, lse_io, s);
 }
 
 }  // namespace ccd

@@ -147,6 +147,31 @@ def test_scores_and_staged_calls(case, pool_mode, score_path):
     np.testing.assert_array_equal(kh, gu.replay_select(sh, cfg.k))                # (C) replay on the GPU's scores
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp32", 64)])
+@pytest.mark.parametrize("G,P", [(1, 64), (1, 65), (4, 32), (3, 43), (4, 33), (2, 96), (8, 33)])
+def test_unit_kernel_sweep_widths(G, P, dtype, d):
+    """The unit score kernel is built for sweeps of 64, 128 and 256 query rows: G * P at and around the limits (64, 65,
+    128, 129, 132, 192) and beyond one sweep (264), with K_cap for bf16 (the CaP block is computed by the waves that
+    own query rows)."""
+    cfg = _cfg(dtype=dtype, d=d, B=1, L=2, Hq=2 * G, Hkv=2, P=P, N=777, k=300, T=50, w=3, seed=100 + G * P)
+    print(f"sweep widths G*P={G * P} {cfg}", flush=True)
+    inp = synth.make_inputs(cfg)
+    K_cap = synth.cap_keys(cfg) if dtype == "bf16" else None
+    ref = O.compress(inp["Q_cat"], inp["K"], inp["V"], inp["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w, K_cap=K_cap)
+    dev = _upload(inp)
+    shape = ip.make_shape(dev["Q_cat"], dev["K"], dev["novelty"], k=cfg.k, T=cfg.T, pool_w=cfg.w,
+                          score_path=ip.CCD_PATH_MFMA_UNIT)
+    ws = ip.alloc_workspace(shape)
+    scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.N), dtype=torch.float32, device="cuda")
+    if K_cap is not None:
+        rc = ip.ccd_score_kcat(shape, dev["Q_cat"], dev["K"], gu.to_dev(K_cap), dev["novelty"], scores, ws)
+    else:
+        rc = ip.ccd_score(shape, dev["Q_cat"], dev["K"], dev["novelty"], scores, ws)
+    assert rc == ip.CCD_OK
+    torch.cuda.synchronize()
+    gu.assert_scores_close(gu.to_host(scores), ref["scores"], cfg.G * cfg.P)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 @pytest.mark.parametrize("score_path", SCORE_PATHS)
 @pytest.mark.parametrize("N", [1, 2, 31, 32, 33, 97, 128, 129])
